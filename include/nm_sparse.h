@@ -1,0 +1,179 @@
+/*
+ * nm_sparse.h -- C ABI of the N:M-sparse linear layer for AMD MI355X (gfx950).
+ *
+ * The library implements the deployment primitive that layer-wise N:M sparsity for
+ * vision transformers assumes (Section 3, "Problem Formulation": an accelerator that
+ * supports several N:M levels, one level chosen per linear layer):
+ *
+ *   prune  -- Section 3.1, "Dynamic Masking", Eq. (1): in every group of M consecutive
+ *             weights keep the N of largest saliency; saliency = weight magnitude.
+ *   pack   -- Section 1 and Section 2 (Fig. 2, upper part): store the kept values and,
+ *             for each, a log2(M)-bit index of its position inside its group.
+ *   spmm   -- Section 2 (Fig. 2, lower part): decode the indices, select the matching
+ *             activations, multiply-accumulate; the result is the exact product with
+ *             the masked weight, with N/M of the dense multiply-accumulates.
+ *
+ * Conventions
+ *   W  [O, K]  weight, row-major, leading dimension ldw (elements); O = out features,
+ *              K = in features = reduction dimension.  Groups of M are aligned
+ *              (k in [g*M, g*M+M)) and run along K.
+ *   X  [T, K]  activations, row-major, leading dimension ldx.  T = tokens.
+ *   Y  [T, O]  Y = X * (W (.) mask)^T (+ bias), row-major, leading dimension ldy.
+ *   All weights and activations are bfloat16 carried as raw 16-bit patterns (nm_bf16);
+ *   products are accumulated in fp32.
+ *   Legal levels: M in {4, 8, 16}, 1 <= N <= M.  K must be a multiple of M.
+ *
+ * Selection rule (exactly N kept per group): order the members of a group by
+ * (magnitude descending, position ascending) and keep the first N.  Magnitude is compared
+ * on the stored bfloat16 value: key = bit pattern & 0x7FFF (so -0 ties +0, Inf beats every
+ * finite value and NaN patterns carry the largest keys).
+ *
+ * Packed layout (the only layout that crosses this boundary)
+ *   values   nm_bf16 [O, K*N/M], row-major, no padding: values[o, g*N + j] is the j-th
+ *            kept weight of group g of row o, kept weights in ascending position.
+ *   indices  uint32  [O, ceil(K*N/M*b/32)], b = log2(M): per row an LSB-first bit stream;
+ *            field f = g*N + j occupies bits [f*b, f*b+b) of the row and holds the
+ *            position (0..M-1) of values[o, f] inside its group; the row is padded with
+ *            zero bits to a 32-bit boundary.  3-bit fields (M = 8) may straddle words.
+ *   mask     uint32  [O, ceil(K/32)]: bit (k mod 32) of word floor(k/32) of row o is
+ *            the mask value of W[o, k]; padding bits are zero.
+ *
+ * Ownership and execution
+ *   Every data pointer is a DEVICE pointer owned by the caller unless it is marked
+ *   "host".  The library allocates no device memory and keeps no state besides the
+ *   last HIP error code.  `stream` is a hipStream_t passed as void* (NULL = the null
+ *   stream).  Calls validate their arguments on the host, enqueue their kernels on
+ *   `stream` and return without synchronising.  Argument errors are reported before
+ *   anything is launched, so they can be exercised without a GPU.
+ *   No function throws, aborts or prints.
+ */
+#ifndef NM_SPARSE_H
+#define NM_SPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t nm_bf16; /* bfloat16 bit pattern */
+
+/* Status codes (return value of every int32_t function). */
+enum {
+  NM_OK = 0,
+  NM_ERR_NULL = 1,      /* a required pointer is NULL */
+  NM_ERR_SHAPE = 2,     /* O, K or T <= 0; K % M != 0; a leading dimension smaller than the row; count <= 0 */
+  NM_ERR_LEVEL = 3,     /* M not in {4, 8, 16} or N outside [1, M] */
+  NM_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
+  NM_ERR_DTYPE = 5,     /* out_dtype is neither NM_OUT_F32 nor NM_OUT_BF16 */
+  NM_ERR_WORKSPACE = 6, /* workspace is NULL or smaller than nm_spmm_workspace_bytes() */
+  NM_ERR_DEVICE = 7     /* a HIP call failed; see nm_last_hip_error() */
+};
+
+enum { NM_OUT_F32 = 0, NM_OUT_BF16 = 1 };
+
+/* Text for a status code (static storage, never NULL). */
+const char* nm_status_string(int32_t status);
+
+/* hipError_t of the most recent failed HIP call made by this library on the calling thread
+ * (0 if none). */
+int32_t nm_last_hip_error(void);
+
+/* Buffer sizes in bytes for the layouts above; 0 if the level or shape is illegal. */
+size_t nm_values_bytes(int64_t O, int64_t K, int32_t N, int32_t M);
+size_t nm_index_bytes(int64_t O, int64_t K, int32_t N, int32_t M);
+size_t nm_mask_bytes(int64_t O, int64_t K);
+
+/* Scratch needed by nm_spmm / nm_linear_forward for this layer and token count (bytes,
+ * possibly 0).  The product kernels consume the weight in matrix-core operand order; for
+ * levels whose packed layout is not already that order the call first rewrites the packed
+ * weight into the scratch.  0 if the level or shape is illegal. */
+size_t nm_spmm_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M, int64_t T);
+
+/*
+ * nm_prune -- Eq. (1) with magnitude saliency (Section 3.1).
+ *   W         in   [O, K], ld ldw, 2-byte aligned
+ *   mask      out  [O, ceil(K/32)] words, 4-byte aligned; exactly N bits set per group
+ *   W_masked  out  optional (NULL to skip): [O, K] with ld ldw; W where mask = 1, +0
+ *                  elsewhere.  May be the same pointer as W (in-place pruning).
+ */
+int32_t nm_prune(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M,
+                 uint32_t* mask, nm_bf16* W_masked, void* stream);
+
+/*
+ * nm_pack -- compress W to the packed layout (Fig. 2, upper part).
+ *   mask == NULL : select by magnitude as nm_prune does, fused with packing (the hot path).
+ *   mask != NULL : use the caller's mask (any saliency, e.g. a Taylor score, Section 3.1).
+ *                  Per group the N lowest set positions are kept; a group with fewer than N
+ *                  set bits is completed with its lowest unset positions, stored with value
+ *                  +0.  Use nm_mask_check to find out whether a mask has exactly N per group.
+ *   values   out  nm_values_bytes(O,K,N,M) bytes, 2-byte aligned (16-byte alignment lets the
+ *                  fast kernels run)
+ *   indices  out  nm_index_bytes(O,K,N,M) bytes, 4-byte aligned; every word is written,
+ *                  padding bits zero
+ * nm_pack(W, mask = NULL) and nm_prune followed by nm_pack(W, mask) write identical bytes.
+ */
+int32_t nm_pack(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M,
+                const uint32_t* mask, nm_bf16* values, uint32_t* indices, void* stream);
+
+/* One nm_pack(mask = NULL) per descriptor, in a single launch (a model's layers are
+ * compressed together: Section 3, configuration alpha = (s^1 ... s^L)). */
+typedef struct nm_pack_desc {
+  const nm_bf16* W; /* device, [O, K] contiguous (ldw = K) */
+  nm_bf16* values;  /* device, out */
+  uint32_t* indices; /* device, out */
+  int64_t O, K;
+  int32_t N, M;
+} nm_pack_desc;
+
+/* descs is a HOST array of `count` descriptors; it is read before the call returns. */
+int32_t nm_pack_batched(const nm_pack_desc* descs, int32_t count, void* stream);
+
+/*
+ * nm_unpack -- inverse of nm_pack: W_dense[o, g*M + idx] = value, +0 elsewhere.
+ *   W_dense  out  [O, K] with ld ldw; every element of the O x K block is written.
+ */
+int32_t nm_unpack(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K,
+                  int32_t N, int32_t M, nm_bf16* W_dense, int64_t ldw, void* stream);
+
+/*
+ * nm_mask_check -- counts the groups of `mask` whose population count differs from N.
+ *   bad_groups  out  one uint32 on the device; overwritten with the count (saturating).
+ */
+int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int32_t M,
+                      uint32_t* bad_groups, void* stream);
+
+/*
+ * nm_spmm -- Y = X * W_s^T from the packed weight (Fig. 2, lower part):
+ *   Y[t, o] = sum_g sum_{j<N} X[t, g*M + idx[o,g,j]] * val[o,g,j], fp32 accumulation.
+ *   values, indices  in   packed layout of an [O, K] weight at level N:M
+ *   X                in   [T, K], ld ldx
+ *   Y                out  [T, O], ld ldy (elements of the output type); float if
+ *                         out_dtype = NM_OUT_F32, bfloat16 (round to nearest even) if
+ *                         NM_OUT_BF16
+ *   workspace        scratch of at least nm_spmm_workspace_bytes(O,K,N,M,T) bytes, 256-byte
+ *                    aligned; may be NULL when that size is 0.  Its contents are undefined
+ *                    after the call; concurrent calls need distinct workspaces.
+ * The matrix-core kernels need K % 64 == 0, 16-byte aligned X, values and Y and ldx, ldy
+ * multiples of 8; other shapes run a slower general kernel with the same results.
+ */
+int32_t nm_spmm(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K,
+                int32_t N, int32_t M, const nm_bf16* X, int64_t T, int64_t ldx,
+                void* Y, int64_t ldy, int32_t out_dtype,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * nm_linear_forward -- one sparse linear layer at its own level (Section 3.1: the level
+ * chosen for a layer is applied when that layer is computed): nm_spmm plus an optional
+ * fp32 bias[O] (NULL = none) added to the fp32 accumulator before the output is rounded.
+ */
+int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K,
+                          int32_t N, int32_t M, const nm_bf16* X, int64_t T, int64_t ldx,
+                          const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NM_SPARSE_H */

@@ -1,0 +1,22 @@
+"""N:M-sparse linear layer for AMD MI355X: thin Python binding over the C ABI in include/nm_sparse.h.
+
+Importing the package does not load the HIP library; the first call does, and fails loudly if the
+library has not been built (python -m paper_2409_09708_amd.build).
+"""
+from .binding import (  # noqa: F401
+    NmError,
+    library_path,
+    load_library,
+    nm_index_bytes,
+    nm_linear_forward,
+    nm_mask_bytes,
+    nm_mask_check,
+    nm_pack,
+    nm_pack_batched,
+    nm_prune,
+    nm_spmm,
+    nm_spmm_workspace_bytes,
+    nm_status_string,
+    nm_unpack,
+    nm_values_bytes,
+)

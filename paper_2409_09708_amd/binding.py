@@ -1,0 +1,278 @@
+"""ctypes binding of libnm_sparse.so.  Argument marshalling only: every step of the path runs in the
+HIP kernels behind the C ABI (include/nm_sparse.h).  torch provides device memory and the stream.
+
+Tensor conventions: weights / activations / packed values are torch.bfloat16 CUDA tensors; index and
+mask words are torch.int32 tensors holding the uint32 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_int32, c_int64, c_size_t, c_void_p
+from typing import List, Optional, Sequence, Tuple
+
+_LIB = None
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+
+NM_OK = 0
+NM_OUT_F32, NM_OUT_BF16 = 0, 1
+
+EXPORTS = (
+    "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
+    "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
+    "nm_spmm", "nm_linear_forward",
+)
+
+
+class NmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"nm_sparse status {status}: {text}")
+        self.status = status
+
+
+class PackDesc(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("values", c_void_p), ("indices", c_void_p),
+                ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32)]
+
+
+def library_path() -> str:
+    return os.path.join(_PKG_DIR, "libnm_sparse.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the HIP library (once).  There is no fallback: a missing library is an error."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2409_09708_amd.build`")
+    lib = ctypes.CDLL(path)
+    lib.nm_status_string.restype = c_char_p
+    lib.nm_status_string.argtypes = [c_int32]
+    lib.nm_last_hip_error.restype = c_int32
+    lib.nm_last_hip_error.argtypes = []
+    for name in ("nm_values_bytes", "nm_index_bytes"):
+        getattr(lib, name).restype = c_size_t
+        getattr(lib, name).argtypes = [c_int64, c_int64, c_int32, c_int32]
+    lib.nm_mask_bytes.restype = c_size_t
+    lib.nm_mask_bytes.argtypes = [c_int64, c_int64]
+    lib.nm_spmm_workspace_bytes.restype = c_size_t
+    lib.nm_spmm_workspace_bytes.argtypes = [c_int64, c_int64, c_int32, c_int32, c_int64]
+    lib.nm_prune.restype = c_int32
+    lib.nm_prune.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p, c_void_p]
+    lib.nm_pack.restype = c_int32
+    lib.nm_pack.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                            c_void_p]
+    lib.nm_pack_batched.restype = c_int32
+    lib.nm_pack_batched.argtypes = [ctypes.POINTER(PackDesc), c_int32, c_void_p]
+    lib.nm_unpack.restype = c_int32
+    lib.nm_unpack.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64, c_void_p]
+    lib.nm_mask_check.restype = c_int32
+    lib.nm_mask_check.argtypes = [c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
+    lib.nm_spmm.restype = c_int32
+    lib.nm_spmm.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64, c_int64,
+                            c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_linear_forward.restype = c_int32
+    lib.nm_linear_forward.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64,
+                                      c_int64, c_void_p, c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    _LIB = lib
+    return lib
+
+
+def nm_status_string(status: int) -> str:
+    return load_library().nm_status_string(status).decode()
+
+
+def _check(status: int) -> None:
+    if status != NM_OK:
+        raise NmError(status, nm_status_string(status))
+
+
+def nm_values_bytes(O: int, K: int, N: int, M: int) -> int:
+    return int(load_library().nm_values_bytes(O, K, N, M))
+
+
+def nm_index_bytes(O: int, K: int, N: int, M: int) -> int:
+    return int(load_library().nm_index_bytes(O, K, N, M))
+
+
+def nm_mask_bytes(O: int, K: int) -> int:
+    return int(load_library().nm_mask_bytes(O, K))
+
+
+def nm_spmm_workspace_bytes(O: int, K: int, N: int, M: int, T: int) -> int:
+    return int(load_library().nm_spmm_workspace_bytes(O, K, N, M, T))
+
+
+# ------------------------------------------------------------------------------------------------
+# tensor marshalling
+# ------------------------------------------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_handle(stream) -> int:
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _need(t, dtype, what: str) -> None:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{what} must be {dtype}, got {t.dtype}")
+
+
+def _rows(t, what: str) -> Tuple[int, int, int]:
+    """(rows, cols, leading dimension) of a 2-D tensor whose rows are contiguous."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{what} must be 2-D with unit stride along its rows")
+    return int(t.shape[0]), int(t.shape[1]), int(t.stride(0)) if t.shape[0] > 1 else int(t.shape[1])
+
+
+def _empty_packed(O: int, K: int, N: int, M: int, device):
+    torch = _torch()
+    vb, ib = nm_values_bytes(O, K, N, M), nm_index_bytes(O, K, N, M)
+    if vb == 0:  # illegal level or shape: let the library name the error (it returns before touching a pointer)
+        _check(load_library().nm_pack(16, O, K, K, N, M, None, 16, 16, None))
+    values = torch.empty((O, vb // (2 * O)), dtype=torch.bfloat16, device=device)
+    indices = torch.empty((O, ib // (4 * O)), dtype=torch.int32, device=device)
+    return values, indices
+
+
+def nm_prune(W, N: int, M: int, W_masked=None, stream=None):
+    """Mask words [O, ceil(K/32)] (int32) of Eq. (1); optionally writes the pruned weight to W_masked."""
+    torch = _torch()
+    _need(W, torch.bfloat16, "W")
+    O, K, ldw = _rows(W, "W")
+    mask = torch.empty((O, (K + 31) // 32), dtype=torch.int32, device=W.device)
+    wm_ptr = None
+    if W_masked is not None:
+        _need(W_masked, torch.bfloat16, "W_masked")
+        if _rows(W_masked, "W_masked") != (O, K, ldw):
+            raise ValueError("W_masked must have the shape and leading dimension of W")
+        wm_ptr = W_masked.data_ptr()
+    _check(load_library().nm_prune(W.data_ptr(), O, K, ldw, N, M, mask.data_ptr(), wm_ptr, _stream_handle(stream)))
+    return mask
+
+
+def nm_pack(W, N: int, M: int, mask=None, stream=None):
+    """(values bf16 [O, K*N/M], indices int32 [O, words]) of W at level N:M."""
+    torch = _torch()
+    _need(W, torch.bfloat16, "W")
+    O, K, ldw = _rows(W, "W")
+    values, indices = _empty_packed(O, K, N, M, W.device)
+    mask_ptr = None
+    if mask is not None:
+        _need(mask, torch.int32, "mask")
+        if tuple(mask.shape) != (O, (K + 31) // 32) or not mask.is_contiguous():
+            raise ValueError("mask must be contiguous [O, ceil(K/32)]")
+        mask_ptr = mask.data_ptr()
+    _check(load_library().nm_pack(W.data_ptr(), O, K, ldw, N, M, mask_ptr, values.data_ptr(), indices.data_ptr(),
+                                  _stream_handle(stream)))
+    return values, indices
+
+
+def nm_pack_batched(layers: Sequence[Tuple[object, int, int]], stream=None, out=None):
+    """One launch for many (W, N, M); returns [(values, indices), ...]."""
+    torch = _torch()
+    descs = (PackDesc * len(layers))()
+    outs: List[Tuple[object, object]] = []
+    for i, (W, N, M) in enumerate(layers):
+        _need(W, torch.bfloat16, "W")
+        if not W.is_contiguous():
+            raise ValueError("nm_pack_batched needs contiguous weights")
+        O, K = int(W.shape[0]), int(W.shape[1])
+        values, indices = out[i] if out is not None else _empty_packed(O, K, N, M, W.device)
+        outs.append((values, indices))
+        descs[i] = PackDesc(W.data_ptr(), values.data_ptr(), indices.data_ptr(), O, K, N, M)
+    _check(load_library().nm_pack_batched(descs, len(layers), _stream_handle(stream)))
+    return outs
+
+
+def nm_unpack(values, indices, K: int, N: int, M: int, stream=None):
+    torch = _torch()
+    _need(values, torch.bfloat16, "values")
+    _need(indices, torch.int32, "indices")
+    O = int(values.shape[0])
+    Wd = torch.empty((O, K), dtype=torch.bfloat16, device=values.device)
+    _check(load_library().nm_unpack(values.data_ptr(), indices.data_ptr(), O, K, N, M, Wd.data_ptr(), K,
+                                    _stream_handle(stream)))
+    return Wd
+
+
+def nm_mask_check(mask, K: int, N: int, M: int, stream=None) -> int:
+    """Number of groups of `mask` that do not hold exactly N ones (synchronises to read it)."""
+    torch = _torch()
+    _need(mask, torch.int32, "mask")
+    O = int(mask.shape[0])
+    bad = torch.empty((1,), dtype=torch.int32, device=mask.device)
+    _check(load_library().nm_mask_check(mask.data_ptr(), O, K, N, M, bad.data_ptr(), _stream_handle(stream)))
+    return int(bad.item()) & 0xFFFFFFFF
+
+
+_WORKSPACES = {}
+
+
+def _workspace(nbytes: int, device):
+    """A cached scratch tensor per device, grown on demand (allocated by torch, not by the library)."""
+    torch = _torch()
+    key = (device.type, device.index)
+    ws = _WORKSPACES.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty((max(nbytes, 1 << 20),), dtype=torch.uint8, device=device)
+        _WORKSPACES[key] = ws
+    return ws
+
+
+def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out_dtype=None, out=None,
+                      workspace=None, stream=None):
+    """Y = X * W_s^T (+ bias) from the packed weight; Y is float32 (default) or bfloat16 [T, O]."""
+    torch = _torch()
+    _need(values, torch.bfloat16, "values")
+    _need(indices, torch.int32, "indices")
+    _need(X, torch.bfloat16, "X")
+    O = int(values.shape[0])
+    T, KX, ldx = _rows(X, "X")
+    if KX != K:
+        raise ValueError("X must be [T, K]")
+    if not values.is_contiguous() or not indices.is_contiguous():
+        raise ValueError("packed tensors must be contiguous")
+    if out is not None:
+        out_dtype = out.dtype
+    out_dtype = out_dtype or torch.float32
+    if out_dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("out dtype must be float32 or bfloat16")
+    if out is None:
+        out = torch.empty((T, O), dtype=out_dtype, device=X.device)
+    TY, OY, ldy = _rows(out, "out")
+    if (TY, OY) != (T, O):
+        raise ValueError("out must be [T, O]")
+    need = nm_spmm_workspace_bytes(O, K, N, M, T)
+    if workspace is None and need:
+        workspace = _workspace(need, X.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    bias_ptr = None
+    if bias is not None:
+        _need(bias, torch.float32, "bias")
+        if bias.numel() != O or not bias.is_contiguous():
+            raise ValueError("bias must be contiguous [O]")
+        bias_ptr = bias.data_ptr()
+    code = NM_OUT_F32 if out_dtype == torch.float32 else NM_OUT_BF16
+    lib = load_library()
+    if bias_ptr is None:
+        st = lib.nm_spmm(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx, out.data_ptr(), ldy,
+                         code, ws_ptr, ws_bytes, _stream_handle(stream))
+    else:
+        st = lib.nm_linear_forward(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx, bias_ptr,
+                                   out.data_ptr(), ldy, code, ws_ptr, ws_bytes, _stream_handle(stream))
+    _check(st)
+    return out
+
+
+def nm_spmm(values, indices, K: int, N: int, M: int, X, out_dtype=None, out=None, workspace=None, stream=None):
+    return nm_linear_forward(values, indices, K, N, M, X, None, out_dtype, out, workspace, stream)

@@ -1,0 +1,146 @@
+// C ABI of the N:M-sparse linear layer: argument validation on the host, then kernel launches on
+// the caller's stream.  Declarations and the contract of every call are in include/nm_sparse.h.
+#include "nm_sparse.h"
+
+#include "nm_device.h"
+#include "nm_launch.h"
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+inline int32_t device_status(hipError_t e) {
+  if (e == hipSuccess) return NM_OK;
+  g_last_hip_error = (int32_t)e;
+  return NM_ERR_DEVICE;
+}
+
+inline bool level_ok(int32_t N, int32_t M) { return (M == 4 || M == 8 || M == 16) && N >= 1 && N <= M; }
+
+inline bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// shape of a weight: level first (so that an illegal M never reaches a modulo), then sizes
+inline int32_t check_weight(int64_t O, int64_t K, int32_t N, int32_t M) {
+  if (!level_ok(N, M)) return NM_ERR_LEVEL;
+  if (O <= 0 || K <= 0 || (K % M) != 0) return NM_ERR_SHAPE;
+  if (O > (int64_t)1 << 31 || K > (int64_t)1 << 31) return NM_ERR_SHAPE;
+  return NM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* nm_status_string(int32_t status) {
+  switch (status) {
+    case NM_OK: return "ok";
+    case NM_ERR_NULL: return "a required pointer is NULL";
+    case NM_ERR_SHAPE: return "illegal shape (sizes must be positive, K a multiple of M, leading dimensions >= row length)";
+    case NM_ERR_LEVEL: return "illegal N:M level (M in {4, 8, 16}, 1 <= N <= M)";
+    case NM_ERR_ALIGN: return "a pointer is not aligned as documented";
+    case NM_ERR_DTYPE: return "unknown output type";
+    case NM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case NM_ERR_DEVICE: return "a HIP call failed (see nm_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int32_t nm_last_hip_error(void) { return g_last_hip_error; }
+
+size_t nm_values_bytes(int64_t O, int64_t K, int32_t N, int32_t M) {
+  if (check_weight(O, K, N, M) != NM_OK) return 0;
+  return (size_t)O * (size_t)nm::values_per_row(K, N, M) * sizeof(nm_bf16);
+}
+
+size_t nm_index_bytes(int64_t O, int64_t K, int32_t N, int32_t M) {
+  if (check_weight(O, K, N, M) != NM_OK) return 0;
+  return (size_t)O * (size_t)nm::index_words_per_row(K, N, M) * sizeof(uint32_t);
+}
+
+size_t nm_mask_bytes(int64_t O, int64_t K) {
+  if (O <= 0 || K <= 0) return 0;
+  return (size_t)O * (size_t)nm::mask_words_per_row(K) * sizeof(uint32_t);
+}
+
+size_t nm_spmm_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M, int64_t T) {
+  if (check_weight(O, K, N, M) != NM_OK || T <= 0) return 0;
+  return nm::spmm_workspace_bytes(O, K, N, M, T);
+}
+
+int32_t nm_prune(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M, uint32_t* mask,
+                 nm_bf16* W_masked, void* stream) {
+  if (!W || !mask) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(W, 2) || !aligned(mask, 4) || !aligned(W_masked, 2)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_prune(W, O, K, ldw, N, M, mask, W_masked, (hipStream_t)stream));
+}
+
+int32_t nm_pack(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M, const uint32_t* mask,
+                nm_bf16* values, uint32_t* indices, void* stream) {
+  if (!W || !values || !indices) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(W, 2) || !aligned(values, 2) || !aligned(indices, 4) || !aligned(mask, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_pack(W, O, K, ldw, N, M, mask, values, indices, (hipStream_t)stream));
+}
+
+int32_t nm_pack_batched(const nm_pack_desc* descs, int32_t count, void* stream) {
+  if (!descs) return NM_ERR_NULL;
+  if (count <= 0) return NM_ERR_SHAPE;
+  static_assert(sizeof(nm_pack_desc) == sizeof(nm::PackDesc), "descriptor layouts must match");
+  for (int32_t i = 0; i < count; ++i) {
+    const nm_pack_desc& d = descs[i];
+    if (!d.W || !d.values || !d.indices) return NM_ERR_NULL;
+    if (int32_t s = check_weight(d.O, d.K, d.N, d.M)) return s;
+    if (!aligned(d.W, 2) || !aligned(d.values, 2) || !aligned(d.indices, 4)) return NM_ERR_ALIGN;
+  }
+  return device_status(nm::launch_pack_batched(reinterpret_cast<const nm::PackDesc*>(descs), count, (hipStream_t)stream));
+}
+
+int32_t nm_unpack(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                  nm_bf16* W_dense, int64_t ldw, void* stream) {
+  if (!values || !indices || !W_dense) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(values, 2) || !aligned(indices, 4) || !aligned(W_dense, 2)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_unpack(values, indices, O, K, N, M, W_dense, ldw, (hipStream_t)stream));
+}
+
+int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* bad_groups,
+                      void* stream) {
+  if (!mask || !bad_groups) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (!aligned(mask, 4) || !aligned(bad_groups, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_mask_check(mask, O, K, N, M, bad_groups, (hipStream_t)stream));
+}
+
+int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                          const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y, int64_t ldy,
+                          int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!values || !indices || !X || !Y) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (T <= 0 || T > (int64_t)1 << 31 || ldx < K || ldy < O) return NM_ERR_SHAPE;
+  if (out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16) return NM_ERR_DTYPE;
+  if (!aligned(values, 2) || !aligned(indices, 4) || !aligned(X, 2) || !aligned(bias, 4) ||
+      !aligned(Y, out_dtype == NM_OUT_F32 ? 4 : 2))
+    return NM_ERR_ALIGN;
+  nm::SpmmArgs a;
+  a.values = values; a.indices = indices; a.O = O; a.K = K; a.N = N; a.M = M;
+  a.X = X; a.T = T; a.ldx = ldx; a.bias = bias; a.Y = Y; a.ldy = ldy;
+  a.out_bf16 = (out_dtype == NM_OUT_BF16);
+  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  bool workspace_short = false;
+  hipError_t e = nm::launch_spmm(a, (hipStream_t)stream, &workspace_short);
+  if (workspace_short) return NM_ERR_WORKSPACE;
+  return device_status(e);
+}
+
+int32_t nm_spmm(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                const nm_bf16* X, int64_t T, int64_t ldx, void* Y, int64_t ldy, int32_t out_dtype, void* workspace,
+                size_t workspace_bytes, void* stream) {
+  return nm_linear_forward(values, indices, O, K, N, M, X, T, ldx, nullptr, Y, ldy, out_dtype, workspace,
+                           workspace_bytes, stream);
+}
+
+}  // extern "C"

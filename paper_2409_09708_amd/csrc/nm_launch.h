@@ -1,0 +1,48 @@
+// Host-side launch interface between the C ABI layer and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace nm {
+
+typedef uint16_t bf16_t;
+
+struct PackDesc {
+  const bf16_t* W;
+  bf16_t* values;
+  uint32_t* indices;
+  int64_t O, K;
+  int32_t N, M;
+};
+
+// nm_pack.hip
+hipError_t launch_prune(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N, int M, uint32_t* mask,
+                        bf16_t* w_masked, hipStream_t s);
+hipError_t launch_pack(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N, int M, const uint32_t* mask,
+                       bf16_t* values, uint32_t* indices, hipStream_t s);
+hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s);
+hipError_t launch_unpack(const bf16_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M,
+                         bf16_t* Wd, int64_t ldw, hipStream_t s);
+hipError_t launch_mask_check(const uint32_t* mask, int64_t O, int64_t K, int N, int M, uint32_t* bad, hipStream_t s);
+
+// nm_spmm.hip
+struct SpmmArgs {
+  const bf16_t* values;
+  const uint32_t* indices;
+  int64_t O, K;
+  int N, M;
+  const bf16_t* X;
+  int64_t T, ldx;
+  const float* bias;  // nullable
+  void* Y;
+  int64_t ldy;
+  int out_bf16;
+  void* workspace;
+  size_t workspace_bytes;
+};
+size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);
+// returns hipSuccess or the launch error; *need_workspace is set when the workspace was required but too small
+hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short);
+
+}  // namespace nm

@@ -1,0 +1,144 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the header
+declares, sizes follow the packed layout, and every argument error is reported before a launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import nm_oracle as orc
+from paper_2409_09708_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000  # a non-NULL, well aligned address that is never dereferenced on the error paths
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nm_sparse.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert {"nm_prune", "nm_pack", "nm_spmm", "nm_linear_forward", "nm_unpack", "nm_pack_batched"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.EXPORTS)
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (4, 4), (1, 8), (2, 8), (3, 8), (4, 8), (1, 16), (2, 16), (4, 16)])
+@pytest.mark.parametrize("O,K", [(1, 16), (5, 80), (768, 768), (3072, 768), (7, 48)])
+def test_sizes_follow_the_layout(lib, N, M, O, K):
+    if K % M:
+        assert lib.nm_values_bytes(O, K, N, M) == 0
+        return
+    assert lib.nm_values_bytes(O, K, N, M) == O * orc.values_per_row(K, N, M) * 2
+    assert lib.nm_index_bytes(O, K, N, M) == O * orc.index_words_per_row(K, N, M) * 4
+    assert lib.nm_mask_bytes(O, K) == O * orc.mask_words_per_row(K) * 4
+
+
+def test_sizes_of_illegal_requests_are_zero(lib):
+    assert lib.nm_values_bytes(4, 16, 0, 4) == 0
+    assert lib.nm_values_bytes(4, 16, 5, 4) == 0
+    assert lib.nm_values_bytes(4, 16, 1, 32) == 0
+    assert lib.nm_index_bytes(0, 16, 1, 4) == 0
+    assert lib.nm_mask_bytes(-1, 16) == 0
+    assert lib.nm_spmm_workspace_bytes(4, 64, 2, 4, 0) == 0
+
+
+def test_workspace_sizes(lib):
+    assert lib.nm_spmm_workspace_bytes(768, 768, 2, 4, 100) == 0       # packed 2:4 is the operand layout
+    assert lib.nm_spmm_workspace_bytes(768, 768, 8, 8, 100) == 0       # dense level
+    assert lib.nm_spmm_workspace_bytes(768, 768, 1, 8, 100) == 768 * 768 + 768 * 768 // 8
+    assert lib.nm_spmm_workspace_bytes(768, 768, 4, 8, 100) == 768 * 768 * 2
+    assert lib.nm_spmm_workspace_bytes(8, 24, 1, 8, 100) == 0          # general kernel, no scratch
+
+
+def test_status_strings(lib):
+    seen = set()
+    for s in range(0, 8):
+        txt = lib.nm_status_string(s).decode()
+        assert txt and txt != "unknown status"
+        seen.add(txt)
+    assert len(seen) == 8
+    assert lib.nm_status_string(99).decode() == "unknown status"
+    assert lib.nm_last_hip_error() == 0
+
+
+def test_prune_argument_errors(lib):
+    assert lib.nm_prune(None, 4, 16, 16, 2, 4, FAKE, None, None) == 1
+    assert lib.nm_prune(FAKE, 4, 16, 16, 2, 4, None, None, None) == 1
+    assert lib.nm_prune(FAKE, 4, 16, 16, 0, 4, FAKE, None, None) == 3
+    assert lib.nm_prune(FAKE, 4, 16, 16, 3, 2, FAKE, None, None) == 3
+    assert lib.nm_prune(FAKE, 4, 16, 16, 1, 5, FAKE, None, None) == 3
+    assert lib.nm_prune(FAKE, 4, 12, 12, 2, 8, FAKE, None, None) == 2   # K % M != 0
+    assert lib.nm_prune(FAKE, 0, 16, 16, 2, 4, FAKE, None, None) == 2
+    assert lib.nm_prune(FAKE, 4, 16, 8, 2, 4, FAKE, None, None) == 2    # ldw < K
+    assert lib.nm_prune(FAKE + 1, 4, 16, 16, 2, 4, FAKE, None, None) == 4
+    assert lib.nm_prune(FAKE, 4, 16, 16, 2, 4, FAKE + 2, None, None) == 4
+
+
+def test_pack_unpack_argument_errors(lib):
+    assert lib.nm_pack(None, 4, 16, 16, 2, 4, None, FAKE, FAKE, None) == 1
+    assert lib.nm_pack(FAKE, 4, 16, 16, 2, 4, None, None, FAKE, None) == 1
+    assert lib.nm_pack(FAKE, 4, 16, 16, 2, 4, None, FAKE, None, None) == 1
+    assert lib.nm_pack(FAKE, 4, 16, 16, 9, 8, None, FAKE, FAKE, None) == 3
+    assert lib.nm_pack(FAKE, 4, 20, 20, 2, 8, None, FAKE, FAKE, None) == 2
+    assert lib.nm_pack(FAKE, 4, 16, 16, 2, 4, FAKE + 1, FAKE, FAKE, None) == 4
+    assert lib.nm_unpack(None, FAKE, 4, 16, 2, 4, FAKE, 16, None) == 1
+    assert lib.nm_unpack(FAKE, FAKE, 4, 16, 2, 4, FAKE, 15, None) == 2
+    assert lib.nm_unpack(FAKE, FAKE, 4, 16, 2, 6, FAKE, 16, None) == 3
+    assert lib.nm_mask_check(FAKE, 4, 16, 2, 4, None, None) == 1
+    assert lib.nm_mask_check(FAKE, 4, 18, 2, 4, FAKE, None) == 2
+
+
+def test_pack_batched_argument_errors(lib):
+    assert lib.nm_pack_batched(None, 1, None) == 1
+    d = (binding.PackDesc * 2)()
+    d[0] = binding.PackDesc(FAKE, FAKE, FAKE, 4, 16, 2, 4)
+    d[1] = binding.PackDesc(FAKE, FAKE, FAKE, 4, 16, 2, 4)
+    assert lib.nm_pack_batched(d, 0, None) == 2
+    d[1] = binding.PackDesc(FAKE, None, FAKE, 4, 16, 2, 4)
+    assert lib.nm_pack_batched(d, 2, None) == 1
+    d[1] = binding.PackDesc(FAKE, FAKE, FAKE, 4, 16, 3, 2)
+    assert lib.nm_pack_batched(d, 2, None) == 3
+    d[1] = binding.PackDesc(FAKE, FAKE, FAKE, 4, 24, 1, 16)
+    assert lib.nm_pack_batched(d, 2, None) == 2
+
+
+def test_spmm_argument_errors(lib):
+    ok = dict(values=FAKE, indices=FAKE, O=64, K=64, N=2, M=4, X=FAKE, T=16, ldx=64, Y=FAKE, ldy=64, dt=0,
+              ws=None, wsb=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.nm_spmm(a["values"], a["indices"], a["O"], a["K"], a["N"], a["M"], a["X"], a["T"], a["ldx"],
+                           a["Y"], a["ldy"], a["dt"], a["ws"], a["wsb"], None)
+
+    assert call(values=None) == 1 and call(indices=None) == 1 and call(X=None) == 1 and call(Y=None) == 1
+    assert call(N=3, M=2) == 3 and call(M=32) == 3
+    assert call(K=66) == 2 and call(T=0) == 2 and call(ldx=32) == 2 and call(ldy=8) == 2
+    assert call(dt=2) == 5
+    assert call(X=FAKE + 1) == 4 and call(Y=FAKE + 2) == 4
+    # a level that needs scratch: missing, short and misaligned workspaces are refused before any launch
+    assert call(N=1, M=8) == 6
+    need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 16)
+    assert need == 64 * 64 + 64 * 64 // 8
+    assert call(N=1, M=8, ws=FAKE, wsb=need - 1) == 6
+    assert call(N=1, M=8, ws=FAKE + 16, wsb=need) == 6
+    assert call(N=4, M=8, ws=None, wsb=0) == 6
+    lf = lib.nm_linear_forward(FAKE, FAKE, 64, 64, 2, 4, FAKE, 16, 64, FAKE + 2, FAKE, 64, 0, None, 0, None)
+    assert lf == 4  # bias must be 4-byte aligned
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_PKG_DIR", str(tmp_path))
+    with pytest.raises(RuntimeError, match="missing"):
+        binding.load_library()
