@@ -5,6 +5,8 @@ library has not been built (python -m paper_2409_09708_amd.build).
 """
 from .binding import (  # noqa: F401
     NmError,
+    bf16_bits,
+    bf16_tensor,
     library_path,
     load_library,
     nm_index_bytes,

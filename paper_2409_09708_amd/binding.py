@@ -214,6 +214,20 @@ def nm_mask_check(mask, K: int, N: int, M: int, stream=None) -> int:
     return int(bad.item()) & 0xFFFFFFFF
 
 
+def bf16_tensor(bits, device="cuda"):
+    """numpy uint16 bf16 bit patterns -> torch.bfloat16 tensor on `device` (a copy of the bits)."""
+    import numpy as np
+    torch = _torch()
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bf16_bits(t):
+    """torch.bfloat16 tensor -> numpy uint16 bit patterns on the host."""
+    import numpy as np
+    torch = _torch()
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
 _WORKSPACES = {}
 
 

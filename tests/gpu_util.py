@@ -5,12 +5,8 @@ import torch
 from oracle import nm_oracle as orc
 
 
-def dev_bf16(bits: np.ndarray) -> torch.Tensor:
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def host_bits(t: torch.Tensor) -> np.ndarray:
-    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+from paper_2409_09708_amd.binding import bf16_bits as host_bits
+from paper_2409_09708_amd.binding import bf16_tensor as dev_bf16
 
 
 def host_words(t: torch.Tensor) -> np.ndarray:
