@@ -14,10 +14,10 @@ LIB_PATH = os.path.join(PKG_DIR, "libnm_sparse.so")
 SOURCES = ("nm_api.hip", "nm_pack.hip", "nm_spmm.hip")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 ALU forms are switched off for this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument",
+    "-Wno-unused-command-line-argument", "-Wno-inline-asm",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

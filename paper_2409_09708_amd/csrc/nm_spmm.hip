@@ -13,12 +13,17 @@
 //    zero-filled operand by the pre-pass and multiplied with v_mfma_f32_16x16x32_bf16.
 //
 // Tiling: a block owns BO x BT outputs; per 64-wide K step the W tile (compressed rows + selector
-// words, or dense rows) and the X tile are staged global -> registers -> LDS (two LDS stages, one
-// barrier per step); each wave reads its operand fragments with 16-byte LDS reads from rows padded
-// to an odd number of 16-byte slots (conflict free) and keeps an (OT*16) x (TT*16) accumulator tile.
+// words, or dense rows) and the X tile are copied global -> LDS asynchronously, two or three stages
+// deep with one barrier per step; each wave reads its operand fragments with 16-byte LDS reads
+// (XOR-swizzled rows, conflict free) and keeps an (OT*16) x (TT*16) accumulator tile.
 // Shapes the tiles cannot take (K % 64 != 0, unaligned pointers) run a plain gather kernel.
 #include "nm_device.h"
 #include "nm_launch.h"
+
+#include <stdlib.h>
+
+#include <type_traits>
+#include <utility>
 
 namespace nm {
 
@@ -78,6 +83,16 @@ recode_to_2of4_kernel(const bf16_t* __restrict__ values, const uint32_t* __restr
 
 // ---------------------------------------------------------------------------------------------
 // Tiled matrix-core product.
+//
+// Operand tiles travel global -> LDS directly (global_load_lds_dwordx4: each lane names its own
+// 16 global bytes, the wave's 64 pieces land in 1 KB of consecutive LDS), STAGES buffers deep, so
+// that two K steps of loads are in flight while a third is multiplied and no register is spent on
+// staging.  The compiler does not track these loads; the kernel counts them itself: every wave
+// issues exactly LPW loads per stage and waits with s_waitcnt vmcnt(LPW) (one younger stage may
+// still be in flight) or vmcnt(0) before the one barrier of the step.
+// LDS rows are not padded (the DMA writes 1 KB runs); instead the 16-byte pieces of a row are
+// XOR-swizzled with the row number on the way in, and the fragment reads apply the same XOR, which
+// keeps 8 consecutive rows on distinct banks.
 // ---------------------------------------------------------------------------------------------
 struct GemmArgs {
   const bf16_t* A;      // SPARSE: compressed values [O, K/2]; dense: W_s [O, K]
@@ -88,33 +103,68 @@ struct GemmArgs {
   int64_t O, K, T, ldx, ldy;
   int n_o_tiles, n_t_tiles;
   int out_bf16;
-  int vec_store;  // Y rows allow 4-wide stores (ldy % 4 == 0, aligned base, O % 4 == 0)
+  int vec_store;  // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
 };
 
-template <bool SPARSE, int WO, int WT, int OT, int TT>
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES_>
 struct GemmCfg {
-  static constexpr int NT = WO * WT * 64;
+  static constexpr int STAGES = STAGES_;
+  static constexpr int NW = WO * WT;
+  static constexpr int NT = NW * 64;
   static constexpr int BO = WO * OT * 16;
   static constexpr int BT = WT * TT * 16;
-  static constexpr int KC = 64;                       // dense k per stage
-  static constexpr int A_ROW = SPARSE ? 80 : 144;     // bytes: 64 + 8 selector + 8 pad | 128 + 16 pad
-  static constexpr int X_ROW = 144;                   // 128 + 16 pad
-  static constexpr int A_BYTES = BO * A_ROW;
-  static constexpr int X_BYTES = BT * X_ROW;
-  static constexpr int STAGE = A_BYTES + X_BYTES;
-  static constexpr int A_CPR = SPARSE ? 4 : 8;        // 16-byte chunks per row per stage
-  static constexpr int A_PER_THREAD = BO * A_CPR / NT;
-  static constexpr int X_PER_THREAD = BT * 8 / NT;
-  static constexpr int LDS_BYTES = 2 * STAGE;
-  static_assert(BO * A_CPR % NT == 0 && BT * 8 % NT == 0, "tile must split evenly over the block");
-  static_assert(BO <= NT, "one selector row per thread");
+  static constexpr int KC = 64;                         // dense k per stage
+  static constexpr int H = SPARSE ? 1 : 2;              // sub-steps (32 matrix instructions each) per stage
+  static constexpr int A_ROWB = SPARSE ? 64 : 128;      // bytes of one W row per stage
+  static constexpr int X_BYTES = BT * 128;
+  static constexpr int A_BYTES = BO * A_ROWB;
+  static constexpr int S_BYTES = SPARSE ? BO * 8 : 0;   // two selector words per row per stage
+  static constexpr int STAGE = X_BYTES + A_BYTES + S_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE;
+  static constexpr int X_LOADS = X_BYTES / 1024;        // wave-wide 16-byte loads per stage
+  static constexpr int A_LOADS = A_BYTES / 1024;
+  static constexpr int S_LOADS = S_BYTES / 256;         // wave-wide 4-byte loads per stage
+  static constexpr int X_PW = (X_LOADS + NW - 1) / NW;  // per wave (surplus waves repeat a load)
+  static constexpr int A_PW = (A_LOADS + NW - 1) / NW;
+  static constexpr int S_PW = SPARSE ? (S_LOADS + NW - 1) / NW : 0;
+  static constexpr int LPW = X_PW + A_PW + S_PW;
+  static_assert(STAGES == 2 || STAGES == 3, "two or three LDS stages");
+  static_assert(STAGES * LPW < 64, "vmcnt is a 6-bit counter");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
-template <bool SPARSE, int WO, int WT, int OT, int TT>
+// Asynchronous 16-byte (4-byte) per lane global -> LDS copy: lane i's piece lands at lds + 16*i (4*i).
+// `base` is wave-uniform (scalar registers), the lane adds an unsigned 32-bit byte offset; M0 carries
+// the LDS byte address and needs one wait state before the load that reads it.
+typedef uint64_t uniform_ptr_t;
+__device__ __forceinline__ uniform_ptr_t make_uniform(const void* p) {
+  const uint64_t v = (uint64_t)(uintptr_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ void dma16(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(lane_byte_offset),
+               "s"(base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds), "v"(lane_byte_offset),
+               "s"(base)
+               : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_outstanding() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, bool PINGPONG>
 __global__ void __launch_bounds__(WO * WT * 64)
 nm_gemm_kernel(const GemmArgs a) {
-  using C = GemmCfg<SPARSE, WO, WT, OT, TT>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+  static_assert(!PINGPONG || (C::NW % 8 == 0), "ping-pong needs one wave of each group per SIMD");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   // XCD-aware tile order: consecutive block ids land on different XCDs (8 of them, each with its
   // own L2); give every XCD a contiguous range of tiles so that the blocks sharing an L2 share X rows.
@@ -129,58 +179,67 @@ nm_gemm_kernel(const GemmArgs a) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wo = wave % WO;
   const int wt = wave / WO;
   const int r16 = lane & 15;
   const int kb = lane >> 4;
 
-  // ---- global -> register staging
-  uint4 a_reg[C::A_PER_THREAD];
-  uint4 x_reg[C::X_PER_THREAD];
-  uint2 s_reg = make_uint2(0, 0);
+  // ---- per-lane source offsets and per-wave LDS destinations of this wave's loads (fixed over K)
   const int64_t a_ld = SPARSE ? (a.K >> 1) : a.K;  // elements per row of A
+  uint32_t x_voff[C::X_PW], a_voff[C::A_PW], s_voff[C::S_PW > 0 ? C::S_PW : 1];
+  uint32_t x_dst[C::X_PW], a_dst[C::A_PW], s_dst[C::S_PW > 0 ? C::S_PW : 1];
+  const int64_t t_last = a.T - 1 - t0, o_last = a.O - 1 - o0;  // rows past the edge re-read the last valid row
+#pragma unroll
+  for (int i = 0; i < C::X_PW; ++i) {
+    const int j = (wave + i * C::NW) % C::X_LOADS;
+    int64_t row = 8 * j + (lane >> 3);
+    const int c = (lane & 7) ^ (int)(row & 7);
+    if (row > t_last) row = t_last;
+    x_voff[i] = (uint32_t)((row * a.ldx + c * 8) * 2);
+    x_dst[i] = (uint32_t)(j * 1024);
+  }
+#pragma unroll
+  for (int i = 0; i < C::A_PW; ++i) {
+    const int j = (wave + i * C::NW) % C::A_LOADS;
+    int64_t row;
+    int c;
+    if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 2) & 3); }
+    else { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (int)(row & 7); }
+    if (row > o_last) row = o_last;
+    a_voff[i] = (uint32_t)((row * a_ld + c * 8) * 2);
+    a_dst[i] = (uint32_t)(C::X_BYTES + j * 1024);
+  }
+  if (SPARSE) {
+#pragma unroll
+    for (int i = 0; i < C::S_PW; ++i) {
+      const int j = (wave + i * C::NW) % C::S_LOADS;
+      int64_t row = 32 * j + (lane >> 1);
+      if (row > o_last) row = o_last;
+      s_voff[i] = (uint32_t)((row * (a.K >> 5) + (lane & 1)) * 4);
+      s_dst[i] = (uint32_t)(C::X_BYTES + C::A_BYTES + j * 256);
+    }
+  }
+  const bf16_t* x_base = a.X + t0 * a.ldx;
+  const bf16_t* a_base = a.A + o0 * a_ld;
+  const uint32_t* s_base = SPARSE ? a.sel + o0 * (a.K >> 5) : nullptr;
 
-  auto load_stage = [&](int ks) {
-#pragma unroll
-    for (int i = 0; i < C::A_PER_THREAD; ++i) {
-      const int q = tid + i * C::NT;
-      const int row = q / C::A_CPR, cc = q % C::A_CPR;
-      const int64_t o = o0 + row;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (o < a.O) v = *reinterpret_cast<const uint4*>(a.A + o * a_ld + (int64_t)ks * (SPARSE ? 32 : 64) + cc * 8);
-      a_reg[i] = v;
-    }
-    if (SPARSE && tid < C::BO) {
-      const int64_t o = o0 + tid;
-      s_reg = make_uint2(0, 0);
-      if (o < a.O) s_reg = *reinterpret_cast<const uint2*>(a.sel + o * (a.K >> 5) + (int64_t)ks * 2);
-    }
-#pragma unroll
-    for (int i = 0; i < C::X_PER_THREAD; ++i) {
-      const int q = tid + i * C::NT;
-      const int row = q >> 3, cc = q & 7;
-      const int64_t t = t0 + row;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (t < a.T) v = *reinterpret_cast<const uint4*>(a.X + t * a.ldx + (int64_t)ks * 64 + cc * 8);
-      x_reg[i] = v;
+  // the d-th of this wave's LPW loads of stage ks into LDS buffer buf (d is a compile-time index)
+  auto issue_one = [&](auto d_tag, int ks, int buf) {
+    constexpr int d = decltype(d_tag)::value;
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
+    if constexpr (d < C::X_PW) {
+      dma16(make_uniform(x_base + (int64_t)ks * 64), x_voff[d], lds + x_dst[d]);
+    } else if constexpr (d < C::X_PW + C::A_PW) {
+      dma16(make_uniform(a_base + (int64_t)ks * (SPARSE ? 32 : 64)), a_voff[d - C::X_PW], lds + a_dst[d - C::X_PW]);
+    } else {
+      dma4(make_uniform(s_base + (int64_t)ks * 2), s_voff[d - C::X_PW - C::A_PW], lds + s_dst[d - C::X_PW - C::A_PW]);
     }
   };
-  auto store_stage = [&](int buf) {
-    unsigned char* base = smem + buf * C::STAGE;
-#pragma unroll
-    for (int i = 0; i < C::A_PER_THREAD; ++i) {
-      const int q = tid + i * C::NT;
-      const int row = q / C::A_CPR, cc = q % C::A_CPR;
-      *reinterpret_cast<uint4*>(base + row * C::A_ROW + cc * 16) = a_reg[i];
-    }
-    if (SPARSE && tid < C::BO) *reinterpret_cast<uint2*>(base + tid * C::A_ROW + 64) = s_reg;
-#pragma unroll
-    for (int i = 0; i < C::X_PER_THREAD; ++i) {
-      const int q = tid + i * C::NT;
-      const int row = q >> 3, cc = q & 7;
-      *reinterpret_cast<uint4*>(base + C::A_BYTES + row * C::X_ROW + cc * 16) = x_reg[i];
-    }
+  auto issue_stage = [&](int ks, int buf) {
+    [&]<int... D>(std::integer_sequence<int, D...>) {
+      (issue_one(std::integral_constant<int, D>{}, ks, buf), ...);
+    }(std::make_integer_sequence<int, C::LPW>{});
   };
 
   f32x4_t acc[OT][TT];
@@ -189,92 +248,209 @@ nm_gemm_kernel(const GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < TT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = (int)(a.K / C::KC);
-  load_stage(0);
-  store_stage(0);
-  __syncthreads();
+  // fragment read offsets inside a stage (the XOR undoes the swizzle applied by the loads)
+  const int x_sw = r16 & 7;
+  const int x_row = (wt * TT * 16 + r16) * 128;
+  const int a_row = C::X_BYTES + (wo * OT * 16 + r16) * C::A_ROWB;
+  const int a_sw = SPARSE ? ((r16 >> 2) & 3) : (r16 & 7);
+  const int s_row = C::X_BYTES + C::A_BYTES + (wo * OT * 16 + r16) * 8 + (kb >> 1) * 4;
 
-  const int a_row0 = (wo * OT * 16 + r16) * C::A_ROW;
-  const int x_row0 = C::A_BYTES + (wt * TT * 16 + r16) * C::X_ROW;
-
-  for (int ks = 0; ks < nk; ++ks) {
-    const int buf = ks & 1;
-    if (ks + 1 < nk) load_stage(ks + 1);
+  // One sub-step = 32 matrix instructions per wave.  SPARSE: a stage is one sub-step (K = 64 through
+  // v_smfmac 16x16x64).  Dense: a stage is two sub-steps of K = 32 (v_mfma 16x16x32), h selects the half.
+  // SPARSE lane (r16, kb) of the W operand covers dense k = 16*kb .. 16*kb+15 of the step (compressed
+  // values 8*kb .. 8*kb+7 and 16 selector bits); the X operand holds k = 8*kb+e (e < 8) and
+  // 32 + 8*kb + e - 8 (e >= 8).
+  constexpr int H = C::H;
+  u32x4_t af[OT];
+  int sel[OT];
+  u32x8_t bs[SPARSE ? TT : 1];
+  u32x4_t bd[SPARSE ? 1 : TT];
+  auto read_frags = [&](int buf, int h) {
     const unsigned char* base = smem + buf * C::STAGE;
-
     if (SPARSE) {
-      // lane (r16, kb) of the W operand covers dense k = 16*kb .. 16*kb+15 of the step: compressed
-      // values 8*kb .. 8*kb+7 and 16 selector bits; the X operand holds k = 8*kb+e (e < 8) and
-      // 32 + 8*kb + e - 8 (e >= 8).
-      u32x4_t af[OT];
-      int sel[OT];
 #pragma unroll
       for (int i = 0; i < OT; ++i) {
-        const unsigned char* row = base + a_row0 + i * 16 * C::A_ROW;
-        af[i] = *reinterpret_cast<const u32x4_t*>(row + kb * 16);
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(row + 64 + (kb >> 1) * 4);
+        af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + ((kb ^ a_sw) * 16));
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_row + i * 16 * 8);
         sel[i] = (int)(w >> ((kb & 1) * 16));
       }
 #pragma unroll
       for (int j = 0; j < TT; ++j) {
-        const unsigned char* row = base + x_row0 + j * 16 * C::X_ROW;
-        u32x8_t bfrag;
-        const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + kb * 16);
-        const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + 64 + kb * 16);
-        bfrag = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-        for (int i = 0; i < OT; ++i)
-          acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
-                                                                __builtin_bit_cast(bf16x16_t, bfrag), acc[i][j],
-                                                                sel[i], 0, 0);
+        const unsigned char* row = base + x_row + j * 16 * 128;
+        const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + ((kb ^ x_sw) * 16));
+        const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + (((4 + kb) ^ x_sw) * 16));
+        bs[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
     } else {
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        u32x4_t af[OT];
+      for (int i = 0; i < OT; ++i)
+        af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + (((h * 4 + kb) ^ a_sw) * 16));
 #pragma unroll
-        for (int i = 0; i < OT; ++i)
-          af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row0 + i * 16 * C::A_ROW + s * 64 + kb * 16);
-#pragma unroll
-        for (int j = 0; j < TT; ++j) {
-          const u32x4_t bfrag =
-              *reinterpret_cast<const u32x4_t*>(base + x_row0 + j * 16 * C::X_ROW + s * 64 + kb * 16);
-#pragma unroll
-          for (int i = 0; i < OT; ++i)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
-                                                                __builtin_bit_cast(bf16x8_t, bfrag), acc[i][j], 0, 0,
-                                                                0);
-        }
-      }
+      for (int j = 0; j < TT; ++j)
+        bd[j] = *reinterpret_cast<const u32x4_t*>(base + x_row + j * 16 * 128 + (((h * 4 + kb) ^ x_sw) * 16));
     }
-    if (ks + 1 < nk) store_stage(buf ^ 1);
-    __syncthreads();
+  };
+  // 32 matrix instructions; when `load` is set, this wave's LPW loads of stage (lks -> lbuf) are issued
+  // between them, one every few instructions, so that the memory pipe is fed evenly instead of in bursts
+  constexpr int MMA = OT * TT;
+  constexpr int EVERY = MMA / C::LPW > 0 ? MMA / C::LPW : 1;
+  auto multiply = [&](bool load, int lks, int lbuf) {
+    [&]<int... Q>(std::integer_sequence<int, Q...>) {
+      ([&] {
+        constexpr int j = Q / OT, i = Q % OT;
+        if (SPARSE)
+          acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
+                                                                __builtin_bit_cast(bf16x16_t, bs[j]), acc[i][j],
+                                                                sel[i], 0, 0);
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
+                                                              __builtin_bit_cast(bf16x8_t, bd[j]), acc[i][j], 0, 0, 0);
+        if constexpr (Q % EVERY == EVERY - 1 && Q / EVERY < C::LPW) {
+          if (load) issue_one(std::integral_constant<int, Q / EVERY>{}, lks, lbuf);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }(), ...);
+    }(std::make_integer_sequence<int, MMA>{});
+  };
+  // stage s has landed in this wave's view once at most the loads of the younger stages issued so far
+  // are outstanding: `younger` of them (0, 1 or 2)
+  auto wait_stage = [&](int younger) {
+    if (younger >= 2) wait_loads_outstanding<2 * C::LPW>();
+    else if (younger == 1) wait_loads_outstanding<C::LPW>();
+    else wait_loads_outstanding<0>();
+  };
+
+  const int nk = (int)(a.K / C::KC);
+#pragma unroll
+  for (int s = 0; s < STAGES; ++s)
+    if (s < (PINGPONG ? STAGES : STAGES - 1) && s < nk) issue_stage(s, s);
+
+  if (!PINGPONG) {
+    // Simple schedule: one barrier per stage; the buffer multiplied in the previous step is refilled
+    // right after the barrier, STAGES-1 stages ahead.
+    int buf = 0;
+    for (int ks = 0; ks < nk; ++ks) {
+      wait_stage((STAGES == 3 && ks + 1 < nk) ? 1 : 0);
+      __builtin_amdgcn_s_barrier();
+      int nbuf = buf + STAGES - 1;
+      if (nbuf >= STAGES) nbuf -= STAGES;
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+        read_frags(buf, h);
+        multiply(h == 0 && ks + STAGES - 1 < nk, ks + STAGES - 1, nbuf);
+      }
+      if (++buf == STAGES) buf = 0;
+    }
+  } else {
+    // Ping-pong schedule.  The waves of a block form two groups (one wave of each per SIMD).  Time is
+    // cut into slots separated by block-wide barriers; group 0 reads the fragments of sub-step u in
+    // slot 2u and multiplies in slot 2u+1, group 1 does the same one slot later, so that in every
+    // slot one wave of a SIMD feeds the matrix pipe while the other one uses the LDS.
+    // Stage s occupies its buffer during slots 2sH .. 2sH+2H-1; at the start of slot 2mH (m >= 1) every
+    // wave issues the loads of stage m+STAGES-1 into the buffer stage m-1 has just left, and at the end
+    // of slot 2sH-1 every wave makes sure its share of stage s has landed.
+    const int grp = (wave >= C::NW / 2) ? 1 : 0;
+    {
+      const int issued = nk < STAGES ? nk : STAGES;
+      wait_stage(issued - 1);
+    }
+    __builtin_amdgcn_s_barrier();
+    if (grp) __builtin_amdgcn_s_barrier();  // group 1 sits out slot 0
+    int buf = 0;
+    for (int ks = 0; ks < nk; ++ks) {
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+        const bool first = (h == 0), last = (h == H - 1);
+        // younger stages in flight when stage ks+1 is awaited at the end of this stage
+        int younger = nk - (ks + 2);
+        if (younger > STAGES - 2) younger = STAGES - 2;
+        if (younger < 0) younger = 0;
+        // both groups run the same sequence; group 1 is simply one barrier behind.  The loads ride
+        // inside the multiply phases: group 0 refills the buffer stage ks-1 has left (with stage
+        // ks+STAGES-1) during its first sub-step of stage ks, group 1 refills this stage's own buffer
+        // (with stage ks+STAGES) during its last sub-step, i.e. both in the slots after 2(ks)H - 1 and
+        // 2(ks+1)H - 1 respectively, when the buffer has been read by everyone.
+        read_frags(buf, h);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (grp && last) wait_stage(younger);
+        __builtin_amdgcn_s_barrier();
+        {
+          int nbuf = buf + STAGES - 1;
+          if (nbuf >= STAGES) nbuf -= STAGES;
+          const bool ld = grp ? (last && ks + STAGES < nk) : (first && ks >= 1 && ks + STAGES - 1 < nk);
+          multiply(ld, grp ? ks + STAGES : ks + STAGES - 1, grp ? buf : nbuf);
+        }
+        if (!grp && last) wait_stage(younger);
+        __builtin_amdgcn_s_barrier();
+      }
+      if (++buf == STAGES) buf = 0;
+    }
+    if (!grp) __builtin_amdgcn_s_barrier();  // group 0 sits out the last slot
   }
 
-  // ---- epilogue: lane holds out-features o .. o+3 (accumulator i -> row 4*kb + i) of token r16
+  // ---- epilogue.  A lane holds out-features o .. o+3 (accumulator element e -> row 4*kb + e of the
+  // 16-row tile) of token r16, i.e. 8 or 16 contiguous bytes of a Y row.  For aligned outputs every
+  // wave transposes 16 tokens at a time through its own LDS slice so that the global stores are
+  // 16 bytes per lane and whole row segments of the wave tile (OW elements) are written contiguously.
+  __builtin_amdgcn_s_barrier();  // every wave is done with the operand stages
+  if (a.vec_store) {
+    constexpr int OW = OT * 16;
+    auto transpose_store = [&](auto out_tag) {
+      using out_t = decltype(out_tag);
+      constexpr int ES = (int)sizeof(out_t);
+      constexpr int RS = OW * ES + 16;        // padded LDS row: 16-byte slots of consecutive tokens differ in bank
+      constexpr int CPR = OW * ES / 16;       // 16-byte pieces per row
+      constexpr int PASSES = 16 * CPR / 64;
+      static_assert(16 * CPR % 64 == 0 && C::NW * 16 * RS <= C::LDS_BYTES, "epilogue slice");
+      unsigned char* slice = smem + wave * (16 * RS);
+      f32x4_t bias[OT];
 #pragma unroll
-  for (int j = 0; j < TT; ++j) {
-    const int64_t t = t0 + (wt * TT + j) * 16 + r16;
-    if (t >= a.T) continue;
+      for (int i = 0; i < OT; ++i) {
+        bias[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        const int64_t o = o0 + (wo * OT + i) * 16 + kb * 4;
+        if (a.bias && o < a.O) {
+          const float4 bv = *reinterpret_cast<const float4*>(a.bias + o);
+          bias[i] = f32x4_t{bv.x, bv.y, bv.z, bv.w};
+        }
+      }
 #pragma unroll
-    for (int i = 0; i < OT; ++i) {
-      const int64_t o = o0 + (wo * OT + i) * 16 + kb * 4;
-      if (o >= a.O) continue;
-      f32x4_t v = acc[i][j];
-      if (a.vec_store) {
-        if (a.bias) {
-          const float4 b = *reinterpret_cast<const float4*>(a.bias + o);
-          v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+      for (int j = 0; j < TT; ++j) {
+#pragma unroll
+        for (int i = 0; i < OT; ++i) {
+          const f32x4_t v = acc[i][j] + bias[i];
+          unsigned char* dst = slice + r16 * RS + (i * 16 + kb * 4) * ES;
+          if constexpr (ES == 2) {
+            uint2 pk;
+            pk.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+            pk.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+            *reinterpret_cast<uint2*>(dst) = pk;
+          } else {
+            *reinterpret_cast<f32x4_t*>(dst) = v;
+          }
         }
-        if (a.out_bf16) {
-          uint2 p;
-          p.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
-          p.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) = p;
-        } else {
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.Y) + t * a.ldy + o) = make_float4(v[0], v[1], v[2], v[3]);
+#pragma unroll
+        for (int pss = 0; pss < PASSES; ++pss) {
+          const int q = pss * 64 + lane;
+          const int row = q / CPR, ch = q % CPR;
+          const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(slice + row * RS + ch * 16);
+          const int64_t t = t0 + (wt * TT + j) * 16 + row;
+          const int64_t o = o0 + wo * OW + ch * (16 / ES);
+          if (t < a.T && o < a.O)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<out_t*>(a.Y) + t * a.ldy + o) = piece;
         }
-      } else {
+      }
+    };
+    if (a.out_bf16) transpose_store(bf16_t{});
+    else transpose_store(float{});
+  } else {
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+      const int64_t t = t0 + (wt * TT + j) * 16 + r16;
+      if (t >= a.T) continue;
+#pragma unroll
+      for (int i = 0; i < OT; ++i) {
+        const int64_t o = o0 + (wo * OT + i) * 16 + kb * 4;
+        const f32x4_t v = acc[i][j];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if (o + e >= a.O) break;
@@ -325,6 +501,7 @@ static bool tiles_ok(const SpmmArgs& a) {
   if (!aligned_to(a.X, 16) || (a.ldx % 8)) return false;
   if (!aligned_to(a.values, 16) || !aligned_to(a.indices, 8)) return false;
   if (a.O > (1 << 24) || a.T > (1ll << 31)) return false;
+  if (a.ldx > (1 << 22) || a.K > (1 << 22)) return false;  // per-lane byte offsets inside a tile stay below 2^32
   return true;
 }
 
@@ -337,10 +514,10 @@ size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   return (size_t)(O * K) * 2;               // dense expansion
 }
 
-template <bool SPARSE, int WO, int WT, int OT, int TT>
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, bool PINGPONG>
 static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
-  using C = GemmCfg<SPARSE, WO, WT, OT, TT>;
-  auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT>;
+  using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+  auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES, PINGPONG>;
   static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -362,9 +539,14 @@ static hipError_t dispatch_gemm(const GemmArgs& g, hipStream_t s) {
   // tile choice: large tiles when there is enough work to fill 256 CUs, smaller ones otherwise
   const int64_t tiles_big = ((g.O + 255) / 256) * ((g.T + 255) / 256);
   const int64_t tiles_mid = ((g.O + 127) / 128) * ((g.T + 127) / 128);
-  if (tiles_big >= 256) return launch_gemm<SPARSE, 2, 4, 8, 4>(g, s);
-  if (tiles_mid >= 256) return launch_gemm<SPARSE, 2, 2, 4, 4>(g, s);
-  return launch_gemm<SPARSE, 2, 2, 2, 2>(g, s);
+  static const int forced = getenv("NM_GEMM_TILE") ? atoi(getenv("NM_GEMM_TILE")) : -1;  // tuning aid
+  const int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
+  switch (pick) {
+    case 0: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, true>(g, s);
+    case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, false>(g, s);
+    case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, false>(g, s);
+    default: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, false>(g, s);
+  }
 }
 
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short) {
@@ -386,8 +568,9 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short) 
   g.O = a.O; g.K = a.K; g.T = a.T; g.ldx = a.ldx; g.ldy = a.ldy;
   g.out_bf16 = a.out_bf16;
   g.n_o_tiles = g.n_t_tiles = 0;
-  const uintptr_t y_align = a.out_bf16 ? 8 : 16;
-  g.vec_store = (a.ldy % 4 == 0) && aligned_to(a.Y, y_align) && (a.O % 4 == 0) &&
+  // 16-byte pieces of Y rows: every row start and the row end fall on a piece boundary
+  const int per_piece = a.out_bf16 ? 8 : 4;
+  g.vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
                 (a.bias == nullptr || aligned_to(a.bias, 16));
   if (a.N <= 2 && a.N < a.M) {
     if (a.N == 2 && a.M == 4) {
