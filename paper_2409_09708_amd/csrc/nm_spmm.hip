@@ -158,11 +158,15 @@ __device__ __forceinline__ void wait_loads_outstanding() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, bool PINGPONG>
+enum { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1, SCHED_STREAM = 2 };
+
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, int SCHED>
 __global__ void __launch_bounds__(WO * WT * 64)
 nm_gemm_kernel(const GemmArgs a) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+  constexpr bool PINGPONG = (SCHED == SCHED_PINGPONG);
   static_assert(!PINGPONG || (C::NW % 8 == 0), "ping-pong needs one wave of each group per SIMD");
+  static_assert(SCHED != SCHED_STREAM || (STAGES == 3 && TT % 4 == 0 && TT >= 4 && OT % 2 == 0), "stream schedule shape");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -323,9 +327,9 @@ nm_gemm_kernel(const GemmArgs a) {
   const int nk = (int)(a.K / C::KC);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s)
-    if (s < (PINGPONG ? STAGES : STAGES - 1) && s < nk) issue_stage(s, s);
+    if (s < (SCHED == SCHED_SIMPLE ? STAGES - 1 : STAGES) && s < nk) issue_stage(s, s);
 
-  if (!PINGPONG) {
+  if constexpr (SCHED == SCHED_SIMPLE) {
     // Simple schedule: one barrier per stage; the buffer multiplied in the previous step is refilled
     // right after the barrier, STAGES-1 stages ahead.
     int buf = 0;
@@ -341,7 +345,7 @@ nm_gemm_kernel(const GemmArgs a) {
       }
       if (++buf == STAGES) buf = 0;
     }
-  } else {
+  } else if constexpr (SCHED == SCHED_PINGPONG) {
     // Ping-pong schedule.  The waves of a block form two groups (one wave of each per SIMD).  Time is
     // cut into slots separated by block-wide barriers; group 0 reads the fragments of sub-step u in
     // slot 2u and multiplies in slot 2u+1, group 1 does the same one slot later, so that in every
@@ -386,6 +390,114 @@ nm_gemm_kernel(const GemmArgs a) {
       if (++buf == STAGES) buf = 0;
     }
     if (!grp) __builtin_amdgcn_s_barrier();  // group 0 sits out the last slot
+  } else {
+    // Streamed schedule: one barrier per stage, and no phase in which a wave only reads.  A wave keeps
+    // the W fragments of the current sub-step in registers and streams the X fragments through a ring
+    // of four, three ahead of the matrix instructions that consume them (four instructions per X
+    // fragment); the fragments of the next sub-step are fetched during the last groups of the current
+    // one.  Mid-way through the last sub-step of stage ks (before anything of stage ks+1 is read) every
+    // wave has issued all its reads of stage ks: it drains them, makes sure its share of stage ks+1 has
+    // landed, meets the others at the barrier and then refills the buffer of stage ks with stage ks+3,
+    // two full stages ahead of its use.
+    using bfrag_t = std::conditional_t<SPARSE, u32x8_t, u32x4_t>;
+    u32x4_t a_cur[OT], a_nxt[OT];
+    int s_cur[OT], s_nxt[OT];
+    bfrag_t bq[4];
+    auto read_a = [&](int buf, int h, int i, u32x4_t& av, int& sv) {
+      const unsigned char* base = smem + buf * C::STAGE;
+      if (SPARSE) {
+        av = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + ((kb ^ a_sw) * 16));
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_row + i * 16 * 8);
+        sv = (int)(w >> ((kb & 1) * 16));
+      } else {
+        av = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + (((h * 4 + kb) ^ a_sw) * 16));
+        sv = 0;
+      }
+    };
+    auto read_b = [&](int buf, int h, int j, bfrag_t& bv) {
+      const unsigned char* row = smem + buf * C::STAGE + x_row + j * 16 * 128;
+      if constexpr (SPARSE) {
+        const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + ((kb ^ x_sw) * 16));
+        const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + (((4 + kb) ^ x_sw) * 16));
+        bv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      } else {
+        bv = *reinterpret_cast<const u32x4_t*>(row + (((h * 4 + kb) ^ x_sw) * 16));
+      }
+    };
+    {
+      const int issued = nk < STAGES ? nk : STAGES;
+      wait_stage(issued - 1);
+    }
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < OT; ++i) read_a(0, 0, i, a_cur[i], s_cur[i]);
+#pragma unroll
+    for (int j = 0; j < 3; ++j) read_b(0, 0, j, bq[j]);
+
+    int buf = 0;
+    for (int ks = 0; ks < nk; ++ks) {
+      int nbuf = buf + 1;
+      if (nbuf == STAGES) nbuf = 0;
+      const bool more = ks + 1 < nk;       // another stage follows
+      const bool refill = ks + STAGES < nk;  // stage ks+3 exists: it goes into this stage's buffer
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+        constexpr int LASTH = H - 1;
+        const bool last = (h == LASTH);
+        const bool has_next = !last || more;
+        const int nb = last ? nbuf : buf;
+        const int nh = last ? 0 : h + 1;
+        [&]<int... J>(std::integer_sequence<int, J...>) {
+          ([&] {
+            constexpr int j = J;
+            if constexpr (j == TT - 3) {
+              if (last && more) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all reads of stage ks are back
+                wait_stage(ks + 2 < nk ? 1 : 0);
+                __builtin_amdgcn_s_barrier();
+              }
+            }
+            if constexpr (j + 3 < TT) {
+              read_b(buf, h, j + 3, bq[(j + 3) & 3]);
+            } else {
+              if (has_next) read_b(nb, nh, j + 3 - TT, bq[(j + 3) & 3]);
+            }
+            if constexpr (j >= TT - 2) {
+              if (has_next) {
+#pragma unroll
+                for (int i = (j - (TT - 2)) * (OT / 2); i < (j - (TT - 2) + 1) * (OT / 2); ++i)
+                  read_a(nb, nh, i, a_nxt[i], s_nxt[i]);
+              }
+            }
+#pragma unroll
+            for (int i = 0; i < OT; ++i) {
+              if constexpr (SPARSE)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+                                                                      __builtin_bit_cast(bf16x16_t, bq[j & 3]),
+                                                                      acc[i][j], s_cur[i], 0, 0);
+              else
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+                                                                    __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
+                                                                    0, 0, 0);
+            }
+            if constexpr (j >= TT - 3) {
+              // this wave's loads of stage ks+3, a third after each of the last three groups
+              if (last && refill) {
+                constexpr int part = j - (TT - 3);
+                constexpr int lo = part * C::LPW / 3, hi = (part + 1) * C::LPW / 3;
+                [&]<int... D>(std::integer_sequence<int, D...>) {
+                  (issue_one(std::integral_constant<int, lo + D>{}, ks + STAGES, buf), ...);
+                }(std::make_integer_sequence<int, hi - lo>{});
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }(), ...);
+        }(std::make_integer_sequence<int, TT>{});
+#pragma unroll
+        for (int i = 0; i < OT; ++i) { a_cur[i] = a_nxt[i]; s_cur[i] = s_nxt[i]; }
+      }
+      buf = nbuf;
+    }
   }
 
   // ---- epilogue.  A lane holds out-features o .. o+3 (accumulator element e -> row 4*kb + e of the
@@ -514,10 +626,10 @@ size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   return (size_t)(O * K) * 2;               // dense expansion
 }
 
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, bool PINGPONG>
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, int SCHED>
 static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
-  auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES, PINGPONG>;
+  auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES, SCHED>;
   static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -542,10 +654,13 @@ static hipError_t dispatch_gemm(const GemmArgs& g, hipStream_t s) {
   static const int forced = getenv("NM_GEMM_TILE") ? atoi(getenv("NM_GEMM_TILE")) : -1;  // tuning aid
   const int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
   switch (pick) {
-    case 0: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, true>(g, s);
-    case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, false>(g, s);
-    case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, false>(g, s);
-    default: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, false>(g, s);
+    case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_SIMPLE>(g, s);
+    case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, SCHED_SIMPLE>(g, s);
+    case 3: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, SCHED_SIMPLE>(g, s);
+    case 4: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_PINGPONG>(g, s);
+    default:
+      if constexpr (SPARSE) return launch_gemm<true, 4, 2, 4, 8, 3, SCHED_STREAM>(g, s);
+      else return launch_gemm<false, 2, 4, 8, 4, 2, SCHED_PINGPONG>(g, s);
   }
 }
 
