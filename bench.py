@@ -47,11 +47,41 @@ def build_inputs(layers, torch, wl, seed=0):
     return Ws, Xs
 
 
-def cpu_baseline(wl, seed=0, tokens=2048):
+def algorithmic_bytes(L, out_bytes=2):
+    """HBM bytes one product launch has to move: X once, the operand-order weight once, Y once."""
+    b = {4: 2, 8: 3, 16: 4}[L.M]
+    if L.N <= 2:
+        w = L.O * L.K * (2 + 2 / 8) / 2  # 2:4 operand form: half the values + 2-bit selectors
+    else:
+        w = L.O * L.K * 2                # dense operand form
+    del b
+    return 2.0 * L.T * L.K + w + out_bytes * L.T * L.O
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None
+    when the kernel source has changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_deit_b256.txt")
+    src = os.path.join(ROOT, "paper_2409_09708_amd", "csrc", "nm_spmm.hip")
+    try:
+        text = open(path).read()
+        now = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if f"nm_spmm.hip {now}" not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith("sparse_gemm_hbm_bytes_per_launch"):
+            return int(line.split()[1])
+    return None
+
+
+def cpu_baseline(wl, seed=0, tokens=16384, blocks=3):
     """The CPU checker as it stands, timed on this host on a bounded sample of the same workload: the
-    four layers of block 0 (their drawn levels) on the first `tokens` tokens: select + pack + fp64 product."""
+    4*blocks layers of the first blocks (their drawn levels) on `tokens` tokens: select + pack + fp64 product."""
     from oracle import nm_oracle as orc
-    layers = wl.deit_b_stack()[:4]
+    layers = wl.deit_b_stack()[:4 * blocks]
     rng = np.random.default_rng(seed)
     data = []
     for L in layers:
@@ -68,8 +98,8 @@ def cpu_baseline(wl, seed=0, tokens=2048):
     dt = time.perf_counter() - t0
     cores = len(os.sched_getaffinity(0))
     return {"value": useful / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"block 0 (qkv 1:16, proj 4:8, fc1 2:8, fc2 2:4) on {tokens} of 50432 tokens: "
-                      f"numpy select+pack+fp64 dense product, {dt:.2f} s"}
+            "sample": f"blocks 0-{blocks - 1} ({len(layers)} layers at their drawn levels) on {tokens} of 50432 tokens: "
+                      f"numpy select + pack + fp64 dense product, {dt:.2f} s"}
 
 
 def main():
@@ -79,6 +109,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true", help="per-layer table on stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known HBM traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -115,6 +147,12 @@ def main():
         for L, (v, i), X, Y in zip(layers, packed, Xs, Ys):
             nm.nm_spmm(v, i, L.K, L.N, L.M, X, out=Y, workspace=workspace, stream=stream)
 
+    if args.calibrate_copy:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -127,7 +165,9 @@ def main():
     useful = sum(L.useful_flops for L in layers)
     dense = sum(L.dense_flops for L in layers)
 
-    # ---- per-call durations with HIP events on the launch stream (a second pass over the same step)
+    # ---- per-kernel durations with HIP events on the launch stream: a second pass over the same step
+    # with the two halves of every product call issued separately (weight re-coding, then the product
+    # kernel alone between the events), so that the figure is the product kernel's own duration
     reps = max(3, min(args.steps, 10))
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
           for _ in range(reps)]
@@ -137,23 +177,27 @@ def main():
         nm.nm_pack_batched(pack_args, stream=stream, out=packed)
         pk[r][1].record(stream)
         for j, (L, (v, i), X, Y) in enumerate(zip(layers, packed, Xs, Ys)):
+            nm.nm_spmm_prepare(v, i, L.K, L.N, L.M, L.T, workspace=workspace, stream=stream)
             ev[r][j][0].record(stream)
-            nm.nm_spmm(v, i, L.K, L.N, L.M, X, out=Y, workspace=workspace, stream=stream)
+            nm.nm_linear_forward_prepared(v, i, L.K, L.N, L.M, X, workspace, out=Y, stream=stream)
             ev[r][j][1].record(stream)
     torch.cuda.synchronize()
     layer_ms = [float(np.median([ev[r][j][0].elapsed_time(ev[r][j][1]) for r in range(reps)])) for j in range(len(layers))]
     pack_ms = float(np.median([a.elapsed_time(b) for a, b in pk]))
 
-    # dominant kernel: the sparse matrix-core product (levels with N <= 2): 36 of the 48 launches
+    # dominant kernel: the sparse matrix-core product (levels with N <= 2): 36 of the 48 launches per step
     sp = [j for j, L in enumerate(layers) if L.N <= 2]
     sp_useful = sum(layers[j].useful_flops for j in sp)
     sp_ms = sum(layer_ms[j] for j in sp)
     achieved = sp_useful / (sp_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_DENSE_TFLOPS, "traffic": None,
-                "kernel": "nm_gemm_kernel<SPARSE> (v_smfmac_f32_16x16x64_bf16), useful FLOPs 2*T*O*K*N/M per launch",
+                "frac": achieved / PEAK_BF16_DENSE_TFLOPS, "traffic": measured_traffic(),
+                "kernel": "nm_gemm_kernel<sparse> (v_smfmac_f32_16x16x64_bf16); useful FLOPs 2*T*O*K*N/M per launch, "
+                          "averaged over the 36 launches per step with N <= 2",
                 "launches_per_step": len(sp), "avg_launch_ms": sp_ms / len(sp),
-                "dense_equivalent_tflops": sum(layers[j].dense_flops for j in sp) / (sp_ms * 1e-3) / 1e12}
+                "useful_flops_per_launch": sp_useful / len(sp),
+                "dense_equivalent_tflops": sum(layers[j].dense_flops for j in sp) / (sp_ms * 1e-3) / 1e12,
+                "algorithmic_hbm_bytes_per_launch": sum(algorithmic_bytes(layers[j]) for j in sp) / len(sp)}
 
     if args.report:
         log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}")

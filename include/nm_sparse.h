@@ -173,6 +173,28 @@ int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_
                           const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The two halves of nm_linear_forward, for callers whose weights stay fixed across many calls (a
+ * deployed layer keeps its level and weights: Section 3, the configuration alpha is chosen once):
+ *   nm_spmm_prepare             rewrites the packed weight into matrix-core operand order in the
+ *                               workspace (nothing to do, and no workspace needed, when
+ *                               nm_spmm_workspace_bytes() is 0).  T is the token count the product
+ *                               calls will use (it selects the same kernels).
+ *   nm_linear_forward_prepared  the product alone, reading a workspace that nm_spmm_prepare filled
+ *                               for the same (values, indices, O, K, N, M, T); the workspace is
+ *                               not modified, so it can serve any number of calls.
+ * nm_linear_forward(args) == nm_spmm_prepare(args) followed by nm_linear_forward_prepared(args).
+ */
+int32_t nm_spmm_prepare(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K,
+                        int32_t N, int32_t M, int64_t T,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indices, int64_t O,
+                                   int64_t K, int32_t N, int32_t M, const nm_bf16* X, int64_t T,
+                                   int64_t ldx, const float* bias, void* Y, int64_t ldy,
+                                   int32_t out_dtype, const void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

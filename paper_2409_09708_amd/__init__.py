@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     load_library,
     nm_index_bytes,
     nm_linear_forward,
+    nm_linear_forward_prepared,
+    nm_spmm_prepare,
     nm_mask_bytes,
     nm_mask_check,
     nm_pack,

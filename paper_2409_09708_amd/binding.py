@@ -20,7 +20,7 @@ NM_OUT_F32, NM_OUT_BF16 = 0, 1
 EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
-    "nm_spmm", "nm_linear_forward",
+    "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
 )
 
 
@@ -76,6 +76,11 @@ def load_library() -> ctypes.CDLL:
     lib.nm_linear_forward.restype = c_int32
     lib.nm_linear_forward.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64,
                                       c_int64, c_void_p, c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_spmm_prepare.restype = c_int32
+    lib.nm_spmm_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_int64, c_void_p, c_size_t,
+                                    c_void_p]
+    lib.nm_linear_forward_prepared.restype = c_int32
+    lib.nm_linear_forward_prepared.argtypes = lib.nm_linear_forward.argtypes
     _LIB = lib
     return lib
 
@@ -242,8 +247,30 @@ def _workspace(nbytes: int, device):
     return ws
 
 
+def nm_spmm_prepare(values, indices, K: int, N: int, M: int, T: int, workspace=None, stream=None):
+    """Fill (and return) the workspace nm_linear_forward_prepared reads; None if the level needs none."""
+    torch = _torch()
+    _need(values, torch.bfloat16, "values")
+    _need(indices, torch.int32, "indices")
+    O = int(values.shape[0])
+    need = nm_spmm_workspace_bytes(O, K, N, M, T)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=values.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().nm_spmm_prepare(values.data_ptr(), indices.data_ptr(), O, K, N, M, T, ws_ptr, ws_bytes,
+                                          _stream_handle(stream)))
+    return workspace
+
+
+def nm_linear_forward_prepared(values, indices, K: int, N: int, M: int, X, workspace, bias=None, out_dtype=None,
+                               out=None, stream=None):
+    """The product alone, from a workspace filled by nm_spmm_prepare."""
+    return nm_linear_forward(values, indices, K, N, M, X, bias, out_dtype, out, workspace, stream, _prepared=True)
+
+
 def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out_dtype=None, out=None,
-                      workspace=None, stream=None):
+                      workspace=None, stream=None, _prepared=False):
     """Y = X * W_s^T (+ bias) from the packed weight; Y is float32 (default) or bfloat16 [T, O]."""
     torch = _torch()
     _need(values, torch.bfloat16, "values")
@@ -267,6 +294,8 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
         raise ValueError("out must be [T, O]")
     need = nm_spmm_workspace_bytes(O, K, N, M, T)
     if workspace is None and need:
+        if _prepared:
+            raise ValueError("a prepared call needs the workspace nm_spmm_prepare filled")
         workspace = _workspace(need, X.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
@@ -278,7 +307,11 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
         bias_ptr = bias.data_ptr()
     code = NM_OUT_F32 if out_dtype == torch.float32 else NM_OUT_BF16
     lib = load_library()
-    if bias_ptr is None:
+    if _prepared:
+        st = lib.nm_linear_forward_prepared(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx,
+                                            bias_ptr, out.data_ptr(), ldy, code, ws_ptr, ws_bytes,
+                                            _stream_handle(stream))
+    elif bias_ptr is None:
         st = lib.nm_spmm(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx, out.data_ptr(), ldy,
                          code, ws_ptr, ws_bytes, _stream_handle(stream))
     else:

@@ -115,32 +115,63 @@ int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int
   return device_status(nm::launch_mask_check(mask, O, K, N, M, bad_groups, (hipStream_t)stream));
 }
 
-int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
-                          const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y, int64_t ldy,
-                          int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!values || !indices || !X || !Y) return NM_ERR_NULL;
+}  // extern "C"
+
+namespace {
+
+int32_t spmm_entry(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                   const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                   void* workspace, size_t workspace_bytes, void* stream, int phases) {
+  const bool product = phases & nm::SPMM_PRODUCT;
+  if (!values || !indices || (product && (!X || !Y))) return NM_ERR_NULL;
   if (int32_t s = check_weight(O, K, N, M)) return s;
-  if (T <= 0 || T > (int64_t)1 << 31 || ldx < K || ldy < O) return NM_ERR_SHAPE;
+  if (T <= 0 || T > (int64_t)1 << 31) return NM_ERR_SHAPE;
+  if (product && (ldx < K || ldy < O)) return NM_ERR_SHAPE;
   if (out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16) return NM_ERR_DTYPE;
   if (!aligned(values, 2) || !aligned(indices, 4) || !aligned(X, 2) || !aligned(bias, 4) ||
       !aligned(Y, out_dtype == NM_OUT_F32 ? 4 : 2))
     return NM_ERR_ALIGN;
   nm::SpmmArgs a;
   a.values = values; a.indices = indices; a.O = O; a.K = K; a.N = N; a.M = M;
-  a.X = X; a.T = T; a.ldx = ldx; a.bias = bias; a.Y = Y; a.ldy = ldy;
+  a.X = X; a.T = T; a.ldx = product ? ldx : K; a.bias = bias; a.Y = Y; a.ldy = ldy;
   a.out_bf16 = (out_dtype == NM_OUT_BF16);
   a.workspace = workspace; a.workspace_bytes = workspace_bytes;
   bool workspace_short = false;
-  hipError_t e = nm::launch_spmm(a, (hipStream_t)stream, &workspace_short);
+  hipError_t e = nm::launch_spmm(a, (hipStream_t)stream, &workspace_short, phases);
   if (workspace_short) return NM_ERR_WORKSPACE;
   return device_status(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                          const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y, int64_t ldy,
+                          int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  return spmm_entry(values, indices, O, K, N, M, X, T, ldx, bias, Y, ldy, out_dtype, workspace, workspace_bytes, stream,
+                    nm::SPMM_PREPARE | nm::SPMM_PRODUCT);
 }
 
 int32_t nm_spmm(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
                 const nm_bf16* X, int64_t T, int64_t ldx, void* Y, int64_t ldy, int32_t out_dtype, void* workspace,
                 size_t workspace_bytes, void* stream) {
-  return nm_linear_forward(values, indices, O, K, N, M, X, T, ldx, nullptr, Y, ldy, out_dtype, workspace,
-                           workspace_bytes, stream);
+  return spmm_entry(values, indices, O, K, N, M, X, T, ldx, nullptr, Y, ldy, out_dtype, workspace, workspace_bytes,
+                    stream, nm::SPMM_PREPARE | nm::SPMM_PRODUCT);
+}
+
+int32_t nm_spmm_prepare(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                        int64_t T, void* workspace, size_t workspace_bytes, void* stream) {
+  return spmm_entry(values, indices, O, K, N, M, nullptr, T, K, nullptr, nullptr, O, NM_OUT_F32, workspace,
+                    workspace_bytes, stream, nm::SPMM_PREPARE);
+}
+
+int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N,
+                                   int32_t M, const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y,
+                                   int64_t ldy, int32_t out_dtype, const void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  return spmm_entry(values, indices, O, K, N, M, X, T, ldx, bias, Y, ldy, out_dtype, const_cast<void*>(workspace),
+                    workspace_bytes, stream, nm::SPMM_PRODUCT);
 }
 
 }  // extern "C"

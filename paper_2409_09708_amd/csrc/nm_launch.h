@@ -42,7 +42,11 @@ struct SpmmArgs {
   size_t workspace_bytes;
 };
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);
-// returns hipSuccess or the launch error; *need_workspace is set when the workspace was required but too small
-hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short);
+// phases: SPMM_PREPARE rewrites the packed weight into matrix-core operand order in the workspace,
+// SPMM_PRODUCT multiplies (expects a prepared workspace); both = the whole call.
+// returns hipSuccess or the launch error; *workspace_short is set when the workspace is required but
+// missing, misaligned or too small (nothing is launched then)
+enum { SPMM_PREPARE = 1, SPMM_PRODUCT = 2 };
+hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases);
 
 }  // namespace nm

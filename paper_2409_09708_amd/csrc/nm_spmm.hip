@@ -664,9 +664,11 @@ static hipError_t dispatch_gemm(const GemmArgs& g, hipStream_t s) {
   }
 }
 
-hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short) {
+hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases) {
   *workspace_short = false;
+  const bool prepare = phases & SPMM_PREPARE, product = phases & SPMM_PRODUCT;
   if (!tiles_ok(a)) {
+    if (!product) return hipSuccess;  // the gather kernel reads the packed layout itself
     const int64_t n_o_tiles = (a.O + 15) / 16, n_t_tiles = (a.T + 15) / 16;
     if (n_o_tiles * n_t_tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
     hipLaunchKernelGGL(spmm_general_kernel, dim3((unsigned)(n_o_tiles * n_t_tiles)), dim3(256), 0, s, a.values,
@@ -693,33 +695,37 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short) 
     } else {
       bf16_t* v24 = reinterpret_cast<bf16_t*>(a.workspace);
       uint32_t* s24 = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(a.workspace) + (size_t)(a.O * a.K));
-      const int64_t n = a.O * (a.K / 32);
-      const dim3 grid((unsigned)((n + 255) / 256));
-      switch (a.N * 32 + a.M) {
+      if (prepare) {
+        const int64_t n = a.O * (a.K / 32);
+        const dim3 grid((unsigned)((n + 255) / 256));
+        switch (a.N * 32 + a.M) {
 #define X(n_, m_)                                                                                                 \
   case n_ * 32 + m_:                                                                                              \
     hipLaunchKernelGGL((recode_to_2of4_kernel<n_, m_>), grid, dim3(256), 0, s, a.values, a.indices, a.O, a.K, v24, s24); \
     break;
-        X(1, 4) X(1, 8) X(2, 8) X(1, 16) X(2, 16)
+          X(1, 4) X(1, 8) X(2, 8) X(1, 16) X(2, 16)
 #undef X
-        default: return hipErrorInvalidValue;
+          default: return hipErrorInvalidValue;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
       }
-      hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return e;
       g.A = v24; g.sel = s24;
     }
-    return dispatch_gemm<true>(g, s);
+    return product ? dispatch_gemm<true>(g, s) : hipSuccess;
   }
   g.sel = nullptr;
   if (a.N == a.M) {
     g.A = a.values;
   } else {
     bf16_t* wd = reinterpret_cast<bf16_t*>(a.workspace);
-    hipError_t e = launch_unpack(a.values, a.indices, a.O, a.K, a.N, a.M, wd, a.K, s);
-    if (e != hipSuccess) return e;
+    if (prepare) {
+      hipError_t e = launch_unpack(a.values, a.indices, a.O, a.K, a.N, a.M, wd, a.K, s);
+      if (e != hipSuccess) return e;
+    }
     g.A = wd;
   }
-  return dispatch_gemm<false>(g, s);
+  return product ? dispatch_gemm<false>(g, s) : hipSuccess;
 }
 
 }  // namespace nm

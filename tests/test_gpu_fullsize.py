@@ -1,0 +1,92 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (bf16 output, one
+batched pack launch, the large-tile product kernels): packed bytes are compared in full, products on
+sampled token rows that the CPU checker computes directly (first tile, last ragged tile, random rows)."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_09708_amd as nm
+from oracle import nm_oracle as orc
+from paper_2409_09708_amd import workloads as wl
+from gpu_util import check_output, dev_bf16, host_bits, host_output, host_words
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(T, rng, n=16):
+    rows = np.concatenate([np.arange(0, n), np.arange(T - n, T), rng.integers(n, T - n, size=n)])
+    return np.unique(rows)
+
+
+def check_layer_sampled(L, X, W, out_dtype, rng):
+    mask = orc.nm_mask(W, L.N, L.M)
+    vals, idx = orc.nm_pack(W, mask, L.N, L.M)
+    v, i = nm.nm_pack(dev_bf16(W), L.N, L.M)
+    assert np.array_equal(host_bits(v), vals), L
+    assert np.array_equal(host_words(i), idx), L
+    Y = nm.nm_spmm(v, i, L.K, L.N, L.M, dev_bf16(X), out_dtype=out_dtype)
+    rows = sample_rows(L.T, rng)
+    Yref, B = orc.nm_linear(X[rows], W, mask)
+    Ys = host_output(Y[torch.from_numpy(rows).cuda()])
+    return check_output(Ys, Yref, B, L.K // L.M * L.N, out_dtype == torch.float32, str(L))
+
+
+DEIT_B256 = [  # (name, K, O, level): every level of the batch-256 configuration on every layer shape it can meet
+    ("qkv", 768, 2304, (1, 16)), ("qkv", 768, 2304, (4, 8)), ("proj", 768, 768, (2, 8)), ("proj", 768, 768, (4, 16)),
+    ("fc1", 768, 3072, (1, 4)), ("fc1", 768, 3072, (2, 4)), ("fc2", 3072, 768, (2, 4)), ("fc2", 3072, 768, (1, 8)),
+]
+
+
+@pytest.mark.parametrize("name,K,O,level", DEIT_B256)
+def test_deit_b_batch256_layers_sampled(name, K, O, level):
+    T = 256 * 197
+    rng = np.random.default_rng(zlib.crc32(f"{name}-{level}".encode()))
+    L = wl.Layer(name, T, K, O, *level)
+    X = wl.draw_activations(rng, T, K)
+    W = wl.draw_weights(rng, O, K)
+    check_layer_sampled(L, X, W, torch.bfloat16, rng)
+
+
+def test_deit_b_batch256_fp32_output_sampled():
+    rng = np.random.default_rng(77)
+    L = wl.Layer("proj", 256 * 197, 768, 768, 2, 4)
+    check_layer_sampled(L, wl.draw_activations(rng, L.T, L.K), wl.draw_weights(rng, L.O, L.K), torch.float32, rng)
+
+
+def test_deit_b_block_batch64_seeded_levels():
+    # the four linears of one block at 12608 tokens, levels drawn with seed 0 (4:8, 2:8, 1:8, 2:4)
+    rng = np.random.default_rng(5)
+    layers = wl.deit_b_block(batch=64, seed=0)
+    assert [(L.N, L.M) for L in layers] == [(4, 8), (2, 8), (1, 8), (2, 4)]
+    for L, X, W in wl.draw_layers(layers, seed=0):
+        check_layer_sampled(L, X, W, torch.bfloat16, rng)
+
+
+def test_swin_b_stage_shapes_sampled():
+    # one block per stage at batch 64: 200704 / 50176 / 12544 / 3136 tokens, widths 128 / 256 / 512 / 1024
+    rng = np.random.default_rng(6)
+    layers = wl.swin_b_stages(batch=64, seed=0)
+    picks = [layers[0], layers[3], layers[6], layers[9], layers[12], layers[15]]  # qkv/fc2 of stage 0, fc1 s1, proj s2, qkv/fc2 s3
+    for L, X, W in wl.draw_layers(picks, seed=1):
+        check_layer_sampled(L, X, W, torch.bfloat16, rng)
+
+
+def test_batched_pack_of_the_whole_stack_matches_single_calls_and_the_checker():
+    # all 48 DeiT-B weights in one launch, as the benchmark does; every matrix equals its single-call result,
+    # and one matrix per level is compared with the CPU checker in full
+    layers = wl.deit_b_stack(batch=256, seed=0)
+    rng = np.random.default_rng(0)
+    Ws = [dev_bf16(wl.draw_weights(rng, L.O, L.K)) for L in layers]
+    outs = nm.nm_pack_batched([(W, L.N, L.M) for W, L in zip(Ws, layers)])
+    seen = set()
+    for W, L, (v, i) in zip(Ws, layers, outs):
+        v1, i1 = nm.nm_pack(W, L.N, L.M)
+        assert torch.equal(v.view(torch.int16), v1.view(torch.int16)) and torch.equal(i, i1), L
+        if (L.N, L.M) not in seen:
+            seen.add((L.N, L.M))
+            Wh = host_bits(W)
+            vals, idx = orc.nm_pack(Wh, orc.nm_mask(Wh, L.N, L.M), L.N, L.M)
+            assert np.array_equal(host_bits(v), vals) and np.array_equal(host_words(i), idx), L
+    assert len(seen) == 7

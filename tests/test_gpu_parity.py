@@ -253,3 +253,21 @@ def test_one_token_and_one_row_edges():
         Yref, B = orc.nm_linear_from_bits(X, W, N, M)
         Y = host_output(run_layer(X, W, N, M, torch.float32))
         check_output(Y, Yref, B, K // M * N, True, (T, K, O, N, M))
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (1, 16), (4, 8), (8, 8)])
+def test_prepare_then_prepared_equals_the_single_call(N, M):
+    rng = np.random.default_rng(4700 + N + M)
+    T, K, O = 300, 256, 272
+    X = dev_bf16(wl.draw_activations(rng, T, K))
+    v, i = nm.nm_pack(dev_bf16(wl.draw_weights(rng, O, K)), N, M)
+    bias = torch.from_numpy(rng.standard_normal(O).astype(np.float32)).cuda()
+    whole = nm.nm_linear_forward(v, i, K, N, M, X, bias=bias)
+    ws = nm.nm_spmm_prepare(v, i, K, N, M, T)
+    assert (ws is None) == (nm.nm_spmm_workspace_bytes(O, K, N, M, T) == 0)
+    snapshot = None if ws is None else ws.clone()
+    for _ in range(2):  # the prepared workspace serves any number of calls and is not modified
+        part = nm.nm_linear_forward_prepared(v, i, K, N, M, X, ws, bias=bias)
+        assert torch.equal(whole, part)
+    if ws is not None:
+        assert torch.equal(ws, snapshot)

@@ -137,6 +137,22 @@ def test_spmm_argument_errors(lib):
     assert lf == 4  # bias must be 4-byte aligned
 
 
+def test_prepare_and_prepared_argument_errors(lib):
+    need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 16)
+    assert lib.nm_spmm_prepare(None, FAKE, 64, 64, 1, 8, 16, FAKE, need, None) == 1
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 9, 8, 16, FAKE, need, None) == 3
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 60, 1, 8, 16, FAKE, need, None) == 2
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 0, FAKE, need, None) == 2
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 16, None, 0, None) == 6
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 16, FAKE, need - 1, None) == 6
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 2, 4, 16, None, 0, None) == 0   # nothing to prepare at 2:4
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 8, 24, 1, 8, 16, None, 0, None) == 0    # general kernel: no scratch
+    args = (FAKE, FAKE, 64, 64, 1, 8, FAKE, 16, 64, None, FAKE, 64, 0)
+    assert lib.nm_linear_forward_prepared(*args, None, 0, None) == 6
+    assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, None, 16, 64, None, FAKE, 64, 0, FAKE, need, None) == 1
+    assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, FAKE, 16, 32, None, FAKE, 64, 0, FAKE, need, None) == 2
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "_PKG_DIR", str(tmp_path))
