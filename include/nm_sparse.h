@@ -86,9 +86,10 @@ size_t nm_index_bytes(int64_t O, int64_t K, int32_t N, int32_t M);
 size_t nm_mask_bytes(int64_t O, int64_t K);
 
 /* Scratch needed by nm_spmm / nm_linear_forward for this layer and token count (bytes,
- * possibly 0).  The product kernels consume the weight in matrix-core operand order; for
- * levels whose packed layout is not already that order the call first rewrites the packed
- * weight into the scratch.  0 if the level or shape is illegal. */
+ * possibly 0).  The product kernels consume the weight in matrix-core operand order, which
+ * depends on the kernel the token count selects; whenever the packed layout is not already
+ * that order the call first rewrites the packed weight into the scratch (large layers: always).
+ * 0 if the level or shape is illegal. */
 size_t nm_spmm_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M, int64_t T);
 
 /*

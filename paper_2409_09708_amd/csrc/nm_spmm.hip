@@ -82,6 +82,99 @@ recode_to_2of4_kernel(const bf16_t* __restrict__ values, const uint32_t* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// Pre-pass for the persistent kernel: the weight in "stream order", i.e. exactly the LDS image
+// of every (16-row group, K step) as one contiguous 1 KB block, so that the product kernel's
+// loads are whole contiguous kilobytes (a 16-row x 64-byte slice of a row-major weight touches 16
+// cache lines for one kilobyte, and the selector words one line per 8 bytes).
+//   values/dense block (rg, ks) at ((rg * nk) + ks) * 1024: piece i (16 bytes) = row 16*rg + i/4,
+//     16-byte chunk (i & 3) ^ ((i >> 4) & 3) of that row's 64 bytes of step ks  (the XOR is the
+//     LDS swizzle; a step is 32 compressed values = 64 dense k, or 32 dense weights)
+//   selector block (o_tile, ks) at ((o_tile * nk) + ks) * 2048: row r of the tile at r*8, 2 words
+// Rows from O up to the next multiple of 256 are written as zeros.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t stream_piece_offset(int64_t row, int64_t step, int chunk, int64_t nk) {
+  const int r = (int)(row & 15);
+  return (((row >> 4) * nk + step) << 10) + ((r * 4 + (chunk ^ ((r >> 2) & 3))) << 4);
+}
+
+template <int N, int M>
+__global__ void __launch_bounds__(256)
+recode_stream_kernel(const bf16_t* __restrict__ values, const uint32_t* __restrict__ indices, int64_t O, int64_t O_pad,
+                     int64_t K, unsigned char* __restrict__ vals_s, unsigned char* __restrict__ sel_s) {
+  constexpr int B = log2_of(M);
+  constexpr int G = 32 / M;
+  constexpr int RUNS = M / 4;
+  const int64_t per_row = K / 32;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O_pad * per_row) return;
+  const int64_t o = id / per_row, blk = id % per_row;
+  uint32_t out[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out[i] = 0;
+  uint32_t sel = 0;
+  if (o < O) {
+    const int64_t nf = K / M * N;
+    const int64_t nw = (nf * B + 31) / 32;
+    const int64_t f0 = blk * G * N;
+    const uint32_t fields = stream_bits(indices + o * nw, nw, f0 * B, G * N * B);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      uint32_t prev_run = 0xFFFFFFFFu;
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        const uint32_t p = (fields >> ((g * N + j) * B)) & (M - 1);
+        const uint32_t v = values[o * nf + f0 + g * N + j];
+        const uint32_t run = p >> 2, within = p & 3u;
+        const uint32_t second = (run == prev_run) ? 1u : 0u;
+        prev_run = run;
+#pragma unroll
+        for (int r = 0; r < RUNS; ++r) out[g * RUNS + r] |= (run == (uint32_t)r) ? (v << (16 * second)) : 0u;
+        sel |= within << (4 * (g * RUNS + run) + 2 * second);
+      }
+    }
+  }
+  // 32 weights = 16 slots = chunks 2*half, 2*half+1 of step blk/2
+  const int64_t nk = K / 64, ks = blk >> 1;
+  const int half = (int)(blk & 1);
+  *reinterpret_cast<uint4*>(vals_s + stream_piece_offset(o, ks, 2 * half, nk)) = make_uint4(out[0], out[1], out[2], out[3]);
+  *reinterpret_cast<uint4*>(vals_s + stream_piece_offset(o, ks, 2 * half + 1, nk)) = make_uint4(out[4], out[5], out[6], out[7]);
+  *reinterpret_cast<uint32_t*>(sel_s + (((o >> 8) * nk + ks) << 11) + (o & 255) * 8 + half * 4) = sel;
+}
+
+// dense form: one lane per 8 consecutive weights (one 16-byte piece)
+__global__ void __launch_bounds__(256)
+expand_stream_kernel(const bf16_t* __restrict__ values, const uint32_t* __restrict__ indices, int64_t O, int64_t O_pad,
+                     int64_t K, int N, int M, unsigned char* __restrict__ dense_s) {
+  const int64_t per_row = K / 8;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O_pad * per_row) return;
+  const int64_t o = id / per_row, pc = id % per_row;
+  uint32_t w[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) w[i] = 0;
+  if (o < O) {
+    const int b = log2_of(M);
+    const int64_t nf = K / M * N;
+    const int64_t nw = (nf * b + 31) / 32;
+    const uint32_t* row = indices + o * nw;
+    const int64_t k0 = pc * 8;
+    const int64_t g_first = k0 / M, g_last = (k0 + 7) / M;
+    for (int64_t g = g_first; g <= g_last; ++g) {
+      for (int j = 0; j < N; ++j) {
+        const int64_t f = g * N + j;
+        const int64_t k = g * M + stream_bits(row, nw, f * b, b);
+        const uint32_t v = values[o * nf + f];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = (k == k0 + i) ? v : w[i];
+      }
+    }
+  }
+  const int64_t nk = K / 32, ks = pc >> 2;
+  *reinterpret_cast<uint4*>(dense_s + stream_piece_offset(o, ks, (int)(pc & 3), nk)) =
+      make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+}
+
+// ---------------------------------------------------------------------------------------------
 // Tiled matrix-core product.
 //
 // Operand tiles travel global -> LDS directly (global_load_lds_dwordx4: each lane names its own
@@ -153,12 +246,38 @@ __device__ __forceinline__ void dma4(uniform_ptr_t base, uint32_t lane_byte_offs
                "s"(base)
                : "memory", "m0");
 }
+// Two floats to a pair of bfloat16 (round to nearest even) with the hardware conversion; lo in bits 0..15.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 hwbf16x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, hwbf16x2_t));
+}
+
+// Accumulator start value of the 16 x 16 block whose four out-features start at o: the bias (so
+// that no load sits between the stores of the epilogue), or zero.
+__device__ __forceinline__ f32x4_t bias_init(const float* bias, int64_t o, int64_t O, bool vec) {
+  f32x4_t v = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  if (bias) {
+    if (vec) {
+      if (o < O) {
+        const float4 b = *reinterpret_cast<const float4*>(bias + o);
+        v = f32x4_t{b.x, b.y, b.z, b.w};
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (o + e < O) v[e] = bias[o + e];
+    }
+  }
+  return v;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_loads_outstanding() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-enum { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1, SCHED_STREAM = 2 };
+enum { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1 };
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, int SCHED>
 __global__ void __launch_bounds__(WO * WT * 64)
@@ -166,7 +285,7 @@ nm_gemm_kernel(const GemmArgs a) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
   constexpr bool PINGPONG = (SCHED == SCHED_PINGPONG);
   static_assert(!PINGPONG || (C::NW % 8 == 0), "ping-pong needs one wave of each group per SIMD");
-  static_assert(SCHED != SCHED_STREAM || (STAGES == 3 && TT % 4 == 0 && TT >= 4 && OT % 2 == 0), "stream schedule shape");
+  static_assert(SCHED == SCHED_SIMPLE || SCHED == SCHED_PINGPONG, "schedules of this kernel");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -248,9 +367,11 @@ nm_gemm_kernel(const GemmArgs a) {
 
   f32x4_t acc[OT][TT];
 #pragma unroll
-  for (int i = 0; i < OT; ++i)
+  for (int i = 0; i < OT; ++i) {
+    const f32x4_t b = bias_init(a.bias, o0 + (wo * OT + i) * 16 + kb * 4, a.O, a.vec_store);
 #pragma unroll
-    for (int j = 0; j < TT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < TT; ++j) acc[i][j] = b;
+  }
 
   // fragment read offsets inside a stage (the XOR undoes the swizzle applied by the loads)
   const int x_sw = r16 & 7;
@@ -390,114 +511,6 @@ nm_gemm_kernel(const GemmArgs a) {
       if (++buf == STAGES) buf = 0;
     }
     if (!grp) __builtin_amdgcn_s_barrier();  // group 0 sits out the last slot
-  } else {
-    // Streamed schedule: one barrier per stage, and no phase in which a wave only reads.  A wave keeps
-    // the W fragments of the current sub-step in registers and streams the X fragments through a ring
-    // of four, three ahead of the matrix instructions that consume them (four instructions per X
-    // fragment); the fragments of the next sub-step are fetched during the last groups of the current
-    // one.  Mid-way through the last sub-step of stage ks (before anything of stage ks+1 is read) every
-    // wave has issued all its reads of stage ks: it drains them, makes sure its share of stage ks+1 has
-    // landed, meets the others at the barrier and then refills the buffer of stage ks with stage ks+3,
-    // two full stages ahead of its use.
-    using bfrag_t = std::conditional_t<SPARSE, u32x8_t, u32x4_t>;
-    u32x4_t a_cur[OT], a_nxt[OT];
-    int s_cur[OT], s_nxt[OT];
-    bfrag_t bq[4];
-    auto read_a = [&](int buf, int h, int i, u32x4_t& av, int& sv) {
-      const unsigned char* base = smem + buf * C::STAGE;
-      if (SPARSE) {
-        av = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + ((kb ^ a_sw) * 16));
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_row + i * 16 * 8);
-        sv = (int)(w >> ((kb & 1) * 16));
-      } else {
-        av = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + (((h * 4 + kb) ^ a_sw) * 16));
-        sv = 0;
-      }
-    };
-    auto read_b = [&](int buf, int h, int j, bfrag_t& bv) {
-      const unsigned char* row = smem + buf * C::STAGE + x_row + j * 16 * 128;
-      if constexpr (SPARSE) {
-        const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + ((kb ^ x_sw) * 16));
-        const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + (((4 + kb) ^ x_sw) * 16));
-        bv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      } else {
-        bv = *reinterpret_cast<const u32x4_t*>(row + (((h * 4 + kb) ^ x_sw) * 16));
-      }
-    };
-    {
-      const int issued = nk < STAGES ? nk : STAGES;
-      wait_stage(issued - 1);
-    }
-    __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int i = 0; i < OT; ++i) read_a(0, 0, i, a_cur[i], s_cur[i]);
-#pragma unroll
-    for (int j = 0; j < 3; ++j) read_b(0, 0, j, bq[j]);
-
-    int buf = 0;
-    for (int ks = 0; ks < nk; ++ks) {
-      int nbuf = buf + 1;
-      if (nbuf == STAGES) nbuf = 0;
-      const bool more = ks + 1 < nk;       // another stage follows
-      const bool refill = ks + STAGES < nk;  // stage ks+3 exists: it goes into this stage's buffer
-#pragma unroll
-      for (int h = 0; h < H; ++h) {
-        constexpr int LASTH = H - 1;
-        const bool last = (h == LASTH);
-        const bool has_next = !last || more;
-        const int nb = last ? nbuf : buf;
-        const int nh = last ? 0 : h + 1;
-        [&]<int... J>(std::integer_sequence<int, J...>) {
-          ([&] {
-            constexpr int j = J;
-            if constexpr (j == TT - 3) {
-              if (last && more) {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all reads of stage ks are back
-                wait_stage(ks + 2 < nk ? 1 : 0);
-                __builtin_amdgcn_s_barrier();
-              }
-            }
-            if constexpr (j + 3 < TT) {
-              read_b(buf, h, j + 3, bq[(j + 3) & 3]);
-            } else {
-              if (has_next) read_b(nb, nh, j + 3 - TT, bq[(j + 3) & 3]);
-            }
-            if constexpr (j >= TT - 2) {
-              if (has_next) {
-#pragma unroll
-                for (int i = (j - (TT - 2)) * (OT / 2); i < (j - (TT - 2) + 1) * (OT / 2); ++i)
-                  read_a(nb, nh, i, a_nxt[i], s_nxt[i]);
-              }
-            }
-#pragma unroll
-            for (int i = 0; i < OT; ++i) {
-              if constexpr (SPARSE)
-                acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
-                                                                      __builtin_bit_cast(bf16x16_t, bq[j & 3]),
-                                                                      acc[i][j], s_cur[i], 0, 0);
-              else
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
-                                                                    __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
-                                                                    0, 0, 0);
-            }
-            if constexpr (j >= TT - 3) {
-              // this wave's loads of stage ks+3, a third after each of the last three groups
-              if (last && refill) {
-                constexpr int part = j - (TT - 3);
-                constexpr int lo = part * C::LPW / 3, hi = (part + 1) * C::LPW / 3;
-                [&]<int... D>(std::integer_sequence<int, D...>) {
-                  (issue_one(std::integral_constant<int, lo + D>{}, ks + STAGES, buf), ...);
-                }(std::make_integer_sequence<int, hi - lo>{});
-              }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-          }(), ...);
-        }(std::make_integer_sequence<int, TT>{});
-#pragma unroll
-        for (int i = 0; i < OT; ++i) { a_cur[i] = a_nxt[i]; s_cur[i] = s_nxt[i]; }
-      }
-      buf = nbuf;
-    }
   }
 
   // ---- epilogue.  A lane holds out-features o .. o+3 (accumulator element e -> row 4*kb + e of the
@@ -515,26 +528,16 @@ nm_gemm_kernel(const GemmArgs a) {
       constexpr int PASSES = 16 * CPR / 64;
       static_assert(16 * CPR % 64 == 0 && C::NW * 16 * RS <= C::LDS_BYTES, "epilogue slice");
       unsigned char* slice = smem + wave * (16 * RS);
-      f32x4_t bias[OT];
-#pragma unroll
-      for (int i = 0; i < OT; ++i) {
-        bias[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        const int64_t o = o0 + (wo * OT + i) * 16 + kb * 4;
-        if (a.bias && o < a.O) {
-          const float4 bv = *reinterpret_cast<const float4*>(a.bias + o);
-          bias[i] = f32x4_t{bv.x, bv.y, bv.z, bv.w};
-        }
-      }
 #pragma unroll
       for (int j = 0; j < TT; ++j) {
 #pragma unroll
         for (int i = 0; i < OT; ++i) {
-          const f32x4_t v = acc[i][j] + bias[i];
+          const f32x4_t v = acc[i][j];
           unsigned char* dst = slice + r16 * RS + (i * 16 + kb * 4) * ES;
           if constexpr (ES == 2) {
             uint2 pk;
-            pk.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
-            pk.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+            pk.x = pack_bf16x2(v[0], v[1]);
+            pk.y = pack_bf16x2(v[2], v[3]);
             *reinterpret_cast<uint2*>(dst) = pk;
           } else {
             *reinterpret_cast<f32x4_t*>(dst) = v;
@@ -566,10 +569,319 @@ nm_gemm_kernel(const GemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if (o + e >= a.O) break;
-          float y = v[e];
-          if (a.bias) y += a.bias[o + e];
+          const float y = v[e];
           if (a.out_bf16) reinterpret_cast<bf16_t*>(a.Y)[t * a.ldy + o + e] = (bf16_t)f32_to_bf16_rne(y);
           else reinterpret_cast<float*>(a.Y)[t * a.ldy + o + e] = y;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Persistent streamed product for large layers.
+//
+// One block of 8 waves (4 along O x 2 along T, 64 x 128 outputs each) per CU walks over its share of
+// the 256 x 256 output tiles; the LDS stage ring and the load pipeline run across tile boundaries,
+// so the first stages of the next tile are already in flight (and its first fragments in registers)
+// while the current tile is being written out, and the stores of one tile drain while the next one
+// is multiplied.  A K step is 32 matrix instructions per wave for both operand forms: K = 64 of
+// the 2:4 form through v_smfmac_f32_16x16x64_bf16, K = 32 of the dense form through
+// v_mfma_f32_16x16x32_bf16.
+// Per step a wave keeps its 4 W fragments in registers and streams the 8 X fragments through a ring
+// of four, three ahead of the instructions that consume them; the fragments of the next step are
+// fetched during the last groups of the current one.  Before anything of stage g+1 is read (group
+// TT-3 of stage g) every wave has issued all its reads of stage g: it drains them, makes sure its
+// share of stage g+1 has landed, meets the others at the step's only barrier and then refills the
+// buffer of stage g with stage g+3, two full steps ahead of its use.
+// The weight arrives in stream order (see the pre-pass above): every W load is one contiguous
+// kilobyte.  A ragged last token tile is shifted back inside X (it recomputes a few rows of its
+// neighbour but stores only its own) and the weight is zero-padded to whole tiles, so every tile is
+// full and lane offsets never change.
+// ---------------------------------------------------------------------------------------------
+template <bool SPARSE>
+struct StreamCfg {
+  static constexpr int WO = 4, WT = 2, OT = 4, TT = 8, NW = 8, NT = 512, BO = 256, BT = 256, STAGES = 3;
+  static constexpr int KSTEP = SPARSE ? 64 : 32;         // dense k per stage
+  static constexpr int X_ROWB = KSTEP * 2;               // bytes of one X row per stage
+  static constexpr int A_ROWB = 64;                      // 32 compressed values, or 32 dense weights
+  static constexpr int X_BYTES = BT * X_ROWB;
+  static constexpr int A_BYTES = BO * A_ROWB;
+  static constexpr int S_BYTES = SPARSE ? BO * 8 : 0;
+  static constexpr int STAGE = X_BYTES + A_BYTES + S_BYTES;
+  static constexpr int BIAS0 = STAGES * STAGE;           // one bias slice (BO floats) per stage buffer
+  static constexpr int LDS_BYTES = BIAS0 + STAGES * BO * 4;
+  static constexpr int X_PW = X_BYTES / 1024 / NW;
+  static constexpr int A_PW = A_BYTES / 1024 / NW;
+  static constexpr int S_PW = SPARSE ? S_BYTES / 256 / NW : 0;
+  static constexpr int LPW = X_PW + A_PW + S_PW;
+  static_assert(S_PW <= 1, "one selector load per wave");
+  static_assert(BO * 4 == 1024, "the bias slice of a tile is one wave-load");
+  static_assert(LDS_BYTES <= 160 * 1024 && STAGES * (LPW + 1) < 64, "LDS budget and vmcnt range");
+};
+
+template <bool SPARSE>
+__global__ void __launch_bounds__(512)
+nm_stream_kernel(const GemmArgs a) {
+  using C = StreamCfg<SPARSE>;
+  constexpr int OT = C::OT, TT = C::TT, STAGES = C::STAGES;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+  // ---- this block's tiles: every XCD (block id mod 8) owns a contiguous range of tiles, out-feature
+  // tiles fastest, and its blocks take them round-robin, so that the blocks sharing an L2 work on
+  // neighbouring tiles (same X rows) at the same time
+  const int n_tiles = a.n_o_tiles * a.n_t_tiles;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int slots = (int)(gridDim.x >> 3);
+  const int xcd_first = (int)(blockIdx.x & 7) * per_xcd;
+  int xcd_end = xcd_first + per_xcd;
+  if (xcd_end > n_tiles) xcd_end = n_tiles;
+  const int first = xcd_first + (int)(blockIdx.x >> 3);
+  if (first >= xcd_end) return;
+  const int my_tiles = (xcd_end - first + slots - 1) / slots;
+  const int nk = (int)(a.K / C::KSTEP);
+  const int total = my_tiles * nk;  // stages this block goes through
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wo = wave & 3;
+  const int wt = wave >> 2;
+  const int r16 = lane & 15;
+  const int kb = lane >> 4;
+
+  // ---- fixed per-lane source offsets and per-wave LDS destinations of this wave's loads
+  uint32_t x_voff[C::X_PW];
+  uint32_t x_dst[C::X_PW], a_dst[C::A_PW];
+  int a_grp[C::A_PW];  // 16-row group (within the tile) each W load brings
+#pragma unroll
+  for (int i = 0; i < C::X_PW; ++i) {
+    const int j = wave + i * C::NW;
+    int row, c;
+    if (SPARSE) { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (row & 7); }
+    else { row = 16 * j + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
+    x_voff[i] = (uint32_t)(((int64_t)row * a.ldx + c * 8) * 2);
+    x_dst[i] = (uint32_t)(j * 1024);
+  }
+#pragma unroll
+  for (int i = 0; i < C::A_PW; ++i) {
+    a_grp[i] = wave + i * C::NW;
+    a_dst[i] = (uint32_t)(C::X_BYTES + a_grp[i] * 1024);
+  }
+  const uint32_t w_voff = (uint32_t)(lane * 16);  // W pieces and selector words are contiguous per load
+  const uint32_t s_voff = (uint32_t)(lane * 4);
+  const uint32_t s_dst = (uint32_t)(C::X_BYTES + C::A_BYTES + wave * 256);
+
+  // ---- tile origins; load cursor = the stage to be issued next (tile number in this block, k step)
+  auto tile_origin = [&](int n, int& o_tile, int64_t& t_lo, int64_t& t0) {
+    const int tile = first + n * slots;
+    o_tile = tile % a.n_o_tiles;
+    t_lo = (int64_t)(tile / a.n_o_tiles) * C::BT;
+    t0 = t_lo + C::BT <= a.T ? t_lo : a.T - C::BT;
+  };
+  const unsigned char* const w_all = reinterpret_cast<const unsigned char*>(a.A);
+  const unsigned char* const s_all = reinterpret_cast<const unsigned char*>(a.sel);
+  int cur_n = 0, cur_ks = 0;
+  uint32_t cur_bias_voff = 0;
+  const bf16_t* cur_x = nullptr;
+  const unsigned char* cur_w = nullptr;  // stream-order blocks of the tile's first 16-row group
+  const unsigned char* cur_s = nullptr;
+  auto cursor_tile = [&](int n) {
+    int o_tile;
+    int64_t t_lo, t0;
+    tile_origin(n, o_tile, t_lo, t0);
+    cur_x = a.X + t0 * a.ldx;
+    cur_w = w_all + (((int64_t)o_tile * 16 * nk) << 10);
+    cur_s = SPARSE ? s_all + (((int64_t)o_tile * nk) << 11) : nullptr;
+    // bias[o0 + 4 lane ..]: past the last out-feature re-read the last four (never stored)
+    const int64_t ob = (int64_t)o_tile * C::BO + lane * 4;
+    cur_bias_voff = (uint32_t)((ob + 4 <= a.O ? ob : a.O - 4) * 4);
+    cur_n = n;
+    cur_ks = 0;
+  };
+  auto cursor_advance = [&]() {
+    if (++cur_ks == nk && cur_n + 1 < my_tiles) cursor_tile(cur_n + 1);
+  };
+  // the d-th of this wave's LPW loads of the cursor's stage into LDS buffer buf
+  auto issue_one = [&](auto d_tag, int buf) {
+    constexpr int d = decltype(d_tag)::value;
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
+    if constexpr (d == 0) {
+      // a tile's first stage brings the tile's bias slice along (older than the stage's own loads, so
+      // every wait that covers the stage covers it)
+      if (a.bias != nullptr && cur_ks == 0 && wave == 0)
+        dma16(make_uniform(a.bias), cur_bias_voff,
+              __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(C::BIAS0 + buf * (C::BO * 4))));
+    }
+    if constexpr (d < C::X_PW) {
+      dma16(make_uniform(cur_x + (int64_t)cur_ks * C::KSTEP), x_voff[d], lds + x_dst[d]);
+    } else if constexpr (d < C::X_PW + C::A_PW) {
+      constexpr int q = d - C::X_PW;
+      dma16(make_uniform(cur_w + ((((int64_t)a_grp[q] * nk) + cur_ks) << 10)), w_voff, lds + a_dst[q]);
+    } else {
+      dma4(make_uniform(cur_s + ((int64_t)cur_ks << 11) + wave * 256), s_voff, lds + s_dst);
+    }
+  };
+  auto wait_stage = [&](int younger) {
+    if (younger >= 2) wait_loads_outstanding<2 * C::LPW>();
+    else if (younger == 1) wait_loads_outstanding<C::LPW>();
+    else wait_loads_outstanding<0>();
+  };
+
+  // ---- fragment readers (the XOR undoes the swizzle applied by the loads)
+  using bfrag_t = std::conditional_t<SPARSE, u32x8_t, u32x4_t>;
+  const int a_off = C::X_BYTES + (wo * 64 + r16) * C::A_ROWB + ((kb ^ ((r16 >> 2) & 3)) * 16);
+  const int s_off = C::X_BYTES + C::A_BYTES + (wo * 64 + r16) * 8 + (kb >> 1) * 4;
+  const int x_row = (wt * 128 + r16) * C::X_ROWB;
+  const int x_lo = SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16);
+  const int x_hi = ((4 + kb) ^ (r16 & 7)) * 16;
+  auto read_a = [&](int buf, int i, u32x4_t& av, int& sv) {
+    const unsigned char* base = smem + buf * C::STAGE;
+    av = *reinterpret_cast<const u32x4_t*>(base + a_off + i * 16 * C::A_ROWB);
+    if (SPARSE) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_off + i * 16 * 8);
+      sv = (int)(w >> ((kb & 1) * 16));
+    } else {
+      sv = 0;
+    }
+  };
+  auto read_b = [&](int buf, int j, bfrag_t& bv) {
+    const unsigned char* row = smem + buf * C::STAGE + x_row + j * 16 * C::X_ROWB;
+    if constexpr (SPARSE) {
+      const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + x_lo);
+      const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + x_hi);
+      bv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    } else {
+      bv = *reinterpret_cast<const u32x4_t*>(row + x_lo);
+    }
+  };
+
+  // ---- prologue: three stages in flight, the first one landed, its first fragments in registers
+  cursor_tile(0);
+#pragma unroll
+  for (int s = 0; s < STAGES; ++s) {
+    if (s < total) {
+      [&]<int... D>(std::integer_sequence<int, D...>) {
+        (issue_one(std::integral_constant<int, D>{}, s), ...);
+      }(std::make_integer_sequence<int, C::LPW>{});
+      cursor_advance();
+    }
+  }
+  wait_stage((total < STAGES ? total : STAGES) - 1);
+  __builtin_amdgcn_s_barrier();
+
+  u32x4_t a_cur[OT], a_nxt[OT];
+  int s_cur[OT], s_nxt[OT];
+  bfrag_t bq[4];
+#pragma unroll
+  for (int i = 0; i < OT; ++i) read_a(0, i, a_cur[i], s_cur[i]);
+#pragma unroll
+  for (int j = 0; j < 3; ++j) read_b(0, j, bq[j]);
+
+  int buf = 0;
+  int g = 0;  // stage number within this block
+  for (int n = 0; n < my_tiles; ++n) {
+    int o_tile;
+    int64_t t_lo, t0;
+    tile_origin(n, o_tile, t_lo, t0);
+    const int64_t o0 = (int64_t)o_tile * C::BO;
+    f32x4_t acc[OT][TT];
+#pragma unroll
+    for (int i = 0; i < OT; ++i) {
+      // the accumulators start from the bias, which came with the tile's first stage
+      f32x4_t b = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (a.bias != nullptr)
+        b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + buf * (C::BO * 4) + (wo * 64 + i * 16 + kb * 4) * 4);
+#pragma unroll
+      for (int j = 0; j < TT; ++j) acc[i][j] = b;
+    }
+
+    for (int ks = 0; ks < nk; ++ks, ++g) {
+      int nbuf = buf + 1;
+      if (nbuf == STAGES) nbuf = 0;
+      const bool more = g + 1 < total;         // another stage follows (possibly of the next tile)
+      const bool refill = g + STAGES < total;  // stage g+3 exists: it goes into this stage's buffer
+      [&]<int... J>(std::integer_sequence<int, J...>) {
+        ([&] {
+          constexpr int j = J;
+          if constexpr (j == TT - 3) {
+            if (more) {
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all this wave's reads of stage g are back
+              wait_stage(g + 2 < total ? 1 : 0);
+              __builtin_amdgcn_s_barrier();
+            }
+          }
+          if constexpr (j + 3 < TT) {
+            read_b(buf, j + 3, bq[(j + 3) & 3]);
+          } else {
+            if (more) read_b(nbuf, j + 3 - TT, bq[(j + 3) & 3]);
+          }
+          if constexpr (j >= TT - 2) {
+            if (more) {
+#pragma unroll
+              for (int i = (j - (TT - 2)) * (OT / 2); i < (j - (TT - 2) + 1) * (OT / 2); ++i)
+                read_a(nbuf, i, a_nxt[i], s_nxt[i]);
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < OT; ++i) {
+            if constexpr (SPARSE)
+              acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+                                                                    __builtin_bit_cast(bf16x16_t, bq[j & 3]),
+                                                                    acc[i][j], s_cur[i], 0, 0);
+            else
+              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+                                                                  __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
+                                                                  0, 0, 0);
+          }
+          if constexpr (j >= TT - 3) {
+            // this wave's loads of stage g+3, a third after each of the last three groups
+            if (refill) {
+              constexpr int part = j - (TT - 3);
+              constexpr int lo = part * C::LPW / 3, hi = (part + 1) * C::LPW / 3;
+              [&]<int... D>(std::integer_sequence<int, D...>) {
+                (issue_one(std::integral_constant<int, lo + D>{}, buf), ...);
+              }(std::make_integer_sequence<int, hi - lo>{});
+              if constexpr (part == 2) cursor_advance();
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }(), ...);
+      }(std::make_integer_sequence<int, TT>{});
+#pragma unroll
+      for (int i = 0; i < OT; ++i) { a_cur[i] = a_nxt[i]; s_cur[i] = s_nxt[i]; }
+      buf = nbuf;
+    }
+
+    // ---- write the tile out (no LDS: the stage ring already holds the next tile).  A lane holds
+    // out-features o .. o+3 of token r16 per 16 x 16 block; for bf16 two blocks are exchanged between
+    // the lane rows kb and kb^1 so that every lane owns 8 consecutive out-features (16 bytes).
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+      const int64_t t = t0 + wt * 128 + j * 16 + r16;
+      const bool row_ok = t >= t_lo;
+      if (a.out_bf16) {
+#pragma unroll
+        for (int ip = 0; ip < OT / 2; ++ip) {
+          const f32x4_t v0 = acc[2 * ip][j], v1 = acc[2 * ip + 1][j];
+          const uint32_t a0 = pack_bf16x2(v0[0], v0[1]), a1 = pack_bf16x2(v0[2], v0[3]);
+          const uint32_t b0 = pack_bf16x2(v1[0], v1[1]), b1 = pack_bf16x2(v1[2], v1[3]);
+          // even lane rows keep their first operand and receive the odd partner's; odd rows receive the
+          // even partner's second operand and keep theirs
+          const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
+          const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
+          const int64_t o = o0 + wo * 64 + (2 * ip + (kb & 1)) * 16 + (kb >> 1) * 8;
+          if (row_ok && o < a.O)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) =
+                u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < OT; ++i) {
+          const int64_t o = o0 + wo * 64 + i * 16 + kb * 4;
+          if (row_ok && o < a.O)
+            *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(a.Y) + t * a.ldy + o) = acc[i][j];
         }
       }
     }
@@ -608,22 +920,37 @@ spmm_general_kernel(const bf16_t* __restrict__ values, const uint32_t* __restric
 // ---------------------------------------------------------------------------------------------
 static inline bool aligned_to(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
-static bool tiles_ok(const SpmmArgs& a) {
-  if (a.K % 64) return false;
-  if (!aligned_to(a.X, 16) || (a.ldx % 8)) return false;
-  if (!aligned_to(a.values, 16) || !aligned_to(a.indices, 8)) return false;
-  if (a.O > (1 << 24) || a.T > (1ll << 31)) return false;
-  if (a.ldx > (1 << 22) || a.K > (1 << 22)) return false;  // per-lane byte offsets inside a tile stay below 2^32
+static bool tiles_ok(int64_t K, const void* X, int64_t ldx, const void* values, const void* indices, int64_t O,
+                     int64_t T) {
+  if (K % 64) return false;
+  if (!aligned_to(X, 16) || (ldx % 8)) return false;
+  if (!aligned_to(values, 16) || !aligned_to(indices, 8)) return false;
+  if (O > (1 << 24) || T > (1ll << 31)) return false;
+  if (ldx > (1 << 22) || K > (1 << 22)) return false;  // per-lane byte offsets inside a tile stay below 2^32
   return true;
 }
 
+// Which product kernel a layer of O out-features runs at T tokens: 0 = the persistent 256 x 256 kernel
+// (needs the weight in stream order), 1.. = the tiled kernel with smaller tiles (row-major operand form).
+static int pick_tile(int64_t O, int64_t T) {
+  static const int forced = getenv("NM_GEMM_TILE") ? atoi(getenv("NM_GEMM_TILE")) : -1;  // tuning aid
+  const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
+  const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
+  int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
+  if (pick == 0 && T < 256) pick = 2;
+  return pick;
+}
+
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
-  (void)T;
-  if (K % 64) return 0;                     // general kernel
-  if (N == 2 && M == 4) return 0;           // packed layout is the operand layout
-  if (N == M) return 0;                     // values are the dense weight
-  if (N <= 2) return (size_t)(O * K) + (size_t)(O * K / 8);  // 2:4 re-coding: values + selectors
-  return (size_t)(O * K) * 2;               // dense expansion
+  if (K % 64) return 0;  // general kernel reads the packed layout itself
+  const bool sparse_form = N <= 2 && N < M;
+  if (pick_tile(O, T) == 0) {
+    const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // stream order, whole 256-row tiles
+    return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
+  }
+  if (N == 2 && M == 4) return 0;  // packed layout is the row-major operand form
+  if (N == M) return 0;            // values are the dense weight
+  return sparse_form ? (size_t)(O * K) + (size_t)(O * K / 8) : (size_t)(O * K) * 2;
 }
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, int SCHED>
@@ -647,54 +974,119 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
 }
 
 template <bool SPARSE>
-static hipError_t dispatch_gemm(const GemmArgs& g, hipStream_t s) {
-  // tile choice: large tiles when there is enough work to fill 256 CUs, smaller ones otherwise
-  const int64_t tiles_big = ((g.O + 255) / 256) * ((g.T + 255) / 256);
-  const int64_t tiles_mid = ((g.O + 127) / 128) * ((g.T + 127) / 128);
-  static const int forced = getenv("NM_GEMM_TILE") ? atoi(getenv("NM_GEMM_TILE")) : -1;  // tuning aid
-  const int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
+static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
+  using C = StreamCfg<SPARSE>;
+  auto kern = nm_stream_kernel<SPARSE>;
+  static int n_cu = 0;  // filled once; a race only repeats the query
+  if (!n_cu) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    n_cu = cus > 8 ? (cus / 8) * 8 : 8;
+  }
+  g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
+  g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
+  const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
+  if (n_tiles > 0x7FFFFFF0) return hipErrorInvalidValue;
+  const int64_t want = ((n_tiles + 7) / 8) * 8;
+  const unsigned grid = (unsigned)(want < n_cu ? want : n_cu);  // one persistent block per CU
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, s, g);
+  return hipGetLastError();
+}
+
+template <bool SPARSE>
+static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
+    case 0: return launch_stream<SPARSE>(g, s);
     case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_SIMPLE>(g, s);
     case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, SCHED_SIMPLE>(g, s);
     case 3: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, SCHED_SIMPLE>(g, s);
-    case 4: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_PINGPONG>(g, s);
-    default:
-      if constexpr (SPARSE) return launch_gemm<true, 4, 2, 4, 8, 3, SCHED_STREAM>(g, s);
-      else return launch_gemm<false, 2, 4, 8, 4, 2, SCHED_PINGPONG>(g, s);
+    default: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_PINGPONG>(g, s);
   }
+}
+
+static hipError_t launch_general(const SpmmArgs& a, hipStream_t s) {
+  const int64_t n_o_tiles = (a.O + 15) / 16, n_t_tiles = (a.T + 15) / 16;
+  if (n_o_tiles * n_t_tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(spmm_general_kernel, dim3((unsigned)(n_o_tiles * n_t_tiles)), dim3(256), 0, s, a.values, a.indices,
+                     a.O, a.K, a.N, a.M, a.X, a.T, a.ldx, a.bias, a.Y, a.ldy, a.out_bf16, n_o_tiles);
+  return hipGetLastError();
 }
 
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases) {
   *workspace_short = false;
   const bool prepare = phases & SPMM_PREPARE, product = phases & SPMM_PRODUCT;
-  if (!tiles_ok(a)) {
+  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) {
     if (!product) return hipSuccess;  // the gather kernel reads the packed layout itself
-    const int64_t n_o_tiles = (a.O + 15) / 16, n_t_tiles = (a.T + 15) / 16;
-    if (n_o_tiles * n_t_tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(spmm_general_kernel, dim3((unsigned)(n_o_tiles * n_t_tiles)), dim3(256), 0, s, a.values,
-                       a.indices, a.O, a.K, a.N, a.M, a.X, a.T, a.ldx, a.bias, a.Y, a.ldy, a.out_bf16, n_o_tiles);
-    return hipGetLastError();
+    return launch_general(a, s);
   }
   const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256))) {
     *workspace_short = true;
     return hipSuccess;
   }
+  const int pick = pick_tile(a.O, a.T);
+  const bool sparse_form = a.N <= 2 && a.N < a.M;
   GemmArgs g;
   g.X = a.X; g.bias = a.bias; g.Y = a.Y;
   g.O = a.O; g.K = a.K; g.T = a.T; g.ldx = a.ldx; g.ldy = a.ldy;
   g.out_bf16 = a.out_bf16;
   g.n_o_tiles = g.n_t_tiles = 0;
+  g.sel = nullptr;
   // 16-byte pieces of Y rows: every row start and the row end fall on a piece boundary
   const int per_piece = a.out_bf16 ? 8 : 4;
   g.vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
                 (a.bias == nullptr || aligned_to(a.bias, 16));
-  if (a.N <= 2 && a.N < a.M) {
+  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
+
+  if (pick == 0) {
+    // persistent kernel: every level goes through the stream-order pre-pass; it writes Y in 16-byte pieces only
+    if (product && !g.vec_store) return launch_general(a, s);  // reads the packed layout itself
+    const int64_t o_pad = ((a.O + 255) / 256) * 256;
+    if (sparse_form) {
+      unsigned char* vals_s = ws;
+      unsigned char* sel_s = ws + (size_t)o_pad * (size_t)a.K;
+      if (prepare) {
+        const int64_t n = o_pad * (a.K / 32);
+        const dim3 grid((unsigned)((n + 255) / 256));
+        switch (a.N * 32 + a.M) {
+#define X(n_, m_)                                                                                              \
+  case n_ * 32 + m_:                                                                                           \
+    hipLaunchKernelGGL((recode_stream_kernel<n_, m_>), grid, dim3(256), 0, s, a.values, a.indices, a.O, o_pad, a.K, \
+                       vals_s, sel_s);                                                                         \
+    break;
+          X(1, 4) X(2, 4) X(1, 8) X(2, 8) X(1, 16) X(2, 16)
+#undef X
+          default: return hipErrorInvalidValue;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+      }
+      g.A = reinterpret_cast<const bf16_t*>(vals_s);
+      g.sel = reinterpret_cast<const uint32_t*>(sel_s);
+      return product ? dispatch_gemm<true>(g, pick, s) : hipSuccess;
+    }
+    if (prepare) {
+      const int64_t n = o_pad * (a.K / 8);
+      hipLaunchKernelGGL(expand_stream_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.values, a.indices,
+                         a.O, o_pad, a.K, a.N, a.M, ws);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    g.A = reinterpret_cast<const bf16_t*>(ws);
+    return product ? dispatch_gemm<false>(g, pick, s) : hipSuccess;
+  }
+
+  // tiled kernel with smaller tiles: row-major operand forms
+  if (sparse_form) {
     if (a.N == 2 && a.M == 4) {
       g.A = a.values; g.sel = a.indices;
     } else {
-      bf16_t* v24 = reinterpret_cast<bf16_t*>(a.workspace);
-      uint32_t* s24 = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(a.workspace) + (size_t)(a.O * a.K));
+      bf16_t* v24 = reinterpret_cast<bf16_t*>(ws);
+      uint32_t* s24 = reinterpret_cast<uint32_t*>(ws + (size_t)(a.O * a.K));
       if (prepare) {
         const int64_t n = a.O * (a.K / 32);
         const dim3 grid((unsigned)((n + 255) / 256));
@@ -712,20 +1104,19 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
       }
       g.A = v24; g.sel = s24;
     }
-    return product ? dispatch_gemm<true>(g, s) : hipSuccess;
+    return product ? dispatch_gemm<true>(g, pick, s) : hipSuccess;
   }
-  g.sel = nullptr;
   if (a.N == a.M) {
     g.A = a.values;
   } else {
-    bf16_t* wd = reinterpret_cast<bf16_t*>(a.workspace);
+    bf16_t* wd = reinterpret_cast<bf16_t*>(ws);
     if (prepare) {
       hipError_t e = launch_unpack(a.values, a.indices, a.O, a.K, a.N, a.M, wd, a.K, s);
       if (e != hipSuccess) return e;
     }
     g.A = wd;
   }
-  return product ? dispatch_gemm<false>(g, s) : hipSuccess;
+  return product ? dispatch_gemm<false>(g, pick, s) : hipSuccess;
 }
 
 }  // namespace nm

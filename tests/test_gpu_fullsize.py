@@ -55,6 +55,23 @@ def test_deit_b_batch256_fp32_output_sampled():
     check_layer_sampled(L, wl.draw_activations(rng, L.T, L.K), wl.draw_weights(rng, L.O, L.K), torch.float32, rng)
 
 
+@pytest.mark.parametrize("level,O,out_dtype", [((2, 4), 3072, torch.bfloat16), ((1, 8), 3000, torch.float32),
+                                               ((4, 8), 2304, torch.bfloat16), ((3, 4), 1000, torch.float32)])
+def test_linear_forward_with_bias_at_batch256(level, O, out_dtype):
+    # bias on the large-tile kernels, sparse and dense operand forms, whole and ragged out-feature tiles
+    T, K = 256 * 197, 768
+    rng = np.random.default_rng(zlib.crc32(f"bias-{level}-{O}".encode()))
+    X, W = wl.draw_activations(rng, T, K), wl.draw_weights(rng, O, K)
+    bias = rng.standard_normal(O).astype(np.float32)
+    v, i = nm.nm_pack(dev_bf16(W), *level)
+    Y = nm.nm_linear_forward(v, i, K, *level, dev_bf16(X), bias=torch.from_numpy(bias).cuda(), out_dtype=out_dtype)
+    rows = sample_rows(T, rng)
+    Yref, B = orc.nm_linear_from_bits(X[rows], W, *level, bias=bias)
+    Ys = host_output(Y[torch.from_numpy(rows).cuda()])
+    check_output(Ys, Yref, B + np.abs(bias)[None, :], K // level[1] * level[0] + 1, out_dtype == torch.float32,
+                 f"{level} O={O}")
+
+
 def test_deit_b_block_batch64_seeded_levels():
     # the four linears of one block at 12608 tokens, levels drawn with seed 0 (4:8, 2:8, 1:8, 2:4)
     rng = np.random.default_rng(5)

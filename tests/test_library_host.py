@@ -58,6 +58,12 @@ def test_workspace_sizes(lib):
     assert lib.nm_spmm_workspace_bytes(768, 768, 1, 8, 100) == 768 * 768 + 768 * 768 // 8
     assert lib.nm_spmm_workspace_bytes(768, 768, 4, 8, 100) == 768 * 768 * 2
     assert lib.nm_spmm_workspace_bytes(8, 24, 1, 8, 100) == 0          # general kernel, no scratch
+    # enough 256 x 256 tiles for the persistent kernel: every level is rewritten into stream order,
+    # rows padded to whole tiles (768 -> 768, 700 -> 768)
+    assert lib.nm_spmm_workspace_bytes(768, 768, 2, 4, 50432) == 768 * 768 + 768 * 768 // 8
+    assert lib.nm_spmm_workspace_bytes(700, 768, 1, 16, 50432) == 768 * 768 + 768 * 768 // 8
+    assert lib.nm_spmm_workspace_bytes(768, 768, 4, 8, 50432) == 768 * 768 * 2
+    assert lib.nm_spmm_workspace_bytes(768, 768, 8, 8, 50432) == 768 * 768 * 2
 
 
 def test_status_strings(lib):
