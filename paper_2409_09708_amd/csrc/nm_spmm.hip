@@ -246,6 +246,19 @@ __device__ __forceinline__ void dma4(uniform_ptr_t base, uint32_t lane_byte_offs
                "s"(base)
                : "memory", "m0");
 }
+// The same with the LDS address given as two uniform terms (stage buffer + place inside the stage).
+__device__ __forceinline__ void dma16_at(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds_stage,
+                                         uint32_t lds_offset) {
+  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(lds_stage), "s"(lds_offset),
+               "v"(lane_byte_offset), "s"(base)
+               : "memory", "m0", "scc");
+}
+__device__ __forceinline__ void dma4_at(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds_stage,
+                                        uint32_t lds_offset) {
+  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(lds_stage), "s"(lds_offset),
+               "v"(lane_byte_offset), "s"(base)
+               : "memory", "m0", "scc");
+}
 // Two floats to a pair of bfloat16 (round to nearest even) with the hardware conversion; lo in bits 0..15.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -640,9 +653,6 @@ nm_stream_kernel(const GemmArgs a) {
   const int first = xcd_first + (int)(blockIdx.x >> 3);
   if (first >= xcd_end) return;
   const int my_tiles = (xcd_end - first + slots - 1) / slots;
-  const int nk = (int)(a.K / C::KSTEP);
-  const int total = my_tiles * nk;  // stages this block goes through
-
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -651,10 +661,11 @@ nm_stream_kernel(const GemmArgs a) {
   const int r16 = lane & 15;
   const int kb = lane >> 4;
 
-  // ---- fixed per-lane source offsets and per-wave LDS destinations of this wave's loads
-  uint32_t x_voff[C::X_PW];
+  // ---- fixed per-lane source offsets and per-wave LDS destinations of this wave's loads.  The W piece a
+  // load brings is the one of 16-row group (wave + 8 i) of the tile: group and lane are folded into the
+  // lane offset, so every load of a stage uses one of three running base pointers.
+  uint32_t x_voff[C::X_PW], w_voff[C::A_PW];
   uint32_t x_dst[C::X_PW], a_dst[C::A_PW];
-  int a_grp[C::A_PW];  // 16-row group (within the tile) each W load brings
 #pragma unroll
   for (int i = 0; i < C::X_PW; ++i) {
     const int j = wave + i * C::NW;
@@ -664,16 +675,19 @@ nm_stream_kernel(const GemmArgs a) {
     x_voff[i] = (uint32_t)(((int64_t)row * a.ldx + c * 8) * 2);
     x_dst[i] = (uint32_t)(j * 1024);
   }
+  const int nk = (int)(a.K / C::KSTEP);
 #pragma unroll
   for (int i = 0; i < C::A_PW; ++i) {
-    a_grp[i] = wave + i * C::NW;
-    a_dst[i] = (uint32_t)(C::X_BYTES + a_grp[i] * 1024);
+    const int grp = wave + i * C::NW;
+    w_voff[i] = ((uint32_t)(grp * nk) << 10) + (uint32_t)(lane * 16);  // < 16 * 2^16 * 2^10
+    a_dst[i] = (uint32_t)(C::X_BYTES + grp * 1024);
   }
-  const uint32_t w_voff = (uint32_t)(lane * 16);  // W pieces and selector words are contiguous per load
-  const uint32_t s_voff = (uint32_t)(lane * 4);
+  const uint32_t s_voff = (uint32_t)(wave * 256 + lane * 4);
   const uint32_t s_dst = (uint32_t)(C::X_BYTES + C::A_BYTES + wave * 256);
+  const bool bias_wave = a.bias != nullptr && wave == 0;  // wave 0 also fetches the tiles' bias slices
 
-  // ---- tile origins; load cursor = the stage to be issued next (tile number in this block, k step)
+  // ---- tile origins; load cursor = the stage to be issued next (tile number in this block, k step) as
+  // running pointers: X rows of the tile at the step's k, W and selector blocks of the step
   auto tile_origin = [&](int n, int& o_tile, int64_t& t_lo, int64_t& t0) {
     const int tile = first + n * slots;
     o_tile = tile % a.n_o_tiles;
@@ -682,45 +696,50 @@ nm_stream_kernel(const GemmArgs a) {
   };
   const unsigned char* const w_all = reinterpret_cast<const unsigned char*>(a.A);
   const unsigned char* const s_all = reinterpret_cast<const unsigned char*>(a.sel);
-  int cur_n = 0, cur_ks = 0;
-  uint32_t cur_bias_voff = 0;
-  const bf16_t* cur_x = nullptr;
-  const unsigned char* cur_w = nullptr;  // stream-order blocks of the tile's first 16-row group
-  const unsigned char* cur_s = nullptr;
+  int ld_n = 0, ld_ks = 0;
+  uint32_t ld_bias_voff = 0;
+  const unsigned char* ld_x = nullptr;
+  const unsigned char* ld_w = nullptr;
+  const unsigned char* ld_s = nullptr;
   auto cursor_tile = [&](int n) {
     int o_tile;
     int64_t t_lo, t0;
     tile_origin(n, o_tile, t_lo, t0);
-    cur_x = a.X + t0 * a.ldx;
-    cur_w = w_all + (((int64_t)o_tile * 16 * nk) << 10);
-    cur_s = SPARSE ? s_all + (((int64_t)o_tile * nk) << 11) : nullptr;
+    ld_x = reinterpret_cast<const unsigned char*>(a.X + t0 * a.ldx);
+    ld_w = w_all + (((int64_t)o_tile * 16 * nk) << 10);
+    ld_s = SPARSE ? s_all + (((int64_t)o_tile * nk) << 11) : nullptr;
     // bias[o0 + 4 lane ..]: past the last out-feature re-read the last four (never stored)
     const int64_t ob = (int64_t)o_tile * C::BO + lane * 4;
-    cur_bias_voff = (uint32_t)((ob + 4 <= a.O ? ob : a.O - 4) * 4);
-    cur_n = n;
-    cur_ks = 0;
+    ld_bias_voff = (uint32_t)((ob + 4 <= a.O ? ob : a.O - 4) * 4);
+    ld_n = n;
+    ld_ks = 0;
   };
   auto cursor_advance = [&]() {
-    if (++cur_ks == nk && cur_n + 1 < my_tiles) cursor_tile(cur_n + 1);
+    ld_x += C::KSTEP * 2;
+    ld_w += 1024;
+    if (SPARSE) ld_s += 2048;
+    // past the block's last stage the cursor walks the last tile again: the step below then needs no
+    // conditions (the surplus stages land in buffers nobody reads any more)
+    if (++ld_ks == nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
   };
-  // the d-th of this wave's LPW loads of the cursor's stage into LDS buffer buf
-  auto issue_one = [&](auto d_tag, int buf) {
+  // the d-th of this wave's LPW loads of the cursor's stage into the stage buffer at LDS offset stage_off
+  auto issue_one = [&](auto d_tag, uint32_t stage_off) {
     constexpr int d = decltype(d_tag)::value;
-    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + stage_off);
     if constexpr (d == 0) {
       // a tile's first stage brings the tile's bias slice along (older than the stage's own loads, so
-      // every wait that covers the stage covers it)
-      if (a.bias != nullptr && cur_ks == 0 && wave == 0)
-        dma16(make_uniform(a.bias), cur_bias_voff,
-              __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(C::BIAS0 + buf * (C::BO * 4))));
+      // every wait that covers the stage covers it); slice s belongs to stage buffer s
+      if (bias_wave && ld_ks == 0)
+        dma16(make_uniform(a.bias), ld_bias_voff,
+              __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)C::BIAS0 + stage_off / (uint32_t)C::STAGE * (C::BO * 4)));
     }
     if constexpr (d < C::X_PW) {
-      dma16(make_uniform(cur_x + (int64_t)cur_ks * C::KSTEP), x_voff[d], lds + x_dst[d]);
+      dma16_at(make_uniform(ld_x), x_voff[d], lds, __builtin_amdgcn_readfirstlane(x_dst[d]));
     } else if constexpr (d < C::X_PW + C::A_PW) {
       constexpr int q = d - C::X_PW;
-      dma16(make_uniform(cur_w + ((((int64_t)a_grp[q] * nk) + cur_ks) << 10)), w_voff, lds + a_dst[q]);
+      dma16_at(make_uniform(ld_w), w_voff[q], lds, __builtin_amdgcn_readfirstlane(a_dst[q]));
     } else {
-      dma4(make_uniform(cur_s + ((int64_t)cur_ks << 11) + wave * 256), s_voff, lds + s_dst);
+      dma4_at(make_uniform(ld_s), s_voff, lds, __builtin_amdgcn_readfirstlane(s_dst));
     }
   };
   auto wait_stage = [&](int younger) {
@@ -736,8 +755,8 @@ nm_stream_kernel(const GemmArgs a) {
   const int x_row = (wt * 128 + r16) * C::X_ROWB;
   const int x_lo = SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16);
   const int x_hi = ((4 + kb) ^ (r16 & 7)) * 16;
-  auto read_a = [&](int buf, int i, u32x4_t& av, int& sv) {
-    const unsigned char* base = smem + buf * C::STAGE;
+  auto read_a = [&](uint32_t stage_off, int i, u32x4_t& av, int& sv) {
+    const unsigned char* base = smem + stage_off;
     av = *reinterpret_cast<const u32x4_t*>(base + a_off + i * 16 * C::A_ROWB);
     if (SPARSE) {
       const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_off + i * 16 * 8);
@@ -746,8 +765,8 @@ nm_stream_kernel(const GemmArgs a) {
       sv = 0;
     }
   };
-  auto read_b = [&](int buf, int j, bfrag_t& bv) {
-    const unsigned char* row = smem + buf * C::STAGE + x_row + j * 16 * C::X_ROWB;
+  auto read_b = [&](uint32_t stage_off, int j, bfrag_t& bv) {
+    const unsigned char* row = smem + stage_off + x_row + j * 16 * C::X_ROWB;
     if constexpr (SPARSE) {
       const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + x_lo);
       const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + x_hi);
@@ -761,14 +780,12 @@ nm_stream_kernel(const GemmArgs a) {
   cursor_tile(0);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s) {
-    if (s < total) {
-      [&]<int... D>(std::integer_sequence<int, D...>) {
-        (issue_one(std::integral_constant<int, D>{}, s), ...);
-      }(std::make_integer_sequence<int, C::LPW>{});
-      cursor_advance();
-    }
+    [&]<int... D>(std::integer_sequence<int, D...>) {
+      (issue_one(std::integral_constant<int, D>{}, (uint32_t)(s * C::STAGE)), ...);
+    }(std::make_integer_sequence<int, C::LPW>{});
+    cursor_advance();
   }
-  wait_stage((total < STAGES ? total : STAGES) - 1);
+  wait_loads_outstanding<(STAGES - 1) * C::LPW>();
   __builtin_amdgcn_s_barrier();
 
   u32x4_t a_cur[OT], a_nxt[OT];
@@ -779,80 +796,76 @@ nm_stream_kernel(const GemmArgs a) {
 #pragma unroll
   for (int j = 0; j < 3; ++j) read_b(0, j, bq[j]);
 
-  int buf = 0;
-  int g = 0;  // stage number within this block
+  uint32_t cur_off = 0;  // LDS offset of the buffer that holds the current stage
+  f32x4_t acc[OT][TT];
+
+  // One K step, free of conditions: a wave issues one instruction at a time, in order, so every scalar
+  // instruction of the step is time its matrix instructions do not get.  Every step refills the buffer
+  // it has consumed and prefetches fragments of the next stage, also past the block's last stage.
+  auto step = [&]() {
+    uint32_t nxt_off = cur_off + C::STAGE;
+    if (nxt_off == (uint32_t)(STAGES * C::STAGE)) nxt_off = 0;
+    [&]<int... J>(std::integer_sequence<int, J...>) {
+      ([&] {
+        constexpr int j = J;
+        if constexpr (j == TT - 3) {
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all this wave's reads of the stage are back
+          wait_loads_outstanding<C::LPW>();                   // this wave's share of the next stage has landed
+          __builtin_amdgcn_s_barrier();
+        }
+        if constexpr (j + 3 < TT) read_b(cur_off, j + 3, bq[(j + 3) & 3]);
+        else read_b(nxt_off, j + 3 - TT, bq[(j + 3) & 3]);
+        if constexpr (j >= TT - 2) {
+#pragma unroll
+          for (int i = (j - (TT - 2)) * (OT / 2); i < (j - (TT - 2) + 1) * (OT / 2); ++i)
+            read_a(nxt_off, i, a_nxt[i], s_nxt[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < OT; ++i) {
+          if constexpr (SPARSE)
+            acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+                                                                  __builtin_bit_cast(bf16x16_t, bq[j & 3]),
+                                                                  acc[i][j], s_cur[i], 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+                                                                __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
+                                                                0, 0, 0);
+        }
+        if constexpr (j >= TT - 3) {
+          // this wave's loads of the stage three ahead, a third after each of the last three groups
+          constexpr int part = j - (TT - 3);
+          constexpr int lo = part * C::LPW / 3, hi = (part + 1) * C::LPW / 3;
+          [&]<int... D>(std::integer_sequence<int, D...>) {
+            (issue_one(std::integral_constant<int, lo + D>{}, cur_off), ...);
+          }(std::make_integer_sequence<int, hi - lo>{});
+          if constexpr (part == 2) cursor_advance();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }(), ...);
+    }(std::make_integer_sequence<int, TT>{});
+#pragma unroll
+    for (int i = 0; i < OT; ++i) { a_cur[i] = a_nxt[i]; s_cur[i] = s_nxt[i]; }
+    cur_off = nxt_off;
+  };
+
   for (int n = 0; n < my_tiles; ++n) {
     int o_tile;
     int64_t t_lo, t0;
     tile_origin(n, o_tile, t_lo, t0);
     const int64_t o0 = (int64_t)o_tile * C::BO;
-    f32x4_t acc[OT][TT];
 #pragma unroll
     for (int i = 0; i < OT; ++i) {
       // the accumulators start from the bias, which came with the tile's first stage
       f32x4_t b = f32x4_t{0.f, 0.f, 0.f, 0.f};
       if (a.bias != nullptr)
-        b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + buf * (C::BO * 4) + (wo * 64 + i * 16 + kb * 4) * 4);
+        b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + cur_off / (uint32_t)C::STAGE * (C::BO * 4) +
+                                              (wo * 64 + i * 16 + kb * 4) * 4);
 #pragma unroll
       for (int j = 0; j < TT; ++j) acc[i][j] = b;
     }
 
-    for (int ks = 0; ks < nk; ++ks, ++g) {
-      int nbuf = buf + 1;
-      if (nbuf == STAGES) nbuf = 0;
-      const bool more = g + 1 < total;         // another stage follows (possibly of the next tile)
-      const bool refill = g + STAGES < total;  // stage g+3 exists: it goes into this stage's buffer
-      [&]<int... J>(std::integer_sequence<int, J...>) {
-        ([&] {
-          constexpr int j = J;
-          if constexpr (j == TT - 3) {
-            if (more) {
-              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all this wave's reads of stage g are back
-              wait_stage(g + 2 < total ? 1 : 0);
-              __builtin_amdgcn_s_barrier();
-            }
-          }
-          if constexpr (j + 3 < TT) {
-            read_b(buf, j + 3, bq[(j + 3) & 3]);
-          } else {
-            if (more) read_b(nbuf, j + 3 - TT, bq[(j + 3) & 3]);
-          }
-          if constexpr (j >= TT - 2) {
-            if (more) {
-#pragma unroll
-              for (int i = (j - (TT - 2)) * (OT / 2); i < (j - (TT - 2) + 1) * (OT / 2); ++i)
-                read_a(nbuf, i, a_nxt[i], s_nxt[i]);
-            }
-          }
-#pragma unroll
-          for (int i = 0; i < OT; ++i) {
-            if constexpr (SPARSE)
-              acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
-                                                                    __builtin_bit_cast(bf16x16_t, bq[j & 3]),
-                                                                    acc[i][j], s_cur[i], 0, 0);
-            else
-              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
-                                                                  __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
-                                                                  0, 0, 0);
-          }
-          if constexpr (j >= TT - 3) {
-            // this wave's loads of stage g+3, a third after each of the last three groups
-            if (refill) {
-              constexpr int part = j - (TT - 3);
-              constexpr int lo = part * C::LPW / 3, hi = (part + 1) * C::LPW / 3;
-              [&]<int... D>(std::integer_sequence<int, D...>) {
-                (issue_one(std::integral_constant<int, lo + D>{}, buf), ...);
-              }(std::make_integer_sequence<int, hi - lo>{});
-              if constexpr (part == 2) cursor_advance();
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }(), ...);
-      }(std::make_integer_sequence<int, TT>{});
-#pragma unroll
-      for (int i = 0; i < OT; ++i) { a_cur[i] = a_nxt[i]; s_cur[i] = s_nxt[i]; }
-      buf = nbuf;
-    }
+    for (int ks = 0; ks < nk; ++ks) step();
+    if (n + 1 == my_tiles) wait_loads_outstanding<0>();  // the surplus stages: nothing in flight when the block ends
 
     // ---- write the tile out (no LDS memory: the stage ring already holds the next tile).  A lane holds
     // out-features o .. o+3 of token r16 per 16 x 16 block.  The memory pipeline merges a store only
