@@ -192,7 +192,7 @@ def main():
     achieved = sp_useful / (sp_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_DENSE_TFLOPS, "traffic": measured_traffic(),
-                "kernel": "nm_gemm_kernel<sparse> (v_smfmac_f32_16x16x64_bf16); useful FLOPs 2*T*O*K*N/M per launch, "
+                "kernel": "nm_stream_kernel<sparse> (v_smfmac_f32_16x16x64_bf16); useful FLOPs 2*T*O*K*N/M per launch, "
                           "averaged over the 36 launches per step with N <= 2",
                 "launches_per_step": len(sp), "avg_launch_ms": sp_ms / len(sp),
                 "useful_flops_per_launch": sp_useful / len(sp),
