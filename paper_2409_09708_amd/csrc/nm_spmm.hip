@@ -612,9 +612,13 @@ nm_gemm_kernel(const GemmArgs a) {
 // neighbour but stores only its own) and the weight is zero-padded to whole tiles, so every tile is
 // full and lane offsets never change.
 // ---------------------------------------------------------------------------------------------
-template <bool SPARSE>
+template <bool SPARSE, int WO_>
 struct StreamCfg {
-  static constexpr int WO = 4, WT = 2, OT = 4, TT = 8, NW = 8, NT = 512, BO = 256, BT = 256, STAGES = 3;
+  // WO_ = 4: 8 waves of 64 x 128 outputs, two per SIMD; WO_ = 2: 4 waves of 128 x 128, one per SIMD (the
+  // accumulators alone fill 256 registers; a wave then has the 512-register budget)
+  static constexpr int WO = WO_, WT = 2, BO = 256, BT = 256, OT = BO / (WO * 16), TT = BT / (WT * 16);
+  static constexpr int NW = WO * WT, NT = NW * 64, STAGES = 3;
+  static constexpr int OW = OT * 16;                     // out-features per wave
   static constexpr int KSTEP = SPARSE ? 64 : 32;         // dense k per stage
   static constexpr int X_ROWB = KSTEP * 2;               // bytes of one X row per stage
   static constexpr int A_ROWB = 64;                      // 32 compressed values, or 32 dense weights
@@ -628,15 +632,15 @@ struct StreamCfg {
   static constexpr int A_PW = A_BYTES / 1024 / NW;
   static constexpr int S_PW = SPARSE ? S_BYTES / 256 / NW : 0;
   static constexpr int LPW = X_PW + A_PW + S_PW;
-  static_assert(S_PW <= 1, "one selector load per wave");
+  static_assert(WO == 2 || WO == 4, "wave layouts");
   static_assert(BO * 4 == 1024, "the bias slice of a tile is one wave-load");
   static_assert(LDS_BYTES <= 160 * 1024 && STAGES * (LPW + 1) < 64, "LDS budget and vmcnt range");
 };
 
-template <bool SPARSE>
-__global__ void __launch_bounds__(512)
+template <bool SPARSE, int WO_>
+__global__ void __launch_bounds__(WO_ * 128)
 nm_stream_kernel(const GemmArgs a) {
-  using C = StreamCfg<SPARSE>;
+  using C = StreamCfg<SPARSE, WO_>;
   constexpr int OT = C::OT, TT = C::TT, STAGES = C::STAGES;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -656,8 +660,8 @@ nm_stream_kernel(const GemmArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wo = wave & 3;
-  const int wt = wave >> 2;
+  const int wo = wave % C::WO;
+  const int wt = wave / C::WO;
   const int r16 = lane & 15;
   const int kb = lane >> 4;
 
@@ -682,8 +686,12 @@ nm_stream_kernel(const GemmArgs a) {
     w_voff[i] = ((uint32_t)(grp * nk) << 10) + (uint32_t)(lane * 16);  // < 16 * 2^16 * 2^10
     a_dst[i] = (uint32_t)(C::X_BYTES + grp * 1024);
   }
-  const uint32_t s_voff = (uint32_t)(wave * 256 + lane * 4);
-  const uint32_t s_dst = (uint32_t)(C::X_BYTES + C::A_BYTES + wave * 256);
+  uint32_t s_voff[C::S_PW > 0 ? C::S_PW : 1], s_dst[C::S_PW > 0 ? C::S_PW : 1];
+#pragma unroll
+  for (int i = 0; i < C::S_PW; ++i) {
+    s_voff[i] = (uint32_t)((wave + i * C::NW) * 256 + lane * 4);
+    s_dst[i] = (uint32_t)(C::X_BYTES + C::A_BYTES + (wave + i * C::NW) * 256);
+  }
   const bool bias_wave = a.bias != nullptr && wave == 0;  // wave 0 also fetches the tiles' bias slices
 
   // ---- tile origins; load cursor = the stage to be issued next (tile number in this block, k step) as
@@ -739,7 +747,8 @@ nm_stream_kernel(const GemmArgs a) {
       constexpr int q = d - C::X_PW;
       dma16_at(make_uniform(ld_w), w_voff[q], lds, __builtin_amdgcn_readfirstlane(a_dst[q]));
     } else {
-      dma4_at(make_uniform(ld_s), s_voff, lds, __builtin_amdgcn_readfirstlane(s_dst));
+      constexpr int q = d - C::X_PW - C::A_PW;
+      dma4_at(make_uniform(ld_s), s_voff[q], lds, __builtin_amdgcn_readfirstlane(s_dst[q]));
     }
   };
   auto wait_stage = [&](int younger) {
@@ -748,31 +757,33 @@ nm_stream_kernel(const GemmArgs a) {
     else wait_loads_outstanding<0>();
   };
 
-  // ---- fragment readers (the XOR undoes the swizzle applied by the loads)
+  // ---- fragment readers (the XOR undoes the swizzle applied by the loads).  A lane's four fragment
+  // addresses inside a stage buffer (W values, its 16 selector bits, the two halves of an X row) are kept
+  // for the current and for the next buffer; the two sets swap roles from step to step, so a step spends
+  // four vector additions on addresses and none on moving fragments: vector ALU instructions take issue
+  // slots from the matrix instructions of both waves of the SIMD.
   using bfrag_t = std::conditional_t<SPARSE, u32x8_t, u32x4_t>;
-  const int a_off = C::X_BYTES + (wo * 64 + r16) * C::A_ROWB + ((kb ^ ((r16 >> 2) & 3)) * 16);
-  const int s_off = C::X_BYTES + C::A_BYTES + (wo * 64 + r16) * 8 + (kb >> 1) * 4;
-  const int x_row = (wt * 128 + r16) * C::X_ROWB;
-  const int x_lo = SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16);
-  const int x_hi = ((4 + kb) ^ (r16 & 7)) * 16;
-  auto read_a = [&](uint32_t stage_off, int i, u32x4_t& av, int& sv) {
-    const unsigned char* base = smem + stage_off;
-    av = *reinterpret_cast<const u32x4_t*>(base + a_off + i * 16 * C::A_ROWB);
-    if (SPARSE) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_off + i * 16 * 8);
-      sv = (int)(w >> ((kb & 1) * 16));
-    } else {
-      sv = 0;
-    }
+  struct FragAddr { uint32_t a, s, xlo, xhi; };  // byte offsets into the dynamic LDS
+  FragAddr at0;
+  at0.a = (uint32_t)(C::X_BYTES + (wo * C::OW + r16) * C::A_ROWB + ((kb ^ ((r16 >> 2) & 3)) * 16));
+  at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (wo * C::OW + r16) * 8 + kb * 2);
+  at0.xlo = (uint32_t)((wt * 128 + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16)));
+  at0.xhi = (uint32_t)((wt * 128 + r16) * C::X_ROWB + ((4 + kb) ^ (r16 & 7)) * 16);
+  auto frag_addr = [&](uint32_t stage_off) {
+    return FragAddr{at0.a + stage_off, at0.s + stage_off, at0.xlo + stage_off, at0.xhi + stage_off};
   };
-  auto read_b = [&](uint32_t stage_off, int j, bfrag_t& bv) {
-    const unsigned char* row = smem + stage_off + x_row + j * 16 * C::X_ROWB;
+  auto read_a = [&](const FragAddr& at, int i, u32x4_t& av, int& sv) {
+    av = *reinterpret_cast<const u32x4_t*>(smem + at.a + i * 16 * C::A_ROWB);
+    if (SPARSE) sv = (int)*reinterpret_cast<const int16_t*>(smem + at.s + i * 16 * 8);  // the instruction reads bits 0..15 only
+    else sv = 0;
+  };
+  auto read_b = [&](const FragAddr& at, int j, bfrag_t& bv) {
     if constexpr (SPARSE) {
-      const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(row + x_lo);
-      const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(row + x_hi);
+      const u32x4_t lo = *reinterpret_cast<const u32x4_t*>(smem + at.xlo + j * 16 * C::X_ROWB);
+      const u32x4_t hi = *reinterpret_cast<const u32x4_t*>(smem + at.xhi + j * 16 * C::X_ROWB);
       bv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     } else {
-      bv = *reinterpret_cast<const u32x4_t*>(row + x_lo);
+      bv = *reinterpret_cast<const u32x4_t*>(smem + at.xlo + j * 16 * C::X_ROWB);
     }
   };
 
@@ -788,23 +799,29 @@ nm_stream_kernel(const GemmArgs a) {
   wait_loads_outstanding<(STAGES - 1) * C::LPW>();
   __builtin_amdgcn_s_barrier();
 
-  u32x4_t a_cur[OT], a_nxt[OT];
-  int s_cur[OT], s_nxt[OT];
+  u32x4_t afr[2][OT];  // W fragments of the current step and of the next one; the roles alternate
+  int sfr[2][OT];
+  FragAddr at[2];      // likewise the fragment addresses in the current and in the next buffer
   bfrag_t bq[4];
+  at[0] = at0;
 #pragma unroll
-  for (int i = 0; i < OT; ++i) read_a(0, i, a_cur[i], s_cur[i]);
+  for (int i = 0; i < OT; ++i) read_a(at[0], i, afr[0][i], sfr[0][i]);
 #pragma unroll
-  for (int j = 0; j < 3; ++j) read_b(0, j, bq[j]);
+  for (int j = 0; j < 3; ++j) read_b(at[0], j, bq[j]);
 
   uint32_t cur_off = 0;  // LDS offset of the buffer that holds the current stage
   f32x4_t acc[OT][TT];
 
-  // One K step, free of conditions: a wave issues one instruction at a time, in order, so every scalar
-  // instruction of the step is time its matrix instructions do not get.  Every step refills the buffer
-  // it has consumed and prefetches fragments of the next stage, also past the block's last stage.
-  auto step = [&]() {
+  // One K step, free of conditions: a wave issues one instruction at a time, in order, so every other
+  // instruction of the step is time its matrix instructions do not get.  PP names the fragment and address
+  // set the step multiplies with.  Every step refills the buffer it has consumed and prefetches fragments
+  // of the next stage, also past the block's last stage.
+  constexpr int AG = OT > 4 ? 3 : 2;  // groups that fetch the next step's W fragments (all after the barrier)
+  auto step = [&](auto pp_tag) {
+    constexpr int PP = decltype(pp_tag)::value;
     uint32_t nxt_off = cur_off + C::STAGE;
     if (nxt_off == (uint32_t)(STAGES * C::STAGE)) nxt_off = 0;
+    at[PP ^ 1] = frag_addr(nxt_off);
     [&]<int... J>(std::integer_sequence<int, J...>) {
       ([&] {
         constexpr int j = J;
@@ -813,21 +830,23 @@ nm_stream_kernel(const GemmArgs a) {
           wait_loads_outstanding<C::LPW>();                   // this wave's share of the next stage has landed
           __builtin_amdgcn_s_barrier();
         }
-        if constexpr (j + 3 < TT) read_b(cur_off, j + 3, bq[(j + 3) & 3]);
-        else read_b(nxt_off, j + 3 - TT, bq[(j + 3) & 3]);
-        if constexpr (j >= TT - 2) {
+        if constexpr (j + 3 < TT) read_b(at[PP], j + 3, bq[(j + 3) & 3]);
+        else read_b(at[PP ^ 1], j + 3 - TT, bq[(j + 3) & 3]);
+        if constexpr (j >= TT - AG) {
+          // the next step's W fragments, a share in each of the last AG groups
+          constexpr int part = j - (TT - AG);
 #pragma unroll
-          for (int i = (j - (TT - 2)) * (OT / 2); i < (j - (TT - 2) + 1) * (OT / 2); ++i)
-            read_a(nxt_off, i, a_nxt[i], s_nxt[i]);
+          for (int i = part * OT / AG; i < (part + 1) * OT / AG; ++i)
+            read_a(at[PP ^ 1], i, afr[PP ^ 1][i], sfr[PP ^ 1][i]);
         }
 #pragma unroll
         for (int i = 0; i < OT; ++i) {
           if constexpr (SPARSE)
-            acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+            acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
                                                                   __builtin_bit_cast(bf16x16_t, bq[j & 3]),
-                                                                  acc[i][j], s_cur[i], 0, 0);
+                                                                  acc[i][j], sfr[PP][i], 0, 0);
           else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a_cur[i]),
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
                                                                 __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
                                                                 0, 0, 0);
         }
@@ -843,8 +862,6 @@ nm_stream_kernel(const GemmArgs a) {
         __builtin_amdgcn_sched_barrier(0);
       }(), ...);
     }(std::make_integer_sequence<int, TT>{});
-#pragma unroll
-    for (int i = 0; i < OT; ++i) { a_cur[i] = a_nxt[i]; s_cur[i] = s_nxt[i]; }
     cur_off = nxt_off;
   };
 
@@ -859,12 +876,22 @@ nm_stream_kernel(const GemmArgs a) {
       f32x4_t b = f32x4_t{0.f, 0.f, 0.f, 0.f};
       if (a.bias != nullptr)
         b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + cur_off / (uint32_t)C::STAGE * (C::BO * 4) +
-                                              (wo * 64 + i * 16 + kb * 4) * 4);
+                                              (wo * C::OW + i * 16 + kb * 4) * 4);
 #pragma unroll
       for (int j = 0; j < TT; ++j) acc[i][j] = b;
     }
 
-    for (int ks = 0; ks < nk; ++ks) step();
+    // steps in pairs, so that every tile starts with fragment set 0; an odd count ends with a copy
+    for (int ks = 0; ks + 1 < nk; ks += 2) {
+      step(std::integral_constant<int, 0>{});
+      step(std::integral_constant<int, 1>{});
+    }
+    if (nk & 1) {
+      step(std::integral_constant<int, 0>{});
+      at[0] = at[1];
+#pragma unroll
+      for (int i = 0; i < OT; ++i) { afr[0][i] = afr[1][i]; sfr[0][i] = sfr[1][i]; }
+    }
     if (n + 1 == my_tiles) wait_loads_outstanding<0>();  // the surplus stages: nothing in flight when the block ends
 
     // ---- write the tile out (no LDS memory: the stage ring already holds the next tile).  A lane holds
@@ -896,7 +923,7 @@ nm_stream_kernel(const GemmArgs a) {
           piece[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s1[0]);
           piece[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s0[1]);
           piece[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s1[1]);
-          const int64_t o = o0 + wo * 64 + ip * 32 + q * 8;
+          const int64_t o = o0 + wo * C::OW + ip * 32 + q * 8;
           if (row_ok && o < a.O) *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) = piece;
         }
       } else {
@@ -909,7 +936,7 @@ nm_stream_kernel(const GemmArgs a) {
           piece[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[1]);
           piece[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[2]);
           piece[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[3]);
-          const int64_t o = o0 + wo * 64 + i * 16 + q * 4;
+          const int64_t o = o0 + wo * C::OW + i * 16 + q * 4;
           if (row_ok && o < a.O) *reinterpret_cast<u32x4_t*>(reinterpret_cast<float*>(a.Y) + t * a.ldy + o) = piece;
         }
       }
@@ -966,14 +993,14 @@ static int pick_tile(int64_t O, int64_t T) {
   const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
   const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
   int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
-  if (pick == 0 && T < 256) pick = 2;
+  if ((pick == 0 || pick == 5) && T < 256) pick = 2;
   return pick;
 }
 
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   if (K % 64) return 0;  // general kernel reads the packed layout itself
   const bool sparse_form = N <= 2 && N < M;
-  if (pick_tile(O, T) == 0) {
+  if (const int pk = pick_tile(O, T); pk == 0 || pk == 5) {
     const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // stream order, whole 256-row tiles
     return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
   }
@@ -1002,10 +1029,10 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <bool SPARSE>
+template <bool SPARSE, int WO_>
 static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
-  using C = StreamCfg<SPARSE>;
-  auto kern = nm_stream_kernel<SPARSE>;
+  using C = StreamCfg<SPARSE, WO_>;
+  auto kern = nm_stream_kernel<SPARSE, WO_>;
   static int n_cu = 0;  // filled once; a race only repeats the query
   if (!n_cu) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1029,7 +1056,8 @@ static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
 template <bool SPARSE>
 static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
-    case 0: return launch_stream<SPARSE>(g, s);
+    case 0: return launch_stream<SPARSE, 4>(g, s);
+    case 5: return launch_stream<SPARSE, 2>(g, s);
     case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_SIMPLE>(g, s);
     case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, SCHED_SIMPLE>(g, s);
     case 3: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, SCHED_SIMPLE>(g, s);
@@ -1071,7 +1099,7 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
                 (a.bias == nullptr || aligned_to(a.bias, 16));
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
 
-  if (pick == 0) {
+  if (pick == 0 || pick == 5) {
     // persistent kernel: every level goes through the stream-order pre-pass; it writes Y in 16-byte pieces only
     if (product && !g.vec_store) return launch_general(a, s);  // reads the packed layout itself
     const int64_t o_pad = ((a.O + 255) / 256) * 256;
