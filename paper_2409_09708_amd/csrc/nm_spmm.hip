@@ -138,7 +138,13 @@ recode_stream_kernel(const bf16_t* __restrict__ values, const uint32_t* __restri
   const int half = (int)(blk & 1);
   *reinterpret_cast<uint4*>(vals_s + stream_piece_offset(o, ks, 2 * half, nk)) = make_uint4(out[0], out[1], out[2], out[3]);
   *reinterpret_cast<uint4*>(vals_s + stream_piece_offset(o, ks, 2 * half + 1, nk)) = make_uint4(out[4], out[5], out[6], out[7]);
-  *reinterpret_cast<uint32_t*>(sel_s + (((o >> 8) * nk + ks) << 11) + (o & 255) * 8 + half * 4) = sel;
+  // selectors: per (tile, step) a 2 KiB block; rows r and r+16 of a 32-row pair share the word of a lane
+  // (r mod 16, kb): low half = the first row's 16 bits, high half = the second row's, which is what the
+  // matrix instruction's ABID modifier selects
+  const int r = (int)(o & 255);
+  unsigned char* word = sel_s + (((o >> 8) * nk + ks) << 11) + (r >> 5) * 256 + (r & 15) * 16 + ((r >> 4) & 1) * 2;
+  *reinterpret_cast<uint16_t*>(word + (2 * half) * 4) = (uint16_t)sel;
+  *reinterpret_cast<uint16_t*>(word + (2 * half + 1) * 4) = (uint16_t)(sel >> 16);
 }
 
 // dense form: one lane per 8 consecutive weights (one 16-byte piece)
@@ -612,12 +618,16 @@ nm_gemm_kernel(const GemmArgs a) {
 // neighbour but stores only its own) and the weight is zero-padded to whole tiles, so every tile is
 // full and lane offsets never change.
 // ---------------------------------------------------------------------------------------------
-template <bool SPARSE, int WO_>
+template <bool SPARSE, int WO_, int WT_, int STAGES_>
 struct StreamCfg {
-  // WO_ = 4: 8 waves of 64 x 128 outputs, two per SIMD; WO_ = 2: 4 waves of 128 x 128, one per SIMD (the
-  // accumulators alone fill 256 registers; a wave then has the 512-register budget)
-  static constexpr int WO = WO_, WT = 2, BO = 256, BT = 256, OT = BO / (WO * 16), TT = BT / (WT * 16);
-  static constexpr int NW = WO * WT, NT = NW * 64, STAGES = 3;
+  // Tiles are 256 out-features x (128 WT) tokens, a wave's share is 128 tokens wide.
+  //   WO 4, WT 2, 3 stages: one block of 8 waves (64 x 128 outputs each) per CU, two waves per SIMD
+  //   WO 2, WT 2, 3 stages: one block of 4 waves (128 x 128 each, 512-register budget), one wave per SIMD
+  //   WO 4, WT 1, 2 stages: 4 waves (64 x 128 each) on a 256 x 128 tile; two such blocks share a CU, so
+  //                         that one block's barrier waits and tile write-out run under the other's steps
+  static constexpr int WO = WO_, WT = WT_, BO = 256, BT = 128 * WT, OT = BO / (WO * 16), TT = 8;
+  static constexpr int NW = WO * WT, NT = NW * 64, STAGES = STAGES_;
+  static constexpr int PER_CU = (NW == 4 && STAGES == 2) ? 2 : 1;  // co-resident blocks
   static constexpr int OW = OT * 16;                     // out-features per wave
   static constexpr int KSTEP = SPARSE ? 64 : 32;         // dense k per stage
   static constexpr int X_ROWB = KSTEP * 2;               // bytes of one X row per stage
@@ -634,13 +644,13 @@ struct StreamCfg {
   static constexpr int LPW = X_PW + A_PW + S_PW;
   static_assert(WO == 2 || WO == 4, "wave layouts");
   static_assert(BO * 4 == 1024, "the bias slice of a tile is one wave-load");
-  static_assert(LDS_BYTES <= 160 * 1024 && STAGES * (LPW + 1) < 64, "LDS budget and vmcnt range");
+  static_assert(LDS_BYTES * PER_CU <= 160 * 1024 && STAGES * (LPW + 1) < 64, "LDS budget and vmcnt range");
 };
 
-template <bool SPARSE, int WO_>
-__global__ void __launch_bounds__(WO_ * 128)
+template <bool SPARSE, int WO_, int WT_, int STAGES_>
+__global__ void __launch_bounds__(WO_ * WT_ * 64, (WO_ * WT_ == 4 && STAGES_ == 2) ? 2 : (WO_ * WT_) / 4)
 nm_stream_kernel(const GemmArgs a) {
-  using C = StreamCfg<SPARSE, WO_>;
+  using C = StreamCfg<SPARSE, WO_, WT_, STAGES_>;
   constexpr int OT = C::OT, TT = C::TT, STAGES = C::STAGES;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -766,15 +776,17 @@ nm_stream_kernel(const GemmArgs a) {
   struct FragAddr { uint32_t a, s, xlo, xhi; };  // byte offsets into the dynamic LDS
   FragAddr at0;
   at0.a = (uint32_t)(C::X_BYTES + (wo * C::OW + r16) * C::A_ROWB + ((kb ^ ((r16 >> 2) & 3)) * 16));
-  at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (wo * C::OW + r16) * 8 + kb * 2);
+  at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (wo * C::OW / 32) * 256 + r16 * 16 + kb * 4);
   at0.xlo = (uint32_t)((wt * 128 + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16)));
   at0.xhi = (uint32_t)((wt * 128 + r16) * C::X_ROWB + ((4 + kb) ^ (r16 & 7)) * 16);
   auto frag_addr = [&](uint32_t stage_off) {
     return FragAddr{at0.a + stage_off, at0.s + stage_off, at0.xlo + stage_off, at0.xhi + stage_off};
   };
-  auto read_a = [&](const FragAddr& at, int i, u32x4_t& av, int& sv) {
-    av = *reinterpret_cast<const u32x4_t*>(smem + at.a + i * 16 * C::A_ROWB);
-    if (SPARSE) sv = (int)*reinterpret_cast<const int16_t*>(smem + at.s + i * 16 * 8);  // the instruction reads bits 0..15 only
+  // W fragments come in pairs of 16-row blocks: one selector word serves both (low / high half)
+  auto read_a2 = [&](const FragAddr& at, int ip, u32x4_t& av0, u32x4_t& av1, int& sv) {
+    av0 = *reinterpret_cast<const u32x4_t*>(smem + at.a + (2 * ip) * 16 * C::A_ROWB);
+    av1 = *reinterpret_cast<const u32x4_t*>(smem + at.a + (2 * ip + 1) * 16 * C::A_ROWB);
+    if (SPARSE) sv = (int)*reinterpret_cast<const uint32_t*>(smem + at.s + ip * 256);
     else sv = 0;
   };
   auto read_b = [&](const FragAddr& at, int j, bfrag_t& bv) {
@@ -800,12 +812,12 @@ nm_stream_kernel(const GemmArgs a) {
   __builtin_amdgcn_s_barrier();
 
   u32x4_t afr[2][OT];  // W fragments of the current step and of the next one; the roles alternate
-  int sfr[2][OT];
+  int sfr[2][OT / 2];
   FragAddr at[2];      // likewise the fragment addresses in the current and in the next buffer
   bfrag_t bq[4];
   at[0] = at0;
 #pragma unroll
-  for (int i = 0; i < OT; ++i) read_a(at[0], i, afr[0][i], sfr[0][i]);
+  for (int ip = 0; ip < OT / 2; ++ip) read_a2(at[0], ip, afr[0][2 * ip], afr[0][2 * ip + 1], sfr[0][ip]);
 #pragma unroll
   for (int j = 0; j < 3; ++j) read_b(at[0], j, bq[j]);
 
@@ -827,7 +839,7 @@ nm_stream_kernel(const GemmArgs a) {
         constexpr int j = J;
         if constexpr (j == TT - 3) {
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // all this wave's reads of the stage are back
-          wait_loads_outstanding<C::LPW>();                   // this wave's share of the next stage has landed
+          wait_loads_outstanding<(STAGES - 2) * C::LPW>();    // this wave's share of the next stage has landed
           __builtin_amdgcn_s_barrier();
         }
         if constexpr (j + 3 < TT) read_b(at[PP], j + 3, bq[(j + 3) & 3]);
@@ -836,20 +848,22 @@ nm_stream_kernel(const GemmArgs a) {
           // the next step's W fragments, a share in each of the last AG groups
           constexpr int part = j - (TT - AG);
 #pragma unroll
-          for (int i = part * OT / AG; i < (part + 1) * OT / AG; ++i)
-            read_a(at[PP ^ 1], i, afr[PP ^ 1][i], sfr[PP ^ 1][i]);
+          for (int ip = part * (OT / 2) / AG; ip < (part + 1) * (OT / 2) / AG; ++ip)
+            read_a2(at[PP ^ 1], ip, afr[PP ^ 1][2 * ip], afr[PP ^ 1][2 * ip + 1], sfr[PP ^ 1][ip]);
         }
-#pragma unroll
-        for (int i = 0; i < OT; ++i) {
-          if constexpr (SPARSE)
-            acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
-                                                                  __builtin_bit_cast(bf16x16_t, bq[j & 3]),
-                                                                  acc[i][j], sfr[PP][i], 0, 0);
-          else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
-                                                                __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
-                                                                0, 0, 0);
-        }
+        [&]<int... I>(std::integer_sequence<int, I...>) {
+          ([&] {
+            constexpr int i = I;
+            if constexpr (SPARSE)
+              acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
+                                                                    __builtin_bit_cast(bf16x16_t, bq[j & 3]),
+                                                                    acc[i][j], sfr[PP][i / 2], 0, i & 1);
+            else
+              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
+                                                                  __builtin_bit_cast(bf16x8_t, bq[j & 3]), acc[i][j],
+                                                                  0, 0, 0);
+          }(), ...);
+        }(std::make_integer_sequence<int, OT>{});
         if constexpr (j >= TT - 3) {
           // this wave's loads of the stage three ahead, a third after each of the last three groups
           constexpr int part = j - (TT - 3);
@@ -890,7 +904,7 @@ nm_stream_kernel(const GemmArgs a) {
       step(std::integral_constant<int, 0>{});
       at[0] = at[1];
 #pragma unroll
-      for (int i = 0; i < OT; ++i) { afr[0][i] = afr[1][i]; sfr[0][i] = sfr[1][i]; }
+      for (int i = 0; i < OT; ++i) { afr[0][i] = afr[1][i]; sfr[0][i / 2] = sfr[1][i / 2]; }
     }
     if (n + 1 == my_tiles) wait_loads_outstanding<0>();  // the surplus stages: nothing in flight when the block ends
 
@@ -993,14 +1007,14 @@ static int pick_tile(int64_t O, int64_t T) {
   const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
   const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
   int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
-  if ((pick == 0 || pick == 5) && T < 256) pick = 2;
+  if ((pick == 0 || pick >= 5) && T < 256) pick = 2;
   return pick;
 }
 
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   if (K % 64) return 0;  // general kernel reads the packed layout itself
   const bool sparse_form = N <= 2 && N < M;
-  if (const int pk = pick_tile(O, T); pk == 0 || pk == 5) {
+  if (const int pk = pick_tile(O, T); pk == 0 || pk >= 5) {
     const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // stream order, whole 256-row tiles
     return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
   }
@@ -1029,10 +1043,10 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <bool SPARSE, int WO_>
+template <bool SPARSE, int WO_, int WT_, int STAGES_>
 static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
-  using C = StreamCfg<SPARSE, WO_>;
-  auto kern = nm_stream_kernel<SPARSE, WO_>;
+  using C = StreamCfg<SPARSE, WO_, WT_, STAGES_>;
+  auto kern = nm_stream_kernel<SPARSE, WO_, WT_, STAGES_>;
   static int n_cu = 0;  // filled once; a race only repeats the query
   if (!n_cu) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1048,7 +1062,8 @@ static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
   const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
   if (n_tiles > 0x7FFFFFF0) return hipErrorInvalidValue;
   const int64_t want = ((n_tiles + 7) / 8) * 8;
-  const unsigned grid = (unsigned)(want < n_cu ? want : n_cu);  // one persistent block per CU
+  const int64_t resident = (int64_t)n_cu * C::PER_CU;  // persistent blocks: as many as fit at once
+  const unsigned grid = (unsigned)(want < resident ? want : resident);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, s, g);
   return hipGetLastError();
 }
@@ -1056,8 +1071,9 @@ static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
 template <bool SPARSE>
 static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
-    case 0: return launch_stream<SPARSE, 4>(g, s);
-    case 5: return launch_stream<SPARSE, 2>(g, s);
+    case 0: return launch_stream<SPARSE, 4, 2, 3>(g, s);
+    case 5: return launch_stream<SPARSE, 2, 2, 3>(g, s);
+    case 6: return launch_stream<SPARSE, 4, 1, 2>(g, s);
     case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_SIMPLE>(g, s);
     case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, SCHED_SIMPLE>(g, s);
     case 3: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, SCHED_SIMPLE>(g, s);
@@ -1099,7 +1115,7 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
                 (a.bias == nullptr || aligned_to(a.bias, 16));
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
 
-  if (pick == 0 || pick == 5) {
+  if (pick == 0 || pick >= 5) {
     // persistent kernel: every level goes through the stream-order pre-pass; it writes Y in 16-byte pieces only
     if (product && !g.vec_store) return launch_general(a, s);  // reads the packed layout itself
     const int64_t o_pad = ((a.O + 255) / 256) * 256;
