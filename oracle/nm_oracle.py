@@ -18,6 +18,14 @@ What it computes, and where the paper defines it:
                    the ordinary matrix product with the masked weight.  It is
                    written here as exactly that: a dense fp64 GEMM.
 
+* `nm_rank`      -- Section 3, "Subset-Superset Relationship": under one pruning
+                   criterion the weights kept at a sparser level are a subset
+                   of those kept at a denser one.  So one number per weight,
+                   its rank inside its group in the order (saliency
+                   descending, position ascending), holds every level at once:
+                   the mask of N:M is rank < N.  `rank_nibbles` is its stored
+                   form (4 bits per weight).
+
 Readings where the paper is silent or garbled (all listed in the design notes):
 zeta of Eq. (1) is the N-th LARGEST score; exactly N are kept, equal scores go
 to the lower index; groups are aligned and run along the input (reduction)
@@ -74,6 +82,41 @@ def nm_mask(w_bits: np.ndarray, N: int, M: int) -> np.ndarray:
     mask = np.zeros((O, K // M, M), dtype=bool)
     np.put_along_axis(mask, order[..., :N], True, axis=-1)
     return mask.reshape(O, K)
+
+
+def nm_rank(w_bits: np.ndarray, M: int) -> np.ndarray:
+    """Section 3, subset-superset relationship: rank [O, K] (uint8, 0..M-1) of each weight inside
+    its aligned group of M, counted in the order (saliency descending, position ascending).
+
+    The weight of rank r is the (r+1)-th to be kept as N grows, so the mask of level N:M is
+    rank < N for every N (and N = M keeps everything).
+    """
+    check_level(M, M)
+    O, K = w_bits.shape
+    if K % M:
+        raise ValueError("K must be a multiple of M")
+    key = saliency_key(w_bits).reshape(O, K // M, M)
+    order = np.argsort(-key, axis=-1, kind="stable")
+    rank = np.empty((O, K // M, M), dtype=np.uint8)
+    np.put_along_axis(rank, order, np.broadcast_to(np.arange(M, dtype=np.uint8), order.shape), axis=-1)
+    return rank.reshape(O, K)
+
+
+def rank_nibbles(rank: np.ndarray) -> np.ndarray:
+    """Stored form of the ranks: uint8 [O, K/2]; weight k sits in bits [4 (k mod 2), +4) of byte k // 2."""
+    O, K = rank.shape
+    if K % 2:
+        raise ValueError("K must be even")
+    r = rank.astype(np.uint8)
+    return (r[:, 0::2] | (r[:, 1::2] << np.uint8(4))).astype(np.uint8)
+
+
+def nibbles_to_rank(nib: np.ndarray) -> np.ndarray:
+    O, H = nib.shape
+    out = np.empty((O, 2 * H), dtype=np.uint8)
+    out[:, 0::2] = nib & np.uint8(15)
+    out[:, 1::2] = nib >> np.uint8(4)
+    return out
 
 
 def apply_mask(w_bits: np.ndarray, mask: np.ndarray) -> np.ndarray:
@@ -220,6 +263,23 @@ def nm_mask_loops(w_bits: np.ndarray, N: int, M: int) -> np.ndarray:
             for i in kept:
                 mask[o, g * M + i] = True
     return mask
+
+
+def nm_rank_loops(w_bits: np.ndarray, M: int) -> np.ndarray:
+    """The rank by counting: how many members of the group come before this one, i.e. have a larger
+    score, or the same score and a lower position."""
+    O, K = w_bits.shape
+    rank = np.zeros((O, K), dtype=np.uint8)
+    for o in range(O):
+        for g in range(K // M):
+            grp = [int(w_bits[o, g * M + i]) & 0x7FFF for i in range(M)]
+            for i in range(M):
+                before = 0
+                for j in range(M):
+                    if grp[j] > grp[i] or (grp[j] == grp[i] and j < i):
+                        before += 1
+                rank[o, g * M + i] = before
+    return rank
 
 
 def spmm_gather_loops(values: np.ndarray, indices: np.ndarray, x_bits: np.ndarray,

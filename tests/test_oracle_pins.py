@@ -351,3 +351,47 @@ def test_level_draws_are_the_documented_ones():
     assert [L.O for L in blk] == [2304, 768, 3072, 768] and blk[0].T == 12608
     sw = wl.swin_b_stages()
     assert [L.T for L in sw[::4]] == [200704, 50176, 12544, 3136]
+
+
+# --------------------------------------------------------------------------------------
+# Ranks inside a group (Section 3, subset-superset relationship): one rank per weight holds
+# every level of that M.  Pinned by the counting definition, by the nesting it expresses
+# (against the mask, which is pinned above) and by closed forms.
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M", [4, 8, 16])
+def test_rank_is_the_number_of_members_that_come_first(M):
+    rng = np.random.default_rng(300 + M)
+    W = wl.tie_heavy_weights(rng, 6, 4 * M)
+    assert np.array_equal(orc.nm_rank(W, M), orc.nm_rank_loops(W, M))
+    W = wl.draw_weights(rng, 5, 3 * M)
+    assert np.array_equal(orc.nm_rank(W, M), orc.nm_rank_loops(W, M))
+
+
+@pytest.mark.parametrize("M", [4, 8, 16])
+def test_rank_is_a_permutation_per_group_and_every_level_is_rank_below_n(M):
+    rng = np.random.default_rng(310 + M)
+    for W in (wl.draw_weights(rng, 16, 8 * M), wl.tie_heavy_weights(rng, 16, 8 * M)):
+        rank = orc.nm_rank(W, M)
+        groups = rank.reshape(W.shape[0], -1, M)
+        assert np.array_equal(np.sort(groups, axis=-1), np.broadcast_to(np.arange(M), groups.shape))
+        for N in range(1, M + 1):
+            assert np.array_equal(rank < N, orc.nm_mask(W, N, M)), (N, M)
+
+
+def test_rank_closed_forms():
+    M = 8
+    dec = wl.f32_to_bf16_bits(np.array([[8, -7, 6, -5, 4, -3, 2, -1]], dtype=np.float32))
+    assert orc.nm_rank(dec, M).tolist() == [[0, 1, 2, 3, 4, 5, 6, 7]]
+    inc = dec[:, ::-1].copy()
+    assert orc.nm_rank(inc, M).tolist() == [[7, 6, 5, 4, 3, 2, 1, 0]]
+    same = wl.f32_to_bf16_bits(np.full((1, M), -0.5, dtype=np.float32))
+    assert orc.nm_rank(same, M).tolist() == [[0, 1, 2, 3, 4, 5, 6, 7]]
+    mixed = wl.f32_to_bf16_bits(np.array([[1, -2, 2, 0]], dtype=np.float32))  # the tie goes to the lower index
+    assert orc.nm_rank(mixed, 4).tolist() == [[2, 0, 1, 3]]
+
+
+def test_rank_nibbles_round_trip_and_layout():
+    rank = np.array([[0, 3, 1, 2, 15, 14, 0, 9]], dtype=np.uint8)
+    nib = orc.rank_nibbles(rank)
+    assert nib.tolist() == [[0x30, 0x21, 0xEF, 0x90]]
+    assert np.array_equal(orc.nibbles_to_rank(nib), rank)
