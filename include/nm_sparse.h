@@ -146,6 +146,30 @@ int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int
                       uint32_t* bad_groups, void* stream);
 
 /*
+ * Nested levels from one stored rank per weight -- Section 3, "Subset-Superset Relationship": under one
+ * pruning criterion the weights kept at a sparser level are among those kept at a denser level of the same
+ * M.  The rank of a weight inside its group, in the order of the selection rule above (magnitude
+ * descending, position ascending; 0 = kept first), therefore holds every level at once: the mask of N:M is
+ * rank < N.  A supernet that derives a layer's sparse weight each time a level is sampled (Section 3.1,
+ * "Dynamic Masking") ranks a weight once per update and takes any level from the ranks.
+ *   rank layout  uint8 [O, K/2], row-major, no padding: weight k of row o in bits [4 (k mod 2), +4) of byte
+ *                o*K/2 + k/2; nm_rank_bytes(O, K) bytes (0 if the shape is illegal).
+ *   nm_rank         W [O, K] (ld ldw) -> ranks for groups of M.  A 16-byte aligned W with ldw = K and a
+ *                   16-byte aligned rank buffer run the fast kernel; any other case a slower one.
+ *   nm_rank_mask    mask words of level N:M (layout of nm_prune's mask): bit = rank < N.  For ranks written
+ *                   by nm_rank(W, M) the words equal those of nm_prune(W, N, M).
+ *   nm_pack_ranked  nm_pack with the selection read from the ranks; for ranks written by nm_rank(W, M) it
+ *                   writes the bytes nm_pack(W, mask = NULL) writes.  Ranks that are not a permutation per
+ *                   group are treated like a caller's mask with the wrong count (see nm_pack).
+ */
+size_t nm_rank_bytes(int64_t O, int64_t K);
+int32_t nm_rank(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t M, uint8_t* rank, void* stream);
+int32_t nm_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* mask,
+                     void* stream);
+int32_t nm_pack_ranked(const nm_bf16* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int32_t N,
+                       int32_t M, nm_bf16* values, uint32_t* indices, void* stream);
+
+/*
  * nm_spmm -- Y = X * W_s^T from the packed weight (Fig. 2, lower part):
  *   Y[t, o] = sum_g sum_{j<N} X[t, g*M + idx[o,g,j]] * val[o,g,j], fp32 accumulation.
  *   values, indices  in   packed layout of an [O, K] weight at level N:M

@@ -17,7 +17,11 @@ from .binding import (  # noqa: F401
     nm_mask_check,
     nm_pack,
     nm_pack_batched,
+    nm_pack_ranked,
     nm_prune,
+    nm_rank,
+    nm_rank_bytes,
+    nm_rank_mask,
     nm_spmm,
     nm_spmm_workspace_bytes,
     nm_status_string,

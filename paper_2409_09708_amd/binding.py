@@ -21,6 +21,7 @@ EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
+    "nm_rank_bytes", "nm_rank", "nm_rank_mask", "nm_pack_ranked",
 )
 
 
@@ -81,6 +82,15 @@ def load_library() -> ctypes.CDLL:
                                     c_void_p]
     lib.nm_linear_forward_prepared.restype = c_int32
     lib.nm_linear_forward_prepared.argtypes = lib.nm_linear_forward.argtypes
+    lib.nm_rank_bytes.restype = c_size_t
+    lib.nm_rank_bytes.argtypes = [c_int64, c_int64]
+    lib.nm_rank.restype = c_int32
+    lib.nm_rank.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_void_p, c_void_p]
+    lib.nm_rank_mask.restype = c_int32
+    lib.nm_rank_mask.argtypes = [c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
+    lib.nm_pack_ranked.restype = c_int32
+    lib.nm_pack_ranked.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p,
+                                   c_void_p]
     _LIB = lib
     return lib
 
@@ -162,6 +172,49 @@ def nm_prune(W, N: int, M: int, W_masked=None, stream=None):
         wm_ptr = W_masked.data_ptr()
     _check(load_library().nm_prune(W.data_ptr(), O, K, ldw, N, M, mask.data_ptr(), wm_ptr, _stream_handle(stream)))
     return mask
+
+
+def nm_rank_bytes(O: int, K: int) -> int:
+    return int(load_library().nm_rank_bytes(O, K))
+
+
+def nm_rank(W, M: int, stream=None):
+    """Ranks (uint8 [O, K/2], two 4-bit ranks per byte) of the weights inside their groups of M."""
+    torch = _torch()
+    _need(W, torch.bfloat16, "W")
+    O, K, ldw = _rows(W, "W")
+    rank = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
+    _check(load_library().nm_rank(W.data_ptr(), O, K, ldw, M, rank.data_ptr(), _stream_handle(stream)))
+    return rank
+
+
+def _need_rank(rank, O: int, K: int) -> None:
+    torch = _torch()
+    _need(rank, torch.uint8, "rank")
+    if tuple(rank.shape) != (O, K // 2) or not rank.is_contiguous():
+        raise ValueError("rank must be contiguous [O, K/2]")
+
+
+def nm_rank_mask(rank, K: int, N: int, M: int, stream=None):
+    """Mask words [O, ceil(K/32)] (int32) of level N:M from stored ranks: bit = rank < N."""
+    torch = _torch()
+    O = int(rank.shape[0])
+    _need_rank(rank, O, K)
+    mask = torch.empty((O, (K + 31) // 32), dtype=torch.int32, device=rank.device)
+    _check(load_library().nm_rank_mask(rank.data_ptr(), O, K, N, M, mask.data_ptr(), _stream_handle(stream)))
+    return mask
+
+
+def nm_pack_ranked(W, rank, N: int, M: int, stream=None):
+    """nm_pack with the selection read from stored ranks."""
+    torch = _torch()
+    _need(W, torch.bfloat16, "W")
+    O, K, ldw = _rows(W, "W")
+    _need_rank(rank, O, K)
+    values, indices = _empty_packed(O, K, N, M, W.device)
+    _check(load_library().nm_pack_ranked(W.data_ptr(), rank.data_ptr(), O, K, ldw, N, M, values.data_ptr(),
+                                         indices.data_ptr(), _stream_handle(stream)))
+    return values, indices
 
 
 def nm_pack(W, N: int, M: int, mask=None, stream=None):

@@ -107,6 +107,35 @@ int32_t nm_unpack(const nm_bf16* values, const uint32_t* indices, int64_t O, int
   return device_status(nm::launch_unpack(values, indices, O, K, N, M, W_dense, ldw, (hipStream_t)stream));
 }
 
+size_t nm_rank_bytes(int64_t O, int64_t K) {
+  if (O <= 0 || K <= 0 || (K % 4) != 0) return 0;
+  return (size_t)O * (size_t)K / 2;
+}
+
+int32_t nm_rank(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t M, uint8_t* rank, void* stream) {
+  if (!W || !rank) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, M, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(W, 2)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_rank(W, O, K, ldw, M, rank, (hipStream_t)stream));
+}
+
+int32_t nm_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* mask, void* stream) {
+  if (!rank || !mask) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (!aligned(mask, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_rank_mask(rank, O, K, N, mask, (hipStream_t)stream));
+}
+
+int32_t nm_pack_ranked(const nm_bf16* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M,
+                       nm_bf16* values, uint32_t* indices, void* stream) {
+  if (!W || !rank || !values || !indices) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(W, 2) || !aligned(values, 2) || !aligned(indices, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_pack_ranked(W, rank, O, K, ldw, N, M, values, indices, (hipStream_t)stream));
+}
+
 int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* bad_groups,
                       void* stream) {
   if (!mask || !bad_groups) return NM_ERR_NULL;

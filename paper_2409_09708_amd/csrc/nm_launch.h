@@ -24,7 +24,13 @@ hipError_t launch_pack(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N
 hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s);
 hipError_t launch_unpack(const bf16_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M,
                          bf16_t* Wd, int64_t ldw, hipStream_t s);
+hipError_t launch_pack_ranked(const bf16_t* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int N, int M,
+                              bf16_t* values, uint32_t* indices, hipStream_t s);
 hipError_t launch_mask_check(const uint32_t* mask, int64_t O, int64_t K, int N, int M, uint32_t* bad, hipStream_t s);
+
+// nm_rank.hip
+hipError_t launch_rank(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int M, uint8_t* rank, hipStream_t s);
+hipError_t launch_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int N, uint32_t* mask, hipStream_t s);
 
 // nm_spmm.hip
 struct SpmmArgs {

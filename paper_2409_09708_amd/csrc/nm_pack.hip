@@ -89,11 +89,14 @@ __device__ __forceinline__ void store_values(bf16_t* __restrict__ dst, const uin
 
 // Work of one block on 256 consecutive chunks of one contiguous matrix.
 //   values/indices may be NULL (prune only); mask_out / w_masked may be NULL (pack only).
-template <int N, int M, bool EXTERNAL_MASK>
+// SRC: where the selection comes from: 0 = magnitude (Eq. (1)), 1 = the caller's mask words, 2 = stored ranks
+// (4 bits per weight; kept = rank < N)
+template <int N, int M, int SRC>
 __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, int64_t chunk0,
                                            const uint32_t* __restrict__ mask_in, bf16_t* __restrict__ values,
                                            uint32_t* __restrict__ indices, uint32_t* __restrict__ mask_out,
                                            bf16_t* w_masked, uint32_t* sbits) {
+  constexpr bool EXTERNAL_MASK = SRC != 0;
   using Coder = ChunkCoder<N, M, EXTERNAL_MASK>;
   constexpr int NB = Coder::NB;
   constexpr bool DIRECT_INDEX = (NB == 8 || NB == 16 || NB == 32 || NB == 64);
@@ -115,7 +118,12 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
 #pragma unroll
     for (int i = 0; i < 8; ++i) { e[2 * i] = d[i] & 0xFFFFu; e[2 * i + 1] = d[i] >> 16; }
     uint32_t mask16 = 0;
-    if (EXTERNAL_MASK) mask16 = reinterpret_cast<const uint16_t*>(mask_in)[c];
+    if (SRC == 1) mask16 = reinterpret_cast<const uint16_t*>(mask_in)[c];
+    if (SRC == 2) {
+      const uint64_t r = reinterpret_cast<const uint64_t*>(mask_in)[c];
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) mask16 |= (((uint32_t)(r >> (4 * i)) & 15u) < (uint32_t)N ? 1u : 0u) << i;
+    }
     coder.run(e, mask16);
 
     if (values) store_values<Coder::NV>(values + c * Coder::NV, coder.vals);
@@ -160,13 +168,13 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
 
 constexpr int kSbitsWords = kPackThreads * 64 / 32 + 2;  // room for the widest per-chunk index field run (<= 64 bits)
 
-template <int N, int M, bool EXTERNAL_MASK>
+template <int N, int M, int SRC>
 __global__ void __launch_bounds__(kPackThreads)
 code_flat_kernel(const bf16_t* W, int64_t n_chunks, const uint32_t* __restrict__ mask_in,
                  bf16_t* __restrict__ values, uint32_t* __restrict__ indices, uint32_t* __restrict__ mask_out,
                  bf16_t* w_masked) {  // w_masked may be W itself (in-place pruning)
   __shared__ uint32_t sbits[kSbitsWords];
-  code_block<N, M, EXTERNAL_MASK>(W, n_chunks, (int64_t)blockIdx.x * kPackThreads, mask_in, values, indices,
+  code_block<N, M, SRC>(W, n_chunks, (int64_t)blockIdx.x * kPackThreads, mask_in, values, indices,
                                   mask_out, w_masked, sbits);
 }
 
@@ -221,8 +229,18 @@ __global__ void __launch_bounds__(kPackThreads) pack_batched_kernel(const BatchA
 // General kernels: any K % M == 0, any leading dimension, no alignment beyond the element.
 // ---------------------------------------------------------------------------------------------
 __device__ inline uint32_t group_keep(const bf16_t* __restrict__ W, int64_t ldw, const uint32_t* __restrict__ mask_in,
-                                      int64_t K, int64_t o, int64_t g, int N, int M, uint32_t* filled) {
+                                      int64_t K, int64_t o, int64_t g, int N, int M, uint32_t* filled,
+                                      const uint8_t* __restrict__ rank_in = nullptr) {
   *filled = 0;
+  if (rank_in) {  // stored ranks: kept = rank < N
+    uint32_t km = 0;
+    for (int i = 0; i < M; i += 2) {
+      const uint32_t byte = rank_in[(o * K + g * M + i) / 2];
+      km |= ((byte & 15u) < (uint32_t)N ? 1u : 0u) << i;
+      km |= ((byte >> 4) < (uint32_t)N ? 1u : 0u) << (i + 1);
+    }
+    return legalize_mask(km, N, M, filled);
+  }
   if (mask_in) {
     const int64_t k0 = g * M;
     const uint32_t word = mask_in[o * mask_words_per_row(K) + (k0 >> 5)];
@@ -241,13 +259,14 @@ __device__ inline int nth_set(uint32_t km, int j) {
 }
 
 __global__ void pack_values_general_kernel(const bf16_t* __restrict__ W, int64_t O, int64_t K, int64_t ldw, int N, int M,
-                                           const uint32_t* __restrict__ mask_in, bf16_t* __restrict__ values) {
+                                           const uint32_t* __restrict__ mask_in, bf16_t* __restrict__ values,
+                                           const uint8_t* __restrict__ rank_in) {
   const int64_t G = K / M;
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= O * G) return;
   const int64_t o = id / G, g = id % G;
   uint32_t filled;
-  const uint32_t km = group_keep(W, ldw, mask_in, K, o, g, N, M, &filled);
+  const uint32_t km = group_keep(W, ldw, mask_in, K, o, g, N, M, &filled, rank_in);
   int j = 0;
   for (int i = 0; i < M; ++i)
     if ((km >> i) & 1u) {
@@ -257,7 +276,8 @@ __global__ void pack_values_general_kernel(const bf16_t* __restrict__ W, int64_t
 }
 
 __global__ void pack_index_general_kernel(const bf16_t* __restrict__ W, int64_t O, int64_t K, int64_t ldw, int N, int M,
-                                          const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ indices) {
+                                          const uint32_t* __restrict__ mask_in, uint32_t* __restrict__ indices,
+                                          const uint8_t* __restrict__ rank_in) {
   const int b = log2_of(M);
   const int64_t nf = K / M * N;
   const int64_t nw = (nf * b + 31) / 32;
@@ -273,7 +293,7 @@ __global__ void pack_index_general_kernel(const bf16_t* __restrict__ W, int64_t 
   uint32_t km = 0, filled;
   for (int64_t f = f_lo; f <= f_hi; ++f) {
     const int64_t g = f / N;
-    if (g != g_cached) { km = group_keep(W, ldw, mask_in, K, o, g, N, M, &filled); g_cached = g; }
+    if (g != g_cached) { km = group_keep(W, ldw, mask_in, K, o, g, N, M, &filled, rank_in); g_cached = g; }
     const uint64_t p = (uint64_t)nth_set(km, (int)(f % N));
     const int64_t off = f * b - bit0;  // may be negative for a field that started in the previous word
     word |= off >= 0 ? (uint32_t)(p << off) : (uint32_t)(p >> (-off));
@@ -368,13 +388,13 @@ static bool flat_ok(int64_t O, int64_t K, int64_t ldw, int N, int M, const void*
   return (all & 15u) == 0;
 }
 
-template <bool EXT>
+template <int SRC>
 static bool launch_flat(int N, int M, dim3 grid, hipStream_t s, const bf16_t* W, int64_t n_chunks, const uint32_t* mask_in,
                         bf16_t* values, uint32_t* indices, uint32_t* mask_out, bf16_t* w_masked) {
   switch (N * 32 + M) {
 #define X(n, mm)                                                                                                  \
   case n * 32 + mm:                                                                                               \
-    hipLaunchKernelGGL((code_flat_kernel<n, mm, EXT>), grid, dim3(kPackThreads), 0, s, W, n_chunks, mask_in, values, \
+    hipLaunchKernelGGL((code_flat_kernel<n, mm, SRC>), grid, dim3(kPackThreads), 0, s, W, n_chunks, mask_in, values, \
                        indices, mask_out, w_masked);                                                              \
     return true;
     NM_FOR_EACH_LEVEL(X)
@@ -387,7 +407,7 @@ hipError_t launch_prune(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int 
                         bf16_t* w_masked, hipStream_t s) {
   if (flat_ok(O, K, ldw, N, M, W, mask, w_masked, nullptr, nullptr)) {
     const int64_t n_chunks = O * K / kChunk;
-    launch_flat<false>(N, M, dim3(blocks_for(n_chunks, kPackThreads)), s, W, n_chunks, nullptr, nullptr, nullptr, mask,
+    launch_flat<0>(N, M, dim3(blocks_for(n_chunks, kPackThreads)), s, W, n_chunks, nullptr, nullptr, nullptr, mask,
                        w_masked);
   } else {
     const int64_t n = O * mask_words_per_row(K);
@@ -402,15 +422,33 @@ hipError_t launch_pack(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N
   if (flat_ok(O, K, ldw, N, M, W, mask, values, indices, nullptr)) {
     const int64_t n_chunks = O * K / kChunk;
     const dim3 grid(blocks_for(n_chunks, kPackThreads));
-    if (mask) launch_flat<true>(N, M, grid, s, W, n_chunks, mask, values, indices, nullptr, nullptr);
-    else launch_flat<false>(N, M, grid, s, W, n_chunks, nullptr, values, indices, nullptr, nullptr);
+    if (mask) launch_flat<1>(N, M, grid, s, W, n_chunks, mask, values, indices, nullptr, nullptr);
+    else launch_flat<0>(N, M, grid, s, W, n_chunks, nullptr, values, indices, nullptr, nullptr);
   } else {
     const int64_t ng = O * (K / M);
     hipLaunchKernelGGL(pack_values_general_kernel, dim3(blocks_for(ng, 256)), dim3(256), 0, s, W, O, K, ldw, N, M,
-                       mask, values);
+                       mask, values, (const uint8_t*)nullptr);
     const int64_t nw = O * index_words_per_row(K, N, M);
     hipLaunchKernelGGL(pack_index_general_kernel, dim3(blocks_for(nw, 256)), dim3(256), 0, s, W, O, K, ldw, N, M, mask,
-                       indices);
+                       indices, (const uint8_t*)nullptr);
+  }
+  return hipGetLastError();
+}
+
+// nm_pack with the selection read from stored ranks (kept = rank < N)
+hipError_t launch_pack_ranked(const bf16_t* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int N, int M,
+                              bf16_t* values, uint32_t* indices, hipStream_t s) {
+  if (flat_ok(O, K, ldw, N, M, W, rank, values, indices, nullptr)) {
+    const int64_t n_chunks = O * K / kChunk;
+    launch_flat<2>(N, M, dim3(blocks_for(n_chunks, kPackThreads)), s, W, n_chunks,
+                   reinterpret_cast<const uint32_t*>(rank), values, indices, nullptr, nullptr);
+  } else {
+    const int64_t ng = O * (K / M);
+    hipLaunchKernelGGL(pack_values_general_kernel, dim3(blocks_for(ng, 256)), dim3(256), 0, s, W, O, K, ldw, N, M,
+                       (const uint32_t*)nullptr, values, rank);
+    const int64_t nw = O * index_words_per_row(K, N, M);
+    hipLaunchKernelGGL(pack_index_general_kernel, dim3(blocks_for(nw, 256)), dim3(256), 0, s, W, O, K, ldw, N, M,
+                       (const uint32_t*)nullptr, indices, rank);
   }
   return hipGetLastError();
 }

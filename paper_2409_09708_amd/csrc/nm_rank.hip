@@ -1,0 +1,122 @@
+// Nested N:M levels from one stored rank per weight (Section 3, "Subset-Superset Relationship"): under one
+// pruning criterion the weights kept at a sparser level are among those kept at a denser one, so the rank
+// of a weight inside its group of M, in the order (magnitude descending, position ascending), holds every
+// level of that M at once: the mask of N:M is rank < N.  A supernet that re-derives a layer's mask whenever
+// a new level is sampled (Section 3.1, "Dynamic Masking") ranks a weight matrix once per weight update and
+// then gets any level's mask or packed form from the ranks.
+//
+// Ranks are stored 4 bits per weight: weight k of row o in bits [4 (k mod 2), +4) of byte o*K/2 + k/2.
+// All kernels stream (HBM-bound): 2 bytes read + 1/2 byte written per weight for the ranking.
+#include "nm_device.h"
+#include "nm_launch.h"
+
+namespace nm {
+
+// ranks of the M members of one group by pairwise comparison (equal scores: the lower position goes first)
+template <int M>
+__device__ __forceinline__ uint64_t group_ranks(const uint32_t (&key)[M]) {
+  uint32_t rank[M];
+#pragma unroll
+  for (int i = 0; i < M; ++i) rank[i] = 0;
+#pragma unroll
+  for (int i = 0; i < M; ++i) {
+#pragma unroll
+    for (int j = i + 1; j < M; ++j) {
+      const bool i_first = key[i] >= key[j];
+      rank[j] += i_first ? 1u : 0u;
+      rank[i] += i_first ? 0u : 1u;
+    }
+  }
+  uint64_t packed = 0;
+#pragma unroll
+  for (int i = 0; i < M; ++i) packed |= (uint64_t)rank[i] << (4 * i);
+  return packed;
+}
+
+// contiguous matrix (ldw = K, 16-byte aligned): one lane per 16 weights = 8 bytes of ranks
+template <int M>
+__global__ void __launch_bounds__(256)
+rank_flat_kernel(const bf16_t* __restrict__ W, int64_t n_chunks, uint64_t* __restrict__ rank) {
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= n_chunks) return;
+  const uint4* src = reinterpret_cast<const uint4*>(W + c * 16);
+  const uint4 a = src[0], b = src[1];
+  const uint32_t d[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  uint64_t out = 0;
+#pragma unroll
+  for (int g = 0; g < 16 / M; ++g) {
+    uint32_t key[M];
+#pragma unroll
+    for (int i = 0; i < M; ++i) {
+      const int e = g * M + i;
+      key[i] = saliency_key((e & 1) ? (d[e >> 1] >> 16) : (d[e >> 1] & 0xFFFFu));
+    }
+    out |= group_ranks<M>(key) << (4 * M * g);
+  }
+  rank[c] = out;
+}
+
+// any leading dimension and alignment: one thread per group, M/2 bytes of ranks each
+__global__ void __launch_bounds__(256)
+rank_general_kernel(const bf16_t* __restrict__ W, int64_t O, int64_t K, int64_t ldw, int M, uint8_t* __restrict__ rank) {
+  const int64_t G = K / M;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * G) return;
+  const int64_t o = id / G, g = id % G;
+  uint32_t key[16];
+  for (int i = 0; i < M; ++i) key[i] = saliency_key(W[o * ldw + g * M + i]);
+  uint8_t* dst = rank + (o * K + g * M) / 2;  // K and M are even: a group starts on a byte
+  for (int i = 0; i < M; i += 2) {
+    uint32_t r[2];
+    for (int h = 0; h < 2; ++h) {
+      uint32_t before = 0;
+      for (int j = 0; j < M; ++j) before += (key[j] > key[i + h]) || (key[j] == key[i + h] && j < i + h);
+      r[h] = before;
+    }
+    dst[i / 2] = (uint8_t)(r[0] | (r[1] << 4));
+  }
+}
+
+// mask words of level N from ranks: one thread per 32-bit word
+__global__ void __launch_bounds__(256)
+rank_mask_kernel(const uint8_t* __restrict__ rank, int64_t O, int64_t K, int N, uint32_t* __restrict__ mask) {
+  const int64_t nw = mask_words_per_row(K);
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * nw) return;
+  const int64_t o = id / nw, w = id % nw;
+  uint32_t word = 0;
+  const int64_t k_end = (w * 32 + 32 < K) ? w * 32 + 32 : K;
+  for (int64_t k = w * 32; k < k_end; k += 2) {
+    const uint32_t byte = rank[(o * K + k) / 2];
+    word |= ((byte & 15u) < (uint32_t)N ? 1u : 0u) << (k & 31);
+    word |= ((byte >> 4) < (uint32_t)N ? 1u : 0u) << ((k & 31) + 1);
+  }
+  mask[o * nw + w] = word;
+}
+
+hipError_t launch_rank(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int M, uint8_t* rank, hipStream_t s) {
+  const bool flat = ldw == K && (O * K) % 16 == 0 && (((uintptr_t)W | (uintptr_t)rank) & 15u) == 0 &&
+                    (O * K / 16 + 255) / 256 <= 0x7FFFFFFF;
+  if (flat) {
+    const int64_t n_chunks = O * K / 16;
+    const dim3 grid((unsigned)((n_chunks + 255) / 256));
+    uint64_t* out = reinterpret_cast<uint64_t*>(rank);
+    if (M == 4) hipLaunchKernelGGL(rank_flat_kernel<4>, grid, dim3(256), 0, s, W, n_chunks, out);
+    else if (M == 8) hipLaunchKernelGGL(rank_flat_kernel<8>, grid, dim3(256), 0, s, W, n_chunks, out);
+    else hipLaunchKernelGGL(rank_flat_kernel<16>, grid, dim3(256), 0, s, W, n_chunks, out);
+  } else {
+    const int64_t n = O * (K / M);
+    if ((n + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rank_general_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, W, O, K, ldw, M, rank);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int N, uint32_t* mask, hipStream_t s) {
+  const int64_t n = O * mask_words_per_row(K);
+  if ((n + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rank_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, rank, O, K, N, mask);
+  return hipGetLastError();
+}
+
+}  // namespace nm

@@ -104,6 +104,24 @@ def test_pack_unpack_argument_errors(lib):
     assert lib.nm_mask_check(FAKE, 4, 18, 2, 4, FAKE, None) == 2
 
 
+def test_rank_argument_errors_and_sizes(lib):
+    assert lib.nm_rank_bytes(8, 64) == 8 * 32
+    assert lib.nm_rank_bytes(0, 64) == 0 and lib.nm_rank_bytes(8, 6) == 0
+    assert lib.nm_rank(None, 4, 16, 16, 4, FAKE, None) == 1
+    assert lib.nm_rank(FAKE, 4, 16, 16, 4, None, None) == 1
+    assert lib.nm_rank(FAKE, 4, 16, 16, 5, FAKE, None) == 3
+    assert lib.nm_rank(FAKE, 4, 12, 12, 8, FAKE, None) == 2
+    assert lib.nm_rank(FAKE, 4, 16, 8, 4, FAKE, None) == 2
+    assert lib.nm_rank(FAKE + 1, 4, 16, 16, 4, FAKE, None) == 4
+    assert lib.nm_rank_mask(None, 4, 16, 2, 4, FAKE, None) == 1
+    assert lib.nm_rank_mask(FAKE, 4, 16, 5, 4, FAKE, None) == 3
+    assert lib.nm_rank_mask(FAKE, 4, 16, 2, 4, FAKE + 2, None) == 4
+    assert lib.nm_pack_ranked(FAKE, None, 4, 16, 16, 2, 4, FAKE, FAKE, None) == 1
+    assert lib.nm_pack_ranked(FAKE, FAKE, 4, 16, 16, 0, 4, FAKE, FAKE, None) == 3
+    assert lib.nm_pack_ranked(FAKE, FAKE, 4, 16, 15, 2, 4, FAKE, FAKE, None) == 2
+    assert lib.nm_pack_ranked(FAKE, FAKE, 4, 16, 16, 2, 4, FAKE, FAKE + 2, None) == 4
+
+
 def test_pack_batched_argument_errors(lib):
     assert lib.nm_pack_batched(None, 1, None) == 1
     d = (binding.PackDesc * 2)()
