@@ -199,7 +199,46 @@ def main():
                 "dense_equivalent_tflops": sum(layers[j].dense_flops for j in sp) / (sp_ms * 1e-3) / 1e12,
                 "algorithmic_hbm_bytes_per_launch": sum(algorithmic_bytes(layers[j]) for j in sp) / len(sp)}
 
+    # ---- nested levels (ranks inside groups): rank the 48 weights once for their M, then take each layer's
+    # level from the ranks.  Streaming kernels: algorithmic bytes = 2 read + 1/2 written per weight for the
+    # ranking; 2.5 read + packed bytes written for the ranked pack.
+    ranks = [torch.empty((L.O, L.K // 2), dtype=torch.uint8, device=dev) for L in layers]
+    lib = nm.load_library()
+    sh = int(stream.cuda_stream)
+
+    def rank_all():
+        for W, L, r in zip(Ws, layers, ranks):
+            lib.nm_rank(W.data_ptr(), L.O, L.K, L.K, L.M, r.data_ptr(), sh)
+
+    def pack_ranked_all():
+        for W, L, r, (v, i) in zip(Ws, layers, ranks, packed):
+            lib.nm_pack_ranked(W.data_ptr(), r.data_ptr(), L.O, L.K, L.K, L.N, L.M, v.data_ptr(), i.data_ptr(), sh)
+
+    def timed(fn):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    n_weights = sum(L.O * L.K for L in layers)
+    packed_bytes = sum(v.numel() * 2 + i.numel() * 4 for v, i in packed)
+    rank_ms, pr_ms = timed(rank_all), timed(pack_ranked_all)
+    nested = {"workload": "48 DeiT-B weight matrices, one launch per matrix",
+              "rank": {"ms": rank_ms, "algorithmic_bytes": 2.5 * n_weights,
+                       "roofline": {"bound": "hbm", "achieved": 2.5 * n_weights / rank_ms / 1e6, "peak": 8000.0,
+                                    "unit": "GB/s", "frac": 2.5 * n_weights / rank_ms / 1e6 / 8000.0}},
+              "pack_ranked": {"ms": pr_ms, "algorithmic_bytes": 2.5 * n_weights + packed_bytes,
+                              "roofline": {"bound": "hbm", "achieved": (2.5 * n_weights + packed_bytes) / pr_ms / 1e6,
+                                           "peak": 8000.0, "unit": "GB/s",
+                                           "frac": (2.5 * n_weights + packed_bytes) / pr_ms / 1e6 / 8000.0}}}
+
     if args.report:
+        log(f"nested levels: rank 48 matrices {rank_ms:.3f} ms ({nested['rank']['roofline']['achieved']:.0f} GB/s), "
+            f"pack from ranks {pr_ms:.3f} ms ({nested['pack_ranked']['roofline']['achieved']:.0f} GB/s)")
         log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}")
         for L, ms in zip(layers, layer_ms):
             u = L.useful_flops / ms / 1e9
@@ -229,6 +268,7 @@ def main():
         "dense_equivalent_tflops": dense / dt / 1e12,
         "pack_ms": pack_ms,
         "roofline": roofline,
+        "nested_levels": nested,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -203,7 +203,6 @@ struct GemmArgs {
   int n_o_tiles, n_t_tiles;
   int out_bf16;
   int vec_store;  // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
-  int stream_y;   // write Y with streaming (non-temporal) stores: Y then does not push X and W out of the L2
 };
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES_>
@@ -939,14 +938,7 @@ nm_stream_kernel(const GemmArgs a) {
           piece[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s0[1]);
           piece[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s1[1]);
           const int64_t o = o0 + wo * C::OW + ip * 32 + q * 8;
-          if (row_ok && o < a.O) {
-            u32x4_t* dst = reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o);
-            // (inline asm: as two branches of plain and non-temporal C++ stores the optimiser merges them into
-            // one plain store; the trailing s_nop covers the wait state a 16-byte store needs before its data
-            // registers may be overwritten)
-            if (a.stream_y) asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 0" ::"v"(dst), "v"(piece) : "memory");
-            else *dst = piece;
-          }
+          if (row_ok && o < a.O) *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) = piece;
         }
       } else {
         const int from = (tok + 16 * q) * 4;  // lane row kb holds out-features 4 kb .. 4 kb + 3 of the block
@@ -1069,9 +1061,6 @@ static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
   g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
   const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
   if (n_tiles > 0x7FFFFFF0) return hipErrorInvalidValue;
-  // Measured: with many out-feature tiles per token tile (X re-read from the L2 by each of them) streaming
-  // stores gain 8-10 % on the 2:4 form; with few they lose, and the dense form is indifferent.
-  g.stream_y = SPARSE && g.out_bf16 && g.n_o_tiles >= 8;
   const int64_t want = ((n_tiles + 7) / 8) * 8;
   const int64_t resident = (int64_t)n_cu * C::PER_CU;  // persistent blocks: as many as fit at once
   const unsigned grid = (unsigned)(want < resident ? want : resident);
@@ -1119,7 +1108,6 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
   g.O = a.O; g.K = a.K; g.T = a.T; g.ldx = a.ldx; g.ldy = a.ldy;
   g.out_bf16 = a.out_bf16;
   g.n_o_tiles = g.n_t_tiles = 0;
-  g.stream_y = 0;
   g.sel = nullptr;
   // 16-byte pieces of Y rows: every row start and the row end fall on a piece boundary
   const int per_piece = a.out_bf16 ? 8 : 4;
