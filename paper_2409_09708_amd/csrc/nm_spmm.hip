@@ -909,20 +909,15 @@ nm_stream_kernel(const GemmArgs a) {
     if (n + 1 == my_tiles) wait_loads_outstanding<0>();  // the surplus stages: nothing in flight when the block ends
 
     // ---- write the tile out (no LDS memory: the stage ring already holds the next tile).  A lane holds
-    // out-features o .. o+3 of token r16 per 16 x 16 block.  The memory pipeline merges a store only
-    // across consecutive lanes, so the 16-byte pieces are first moved between lanes (bpermute) until
-    // lanes 4m .. 4m+3 hold 64 consecutive bytes of token m of the block row: 16 segments of 64 bytes
-    // per store instead of 64 pieces of 16.
-    const int tok = lane >> 2, q = lane & 3;
+    // out-features o .. o+3 of token r16 per 16 x 16 block; for bfloat16 two blocks are exchanged between
+    // the lane rows kb and kb^1, so that every lane owns 8 consecutive out-features (16 bytes).  (Moving the
+    // pieces further, until consecutive lanes hold consecutive bytes, makes a lone store four times faster
+    // but was measured to change nothing here: the permutes cost what the merged stores save.)
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
-      const int64_t t = t0 + wt * 128 + j * 16 + tok;
+      const int64_t t = t0 + wt * 128 + j * 16 + r16;
       const bool row_ok = t >= t_lo;
       if (a.out_bf16) {
-        // after the exchange between lane rows kb and kb^1, lane (r16, kb) owns the 8 out-features that
-        // start at (2 ip + (kb & 1)) * 16 + (kb >> 1) * 8; piece q of a token's 64 bytes sits in lane row
-        // kb = (q >> 1) + 2 (q & 1)
-        const int from = (tok + 16 * ((q >> 1) + 2 * (q & 1))) * 4;
 #pragma unroll
         for (int ip = 0; ip < OT / 2; ++ip) {
           const f32x4_t v0 = acc[2 * ip][j], v1 = acc[2 * ip + 1][j];
@@ -932,26 +927,17 @@ nm_stream_kernel(const GemmArgs a) {
           // even partner's second operand and keep theirs
           const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
           const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
-          u32x4_t piece;
-          piece[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s0[0]);
-          piece[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s1[0]);
-          piece[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s0[1]);
-          piece[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)s1[1]);
-          const int64_t o = o0 + wo * C::OW + ip * 32 + q * 8;
-          if (row_ok && o < a.O) *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) = piece;
+          const int64_t o = o0 + wo * C::OW + (2 * ip + (kb & 1)) * 16 + (kb >> 1) * 8;
+          if (row_ok && o < a.O)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) =
+                u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
         }
       } else {
-        const int from = (tok + 16 * q) * 4;  // lane row kb holds out-features 4 kb .. 4 kb + 3 of the block
 #pragma unroll
         for (int i = 0; i < OT; ++i) {
-          const u32x4_t v = __builtin_bit_cast(u32x4_t, acc[i][j]);
-          u32x4_t piece;
-          piece[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[0]);
-          piece[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[1]);
-          piece[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[2]);
-          piece[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)v[3]);
-          const int64_t o = o0 + wo * C::OW + i * 16 + q * 4;
-          if (row_ok && o < a.O) *reinterpret_cast<u32x4_t*>(reinterpret_cast<float*>(a.Y) + t * a.ldy + o) = piece;
+          const int64_t o = o0 + wo * C::OW + i * 16 + kb * 4;
+          if (row_ok && o < a.O)
+            *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(a.Y) + t * a.ldy + o) = acc[i][j];
         }
       }
     }
