@@ -137,15 +137,18 @@ def main():
                torch.empty((L.O, nm.nm_index_bytes(L.O, L.K, L.N, L.M) // (4 * L.O)), dtype=torch.int32, device=dev))
               for L in layers]
     Ys = [torch.empty((L.T, L.O), dtype=torch.bfloat16, device=dev) for L in layers]
-    ws_bytes = max(nm.nm_spmm_workspace_bytes(L.O, L.K, L.N, L.M, L.T) for L in layers)
-    workspace = torch.empty((max(ws_bytes, 256),), dtype=torch.uint8, device=dev)
+    # one operand-order workspace per layer (a deployed model keeps them; here they are rewritten every step)
+    workspaces = [torch.empty((max(nm.nm_spmm_workspace_bytes(L.O, L.K, L.N, L.M, L.T), 256),), dtype=torch.uint8,
+                              device=dev) for L in layers]
     stream = torch.cuda.current_stream()
-    pack_args = [(W, L.N, L.M) for W, L in zip(Ws, layers)]
+    pack_args = [(W, L.N, L.M, L.T) for W, L in zip(Ws, layers)]
 
     def step():
-        nm.nm_pack_batched(pack_args, stream=stream, out=packed)
-        for L, (v, i), X, Y in zip(layers, packed, Xs, Ys):
-            nm.nm_spmm(v, i, L.K, L.N, L.M, X, out=Y, workspace=workspace, stream=stream)
+        # the whole path: select + pack all 48 weights and write their operand-order forms (one launch), then
+        # the 48 products at each layer's own level
+        nm.nm_pack_prepare_batched(pack_args, stream=stream, out=packed, workspaces=workspaces)
+        for L, (v, i), X, Y, ws in zip(layers, packed, Xs, Ys, workspaces):
+            nm.nm_linear_forward_prepared(v, i, L.K, L.N, L.M, X, ws, out=Y, stream=stream)
 
     if args.calibrate_copy:
         src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev).fill_(1)
@@ -165,21 +168,19 @@ def main():
     useful = sum(L.useful_flops for L in layers)
     dense = sum(L.dense_flops for L in layers)
 
-    # ---- per-kernel durations with HIP events on the launch stream: a second pass over the same step
-    # with the two halves of every product call issued separately (weight re-coding, then the product
-    # kernel alone between the events), so that the figure is the product kernel's own duration
+    # ---- per-kernel durations with HIP events on the launch stream: a second pass over the same step with
+    # events around the batched pack and around every product launch
     reps = max(3, min(args.steps, 10))
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
           for _ in range(reps)]
     pk = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for r in range(reps):
         pk[r][0].record(stream)
-        nm.nm_pack_batched(pack_args, stream=stream, out=packed)
+        nm.nm_pack_prepare_batched(pack_args, stream=stream, out=packed, workspaces=workspaces)
         pk[r][1].record(stream)
-        for j, (L, (v, i), X, Y) in enumerate(zip(layers, packed, Xs, Ys)):
-            nm.nm_spmm_prepare(v, i, L.K, L.N, L.M, L.T, workspace=workspace, stream=stream)
+        for j, (L, (v, i), X, Y, ws) in enumerate(zip(layers, packed, Xs, Ys, workspaces)):
             ev[r][j][0].record(stream)
-            nm.nm_linear_forward_prepared(v, i, L.K, L.N, L.M, X, workspace, out=Y, stream=stream)
+            nm.nm_linear_forward_prepared(v, i, L.K, L.N, L.M, X, ws, out=Y, stream=stream)
             ev[r][j][1].record(stream)
     torch.cuda.synchronize()
     layer_ms = [float(np.median([ev[r][j][0].elapsed_time(ev[r][j][1]) for r in range(reps)])) for j in range(len(layers))]
@@ -245,8 +246,10 @@ def main():
             log(f"{L.name:<12}{L.N:>3}:{L.M:<3}{ms:>8.3f}{u:>13.1f}{L.dense_flops / ms / 1e9:>15.1f}{100 * u / PEAK_BF16_DENSE_TFLOPS:>12.1f}%")
         wbytes = sum(L.O * L.K * 2 for L in layers)
         obytes = sum(v.numel() * 2 + i.numel() * 4 for v, i in packed)
-        log(f"pack (48 matrices, one launch): {pack_ms:.3f} ms, {(wbytes + obytes) / pack_ms / 1e6:.0f} GB/s "
-            f"({wbytes / 1e6:.0f} MB read, {obytes / 1e6:.0f} MB written)")
+        sbytes = sum(nm.nm_spmm_workspace_bytes(L.O, L.K, L.N, L.M, L.T) for L in layers)
+        log(f"select + pack + operand order (48 matrices, one launch): {pack_ms:.3f} ms, "
+            f"{(wbytes + obytes + sbytes) / pack_ms / 1e6:.0f} GB/s ({wbytes / 1e6:.0f} MB read, "
+            f"{obytes / 1e6:.0f} MB packed + {sbytes / 1e6:.0f} MB operand order written)")
 
     out = {
         "metric": "N:M sparse-linear useful TFLOP/s (% bf16 MFMA peak), DeiT-B b=256",
@@ -262,7 +265,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "deit_b_linear_stack_batch256: 48 linears, T=50432, layer-wise N:M seed 0 from "
-                               "{1:4,2:4,1:8,2:8,4:8,1:16,4:16}; step = pack 48 weights + 48 sparse products, bf16 out",
+                               "{1:4,2:4,1:8,2:8,4:8,1:16,4:16}; step = select + pack 48 weights (one launch) + 48 sparse products, bf16 out",
                    "tokens": T, "layers": len(layers)},
         "pct_of_bf16_dense_peak": 100.0 * useful / dt / 1e12 / PEAK_BF16_DENSE_TFLOPS,
         "dense_equivalent_tflops": dense / dt / 1e12,

@@ -220,6 +220,30 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
                                    int32_t out_dtype, const void* workspace,
                                    size_t workspace_bytes, void* stream);
 
+/*
+ * nm_pack_prepare_batched -- for every descriptor nm_pack(mask = NULL) followed by nm_spmm_prepare, in as few
+ * launches as the shapes allow: a model's layers are compressed and made ready for their products together
+ * (Section 3, configuration alpha = (s^1 ... s^L); Section 3.1: the sparse weights are derived from the shared
+ * ones each time a configuration is chosen).  It writes exactly the bytes the two calls write.
+ *   descs  HOST array of `count` descriptors, read before the call returns.  W is [O, K] contiguous;
+ *          workspace holds nm_spmm_workspace_bytes(O, K, N, M, T) bytes, 256-byte aligned, one per layer
+ *          (NULL allowed where that size is 0); T is the token count of the product calls that follow
+ *          (nm_linear_forward_prepared with the same values, indices, workspace and T).
+ * Errors as for nm_pack and nm_spmm_prepare; NM_ERR_WORKSPACE before anything is launched.
+ */
+typedef struct nm_layer_desc {
+  const nm_bf16* W;  /* device, [O, K] contiguous */
+  nm_bf16* values;   /* device, out */
+  uint32_t* indices; /* device, out */
+  int64_t O, K;
+  int32_t N, M;
+  int64_t T;
+  void* workspace;   /* device, out */
+  size_t workspace_bytes;
+} nm_layer_desc;
+
+int32_t nm_pack_prepare_batched(const nm_layer_desc* descs, int32_t count, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     nm_mask_check,
     nm_pack,
     nm_pack_batched,
+    nm_pack_prepare_batched,
     nm_pack_ranked,
     nm_prune,
     nm_rank,

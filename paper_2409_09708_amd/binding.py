@@ -21,7 +21,7 @@ EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
-    "nm_rank_bytes", "nm_rank", "nm_rank_mask", "nm_pack_ranked",
+    "nm_rank_bytes", "nm_rank", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
 )
 
 
@@ -34,6 +34,12 @@ class NmError(RuntimeError):
 class PackDesc(ctypes.Structure):
     _fields_ = [("W", c_void_p), ("values", c_void_p), ("indices", c_void_p),
                 ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32)]
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("values", c_void_p), ("indices", c_void_p),
+                ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32),
+                ("T", c_int64), ("workspace", c_void_p), ("workspace_bytes", c_size_t)]
 
 
 def library_path() -> str:
@@ -82,6 +88,8 @@ def load_library() -> ctypes.CDLL:
                                     c_void_p]
     lib.nm_linear_forward_prepared.restype = c_int32
     lib.nm_linear_forward_prepared.argtypes = lib.nm_linear_forward.argtypes
+    lib.nm_pack_prepare_batched.restype = c_int32
+    lib.nm_pack_prepare_batched.argtypes = [ctypes.POINTER(LayerDesc), c_int32, c_void_p]
     lib.nm_rank_bytes.restype = c_size_t
     lib.nm_rank_bytes.argtypes = [c_int64, c_int64]
     lib.nm_rank.restype = c_int32
@@ -249,6 +257,30 @@ def nm_pack_batched(layers: Sequence[Tuple[object, int, int]], stream=None, out=
         descs[i] = PackDesc(W.data_ptr(), values.data_ptr(), indices.data_ptr(), O, K, N, M)
     _check(load_library().nm_pack_batched(descs, len(layers), _stream_handle(stream)))
     return outs
+
+
+def nm_pack_prepare_batched(layers: Sequence[Tuple[object, int, int, int]], stream=None, out=None, workspaces=None):
+    """nm_pack + nm_spmm_prepare for many (W, N, M, T); returns ([(values, indices), ...], [workspace or None, ...])."""
+    torch = _torch()
+    descs = (LayerDesc * len(layers))()
+    outs: List[Tuple[object, object]] = []
+    wss: List[object] = []
+    for i, (W, N, M, T) in enumerate(layers):
+        _need(W, torch.bfloat16, "W")
+        if not W.is_contiguous():
+            raise ValueError("nm_pack_prepare_batched needs contiguous weights")
+        O, K = int(W.shape[0]), int(W.shape[1])
+        values, indices = out[i] if out is not None else _empty_packed(O, K, N, M, W.device)
+        need = nm_spmm_workspace_bytes(O, K, N, M, T)
+        ws = workspaces[i] if workspaces is not None else (
+            torch.empty((need,), dtype=torch.uint8, device=W.device) if need else None)
+        outs.append((values, indices))
+        wss.append(ws)
+        descs[i] = LayerDesc(W.data_ptr(), values.data_ptr(), indices.data_ptr(), O, K, N, M, T,
+                             ws.data_ptr() if ws is not None else None,
+                             ws.numel() * ws.element_size() if ws is not None else 0)
+    _check(load_library().nm_pack_prepare_batched(descs, len(layers), _stream_handle(stream)))
+    return outs, wss
 
 
 def nm_unpack(values, indices, K: int, N: int, M: int, stream=None):

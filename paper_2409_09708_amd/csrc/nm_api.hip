@@ -98,6 +98,24 @@ int32_t nm_pack_batched(const nm_pack_desc* descs, int32_t count, void* stream) 
   return device_status(nm::launch_pack_batched(reinterpret_cast<const nm::PackDesc*>(descs), count, (hipStream_t)stream));
 }
 
+int32_t nm_pack_prepare_batched(const nm_layer_desc* descs, int32_t count, void* stream) {
+  if (!descs) return NM_ERR_NULL;
+  if (count <= 0) return NM_ERR_SHAPE;
+  static_assert(sizeof(nm_layer_desc) == sizeof(nm::LayerDesc), "descriptor layouts must match");
+  for (int32_t i = 0; i < count; ++i) {
+    const nm_layer_desc& d = descs[i];
+    if (!d.W || !d.values || !d.indices) return NM_ERR_NULL;
+    if (int32_t s = check_weight(d.O, d.K, d.N, d.M)) return s;
+    if (d.T <= 0 || d.T > (int64_t)1 << 31) return NM_ERR_SHAPE;
+    if (!aligned(d.W, 2) || !aligned(d.values, 2) || !aligned(d.indices, 4)) return NM_ERR_ALIGN;
+  }
+  bool workspace_short = false;
+  hipError_t e = nm::launch_pack_prepare_batched(reinterpret_cast<const nm::LayerDesc*>(descs), count,
+                                                 (hipStream_t)stream, &workspace_short);
+  if (workspace_short) return NM_ERR_WORKSPACE;
+  return device_status(e);
+}
+
 int32_t nm_unpack(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
                   nm_bf16* W_dense, int64_t ldw, void* stream) {
   if (!values || !indices || !W_dense) return NM_ERR_NULL;

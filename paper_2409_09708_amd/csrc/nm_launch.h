@@ -22,6 +22,18 @@ hipError_t launch_prune(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int 
 hipError_t launch_pack(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N, int M, const uint32_t* mask,
                        bf16_t* values, uint32_t* indices, hipStream_t s);
 hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s);
+// pack + operand-order workspace of the product at T tokens, for many layers
+struct LayerDesc {
+  const bf16_t* W;
+  bf16_t* values;
+  uint32_t* indices;
+  int64_t O, K;
+  int32_t N, M;
+  int64_t T;
+  void* workspace;
+  size_t workspace_bytes;
+};
+hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStream_t s, bool* workspace_short);
 hipError_t launch_unpack(const bf16_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M,
                          bf16_t* Wd, int64_t ldw, hipStream_t s);
 hipError_t launch_pack_ranked(const bf16_t* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int N, int M,
@@ -48,6 +60,7 @@ struct SpmmArgs {
   size_t workspace_bytes;
 };
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);
+bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* sparse_form);
 // phases: SPMM_PREPARE rewrites the packed weight into matrix-core operand order in the workspace,
 // SPMM_PRODUCT multiplies (expects a prepared workspace); both = the whole call.
 // returns hipSuccess or the launch error; *workspace_short is set when the workspace is required but

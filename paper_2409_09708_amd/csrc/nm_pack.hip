@@ -95,7 +95,8 @@ template <int N, int M, int SRC>
 __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, int64_t chunk0,
                                            const uint32_t* __restrict__ mask_in, bf16_t* __restrict__ values,
                                            uint32_t* __restrict__ indices, uint32_t* __restrict__ mask_out,
-                                           bf16_t* w_masked, uint32_t* sbits) {
+                                           bf16_t* w_masked, uint32_t* sbits, unsigned char* stream_ws = nullptr,
+                                           int64_t K = 0) {
   constexpr bool EXTERNAL_MASK = SRC != 0;
   using Coder = ChunkCoder<N, M, EXTERNAL_MASK>;
   constexpr int NB = Coder::NB;
@@ -143,6 +144,50 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
       }
     }
     if (mask_out) reinterpret_cast<uint16_t*>(mask_out)[c] = (uint16_t)coder.keep16;
+    if (stream_ws) {
+      // the product kernel's operand order, written beside the packed form (what nm_spmm_prepare would
+      // write from it): this lane's 16 weights are one 16-byte chunk of a row's K step
+      const int64_t per_row = K / kChunk;
+      const int64_t o = c / per_row, kc = c % per_row;
+      if constexpr (N <= 2 && N < M) {
+        // 2:4 form: per run of four the kept weights in ascending position (at most two), zero-filled, and
+        // their 2-bit positions
+        const int64_t nk = K / 64;
+        uint32_t piece[4], sel = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          uint32_t slot0 = 0, slot1 = 0, cnt = 0;
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const bool k = (coder.keep16 >> (4 * r + p)) & 1u;
+            slot0 = (k && cnt == 0) ? e[4 * r + p] : slot0;
+            slot1 = (k && cnt == 1) ? e[4 * r + p] : slot1;
+            sel |= k ? ((uint32_t)p << (4 * r + 2 * (cnt ? 1 : 0))) : 0u;
+            cnt += k ? 1u : 0u;
+          }
+          piece[r] = slot0 | (slot1 << 16);
+        }
+        *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, kc >> 2, (int)(kc & 3), nk)) =
+            make_uint4(piece[0], piece[1], piece[2], piece[3]);
+        unsigned char* sel_s = stream_ws + (size_t)(n_chunks * 16);  // the values take O*K bytes: 16 per chunk
+        *reinterpret_cast<uint16_t*>(sel_s + stream_selector_offset(o, kc >> 2, (int)(kc & 3), nk)) = (uint16_t)sel;
+      } else {
+        // dense form: the masked weights, two 16-byte pieces of a 32-wide step
+        const int64_t nk = K / 32;
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t lo = ((coder.keep16 >> (2 * i)) & 1u) ? e[2 * i] : 0u;
+          const uint32_t hi = ((coder.keep16 >> (2 * i + 1)) & 1u) ? e[2 * i + 1] : 0u;
+          w[i] = lo | (hi << 16);
+        }
+        const int64_t pc = kc * 2;
+        *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, pc >> 2, (int)(pc & 3), nk)) =
+            make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, (pc + 1) >> 2, (int)((pc + 1) & 3), nk)) =
+            make_uint4(w[4], w[5], w[6], w[7]);
+      }
+    }
     if (w_masked) {
       uint32_t o[8];
 #pragma unroll
@@ -185,11 +230,13 @@ struct BatchEntry {
   const bf16_t* W;
   bf16_t* values;
   uint32_t* indices;
+  unsigned char* stream_ws;  // NULL, or where the product kernel's operand order is written as well
   int64_t n_chunks;
+  int64_t K;
   uint32_t block_end;  // exclusive prefix end, in blocks
   uint16_t N, M;
 };
-constexpr int kBatchMax = 64;
+constexpr int kBatchMax = 56;  // 56 * 64 bytes of descriptors ride in the kernel arguments
 struct BatchArgs {
   BatchEntry e[kBatchMax];
   int count;
@@ -217,7 +264,7 @@ __global__ void __launch_bounds__(kPackThreads) pack_batched_kernel(const BatchA
 #define X(n, mm)                                                                                      \
   case n * 32 + mm:                                                                                   \
     code_block<n, mm, false>(d.W, d.n_chunks, chunk0, nullptr, d.values, d.indices, nullptr, nullptr, \
-                             sbits);                                                                  \
+                             sbits, d.stream_ws, d.K);                                                \
     break;
     NM_FOR_EACH_BATCH_LEVEL(X)
 #undef X
@@ -486,12 +533,75 @@ hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s) 
     if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
     BatchEntry& e = args.e[args.count++];
     e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
+    e.stream_ws = nullptr; e.K = d.K;
     blocks += nb;
     e.block_end = (uint32_t)blocks;
     e.N = (uint16_t)d.N; e.M = (uint16_t)d.M;
   }
   flush();
   return hipGetLastError();
+}
+
+// nm_pack(mask = NULL) + nm_spmm_prepare for many layers.  A layer whose product reads stream order and whose
+// rows fill whole 256-row tiles gets both forms from the one batched launch; any other layer is packed in the
+// batch (or alone) and prepared by its own pre-pass afterwards.
+hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStream_t s, bool* workspace_short) {
+  *workspace_short = false;
+  for (int i = 0; i < count; ++i) {
+    const LayerDesc& d = descs[i];
+    const size_t need = spmm_workspace_bytes(d.O, d.K, d.N, d.M, d.T);
+    if (need && (d.workspace == nullptr || d.workspace_bytes < need || ((uintptr_t)d.workspace & 255u))) {
+      *workspace_short = true;
+      return hipSuccess;
+    }
+  }
+  BatchArgs args;
+  args.count = 0;
+  uint64_t blocks = 0;
+  auto flush = [&]() {
+    if (args.count) {
+      hipLaunchKernelGGL(pack_batched_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, s, args);
+      args.count = 0;
+      blocks = 0;
+    }
+  };
+  for (int i = 0; i < count; ++i) {
+    const LayerDesc& d = descs[i];
+    const bool flat = batch_level(d.N, d.M) && flat_ok(d.O, d.K, d.K, d.N, d.M, d.W, d.values, d.indices, nullptr, nullptr);
+    bool sparse_form = false;
+    const bool fused = flat && spmm_stream_order(d.O, d.K, d.T, d.N, d.M, &sparse_form) && (d.O % 256) == 0;
+    if (flat) {
+      const int64_t n_chunks = d.O * d.K / kChunk;
+      const uint64_t nb = blocks_for(n_chunks, kPackThreads);
+      if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
+      BatchEntry& e = args.e[args.count++];
+      e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
+      e.stream_ws = fused ? reinterpret_cast<unsigned char*>(d.workspace) : nullptr;
+      e.K = d.K;
+      blocks += nb;
+      e.block_end = (uint32_t)blocks;
+      e.N = (uint16_t)d.N; e.M = (uint16_t)d.M;
+    } else {
+      hipError_t e = launch_pack(d.W, d.O, d.K, d.K, d.N, d.M, nullptr, d.values, d.indices, s);
+      if (e != hipSuccess) return e;
+    }
+  }
+  flush();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  for (int i = 0; i < count; ++i) {
+    const LayerDesc& d = descs[i];
+    const bool flat = batch_level(d.N, d.M) && flat_ok(d.O, d.K, d.K, d.N, d.M, d.W, d.values, d.indices, nullptr, nullptr);
+    bool sparse_form = false;
+    if (flat && spmm_stream_order(d.O, d.K, d.T, d.N, d.M, &sparse_form) && (d.O % 256) == 0) continue;
+    SpmmArgs a;
+    a.values = d.values; a.indices = d.indices; a.O = d.O; a.K = d.K; a.N = d.N; a.M = d.M;
+    a.X = nullptr; a.T = d.T; a.ldx = d.K; a.bias = nullptr; a.Y = nullptr; a.ldy = d.O; a.out_bf16 = 0;
+    a.workspace = d.workspace; a.workspace_bytes = d.workspace_bytes;
+    bool ws_short = false;
+    if ((e = launch_spmm(a, s, &ws_short, SPMM_PREPARE)) != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_unpack(const bf16_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M,

@@ -92,10 +92,6 @@ recode_to_2of4_kernel(const bf16_t* __restrict__ values, const uint32_t* __restr
 //   selector block (o_tile, ks) at ((o_tile * nk) + ks) * 2048: row r of the tile at r*8, 2 words
 // Rows from O up to the next multiple of 256 are written as zeros.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int64_t stream_piece_offset(int64_t row, int64_t step, int chunk, int64_t nk) {
-  const int r = (int)(row & 15);
-  return (((row >> 4) * nk + step) << 10) + ((r * 4 + (chunk ^ ((r >> 2) & 3))) << 4);
-}
 
 template <int N, int M>
 __global__ void __launch_bounds__(256)
@@ -141,10 +137,8 @@ recode_stream_kernel(const bf16_t* __restrict__ values, const uint32_t* __restri
   // selectors: per (tile, step) a 2 KiB block; rows r and r+16 of a 32-row pair share the word of a lane
   // (r mod 16, kb): low half = the first row's 16 bits, high half = the second row's, which is what the
   // matrix instruction's ABID modifier selects
-  const int r = (int)(o & 255);
-  unsigned char* word = sel_s + (((o >> 8) * nk + ks) << 11) + (r >> 5) * 256 + (r & 15) * 16 + ((r >> 4) & 1) * 2;
-  *reinterpret_cast<uint16_t*>(word + (2 * half) * 4) = (uint16_t)sel;
-  *reinterpret_cast<uint16_t*>(word + (2 * half + 1) * 4) = (uint16_t)(sel >> 16);
+  *reinterpret_cast<uint16_t*>(sel_s + stream_selector_offset(o, ks, 2 * half, nk)) = (uint16_t)sel;
+  *reinterpret_cast<uint16_t*>(sel_s + stream_selector_offset(o, ks, 2 * half + 1, nk)) = (uint16_t)(sel >> 16);
 }
 
 // dense form: one lane per 8 consecutive weights (one 16-byte piece)
@@ -995,6 +989,15 @@ static int pick_tile(int64_t O, int64_t T) {
   int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
   if ((pick == 0 || pick >= 5) && T < 256) pick = 2;
   return pick;
+}
+
+// Whether the product at T tokens reads this layer's weight in stream order (the persistent kernel), and if
+// so in which form (2:4 values + selectors, or dense).
+bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* sparse_form) {
+  *sparse_form = N <= 2 && N < M;
+  if (K % 64) return false;
+  const int pk = pick_tile(O, T);
+  return pk == 0 || pk >= 5;
 }
 
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {

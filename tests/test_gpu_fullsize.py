@@ -107,3 +107,33 @@ def test_batched_pack_of_the_whole_stack_matches_single_calls_and_the_checker():
             vals, idx = orc.nm_pack(Wh, orc.nm_mask(Wh, L.N, L.M), L.N, L.M)
             assert np.array_equal(host_bits(v), vals) and np.array_equal(host_words(i), idx), L
     assert len(seen) == 7
+
+
+def test_pack_prepare_batched_writes_what_the_two_calls_write():
+    # one block of DeiT-B at 50432 tokens (stream-order workspaces: 2:4 form and dense form), a layer with a
+    # ragged number of rows and a small layer (row-major workspace): packed bytes and workspaces must be
+    # identical to nm_pack + nm_spmm_prepare, and the prepared product must match the checker
+    rng = np.random.default_rng(99)
+    T = 256 * 197
+    shapes = [(2304, 768, 1, 16), (768, 768, 4, 8), (3072, 768, 2, 8), (768, 3072, 2, 4), (3000, 768, 1, 4),
+              (768, 768, 4, 16), (384, 384, 1, 8)]
+    Ts = [T, T, T, T, T, T, 197]
+    Ws = [wl.draw_weights(rng, O, K) for O, K, _, _ in shapes]
+    Wd = [dev_bf16(W) for W in Ws]
+    outs, wss = nm.nm_pack_prepare_batched([(w, N, M, t) for w, (_, _, N, M), t in zip(Wd, shapes, Ts)])
+    for (O, K, N, M), t, w, (v, i), ws in zip(shapes, Ts, Wd, outs, wss):
+        v2, i2 = nm.nm_pack(w, N, M)
+        assert torch.equal(v.view(torch.int16), v2.view(torch.int16)) and torch.equal(i, i2), (O, K, N, M)
+        ws2 = nm.nm_spmm_prepare(v2, i2, K, N, M, t)
+        assert (ws is None) == (ws2 is None), (O, K, N, M)
+        if ws is not None:
+            assert torch.equal(ws, ws2), (O, K, N, M)
+    # product through the fused preparation, checked on sampled rows
+    for idx in (3, 1):
+        O, K, N, M = shapes[idx]
+        X = wl.draw_activations(rng, T, K)
+        Y = nm.nm_linear_forward_prepared(outs[idx][0], outs[idx][1], K, N, M, dev_bf16(X), wss[idx],
+                                          out_dtype=torch.bfloat16)
+        rows = sample_rows(T, rng)
+        Yref, B = orc.nm_linear_from_bits(X[rows], Ws[idx], N, M)
+        check_output(host_output(Y[torch.from_numpy(rows).cuda()]), Yref, B, K // M * N, False, str(shapes[idx]))

@@ -177,6 +177,25 @@ def test_prepare_and_prepared_argument_errors(lib):
     assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, FAKE, 16, 32, None, FAKE, 64, 0, FAKE, need, None) == 2
 
 
+def test_pack_prepare_batched_argument_errors(lib):
+    from paper_2409_09708_amd.binding import LayerDesc
+    lib.nm_pack_prepare_batched.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_int32, ctypes.c_void_p]
+    lib.nm_pack_prepare_batched.restype = ctypes.c_int32
+    d = (LayerDesc * 1)()
+    assert lib.nm_pack_prepare_batched(None, 1, None) == 1
+    assert lib.nm_pack_prepare_batched(d, 0, None) == 2
+    d[0] = LayerDesc(FAKE, FAKE, None, 768, 768, 2, 4, 50432, None, 0)
+    assert lib.nm_pack_prepare_batched(d, 1, None) == 1
+    d[0] = LayerDesc(FAKE, FAKE, FAKE, 768, 768, 3, 2, 50432, None, 0)
+    assert lib.nm_pack_prepare_batched(d, 1, None) == 3
+    d[0] = LayerDesc(FAKE, FAKE, FAKE, 768, 768, 2, 4, 0, None, 0)
+    assert lib.nm_pack_prepare_batched(d, 1, None) == 2
+    d[0] = LayerDesc(FAKE, FAKE, FAKE, 768, 768, 2, 4, 50432, None, 0)   # a large layer needs its workspace
+    assert lib.nm_pack_prepare_batched(d, 1, None) == 6
+    d[0] = LayerDesc(FAKE, FAKE, FAKE, 768, 768, 2, 4, 50432, FAKE, 16)
+    assert lib.nm_pack_prepare_batched(d, 1, None) == 6
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "_PKG_DIR", str(tmp_path))
