@@ -615,7 +615,8 @@ nm_gemm_kernel(const GemmArgs a) {
 template <bool SPARSE, int WO_, int WT_, int STAGES_>
 struct StreamCfg {
   // Tiles are 256 out-features x (128 WT) tokens, a wave's share is 128 tokens wide.
-  //   WO 4, WT 2, 3 stages: one block of 8 waves (64 x 128 outputs each) per CU, two waves per SIMD
+  //   WO 4, WT 2, 3 stages (4 for the dense form, whose stages are 32 KiB): one block of 8 waves (64 x 128
+  //                         outputs each) per CU, two waves per SIMD
   //   WO 2, WT 2, 3 stages: one block of 4 waves (128 x 128 each, 512-register budget), one wave per SIMD
   //   WO 4, WT 1, 2 stages: 4 waves (64 x 128 each) on a 256 x 128 tile; two such blocks share a CU, so
   //                         that one block's barrier waits and tile write-out run under the other's steps
@@ -1060,7 +1061,7 @@ static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
 template <bool SPARSE>
 static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
-    case 0: return launch_stream<SPARSE, 4, 2, 3>(g, s);
+    case 0: return launch_stream<SPARSE, 4, 2, SPARSE ? 3 : 4>(g, s);  // dense stages are half the size: four fit
     case 5: return launch_stream<SPARSE, 2, 2, 3>(g, s);
     case 6: return launch_stream<SPARSE, 4, 1, 2>(g, s);
     case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_SIMPLE>(g, s);
