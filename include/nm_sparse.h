@@ -164,6 +164,15 @@ int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int
  */
 size_t nm_rank_bytes(int64_t O, int64_t K);
 int32_t nm_rank(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t M, uint8_t* rank, void* stream);
+/* One nm_rank per descriptor (W contiguous, ldw = K), in a single launch where the shapes allow: a supernet
+ * ranks all its layers after a weight update.  descs is a HOST array, read before the call returns. */
+typedef struct nm_rank_desc {
+  const nm_bf16* W; /* device, [O, K] contiguous */
+  uint8_t* rank;    /* device, out */
+  int64_t O, K;
+  int32_t M, reserved;
+} nm_rank_desc;
+int32_t nm_rank_batched(const nm_rank_desc* descs, int32_t count, void* stream);
 int32_t nm_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* mask,
                      void* stream);
 int32_t nm_pack_ranked(const nm_bf16* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int32_t N,

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     nm_pack_ranked,
     nm_prune,
     nm_rank,
+    nm_rank_batched,
     nm_rank_bytes,
     nm_rank_mask,
     nm_spmm,

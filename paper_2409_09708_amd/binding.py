@@ -21,7 +21,7 @@ EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
-    "nm_rank_bytes", "nm_rank", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
+    "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
 )
 
 
@@ -40,6 +40,11 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("W", c_void_p), ("values", c_void_p), ("indices", c_void_p),
                 ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32),
                 ("T", c_int64), ("workspace", c_void_p), ("workspace_bytes", c_size_t)]
+
+
+class RankDesc(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("rank", c_void_p), ("O", c_int64), ("K", c_int64), ("M", c_int32),
+                ("reserved", c_int32)]
 
 
 def library_path() -> str:
@@ -94,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     lib.nm_rank_bytes.argtypes = [c_int64, c_int64]
     lib.nm_rank.restype = c_int32
     lib.nm_rank.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_void_p, c_void_p]
+    lib.nm_rank_batched.restype = c_int32
+    lib.nm_rank_batched.argtypes = [ctypes.POINTER(RankDesc), c_int32, c_void_p]
     lib.nm_rank_mask.restype = c_int32
     lib.nm_rank_mask.argtypes = [c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
     lib.nm_pack_ranked.restype = c_int32
@@ -194,6 +201,23 @@ def nm_rank(W, M: int, stream=None):
     rank = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
     _check(load_library().nm_rank(W.data_ptr(), O, K, ldw, M, rank.data_ptr(), _stream_handle(stream)))
     return rank
+
+
+def nm_rank_batched(layers: Sequence[Tuple[object, int]], stream=None, out=None):
+    """One launch for many (W, M); returns the rank tensors."""
+    torch = _torch()
+    descs = (RankDesc * len(layers))()
+    outs = []
+    for i, (W, M) in enumerate(layers):
+        _need(W, torch.bfloat16, "W")
+        if not W.is_contiguous():
+            raise ValueError("nm_rank_batched needs contiguous weights")
+        O, K = int(W.shape[0]), int(W.shape[1])
+        rank = out[i] if out is not None else torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
+        outs.append(rank)
+        descs[i] = RankDesc(W.data_ptr(), rank.data_ptr(), O, K, M, 0)
+    _check(load_library().nm_rank_batched(descs, len(layers), _stream_handle(stream)))
+    return outs
 
 
 def _need_rank(rank, O: int, K: int) -> None:

@@ -138,6 +138,19 @@ int32_t nm_rank(const nm_bf16* W, int64_t O, int64_t K, int64_t ldw, int32_t M, 
   return device_status(nm::launch_rank(W, O, K, ldw, M, rank, (hipStream_t)stream));
 }
 
+int32_t nm_rank_batched(const nm_rank_desc* descs, int32_t count, void* stream) {
+  if (!descs) return NM_ERR_NULL;
+  if (count <= 0) return NM_ERR_SHAPE;
+  static_assert(sizeof(nm_rank_desc) == sizeof(nm::RankDesc), "descriptor layouts must match");
+  for (int32_t i = 0; i < count; ++i) {
+    const nm_rank_desc& d = descs[i];
+    if (!d.W || !d.rank) return NM_ERR_NULL;
+    if (int32_t s = check_weight(d.O, d.K, d.M, d.M)) return s;
+    if (!aligned(d.W, 2)) return NM_ERR_ALIGN;
+  }
+  return device_status(nm::launch_rank_batched(reinterpret_cast<const nm::RankDesc*>(descs), count, (hipStream_t)stream));
+}
+
 int32_t nm_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* mask, void* stream) {
   if (!rank || !mask) return NM_ERR_NULL;
   if (int32_t s = check_weight(O, K, N, M)) return s;

@@ -42,6 +42,13 @@ hipError_t launch_mask_check(const uint32_t* mask, int64_t O, int64_t K, int N, 
 
 // nm_rank.hip
 hipError_t launch_rank(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int M, uint8_t* rank, hipStream_t s);
+struct RankDesc {
+  const bf16_t* W;
+  uint8_t* rank;
+  int64_t O, K;
+  int32_t M, reserved;
+};
+hipError_t launch_rank_batched(const RankDesc* descs, int count, hipStream_t s);
 hipError_t launch_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int N, uint32_t* mask, hipStream_t s);
 
 // nm_spmm.hip

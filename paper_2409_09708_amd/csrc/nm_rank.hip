@@ -35,10 +35,18 @@ __device__ __forceinline__ uint64_t group_ranks(const uint32_t (&key)[M]) {
 
 // contiguous matrix (ldw = K, 16-byte aligned): one lane per 16 weights = 8 bytes of ranks
 template <int M>
+__device__ __forceinline__ void rank_chunk(const bf16_t* __restrict__ W, int64_t c, uint64_t* __restrict__ rank);
+
+template <int M>
 __global__ void __launch_bounds__(256)
 rank_flat_kernel(const bf16_t* __restrict__ W, int64_t n_chunks, uint64_t* __restrict__ rank) {
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (c >= n_chunks) return;
+  if (c < n_chunks) rank_chunk<M>(W, c, rank);
+}
+
+// the work of one lane on chunk c of a contiguous matrix
+template <int M>
+__device__ __forceinline__ void rank_chunk(const bf16_t* __restrict__ W, int64_t c, uint64_t* __restrict__ rank) {
   const uint4* src = reinterpret_cast<const uint4*>(W + c * 16);
   const uint4 a = src[0], b = src[1];
   const uint32_t d[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -54,6 +62,33 @@ rank_flat_kernel(const bf16_t* __restrict__ W, int64_t n_chunks, uint64_t* __res
     out |= group_ranks<M>(key) << (4 * M * g);
   }
   rank[c] = out;
+}
+
+// One launch for many matrices (a supernet ranks all its layers after a weight update): a block finds its
+// matrix from the running block counts, the descriptors ride in the kernel arguments.
+struct RankEntry {
+  const bf16_t* W;
+  uint64_t* rank;
+  int64_t n_chunks;
+  uint32_t block_end;  // exclusive prefix end, in blocks
+  uint32_t M;
+};
+constexpr int kRankBatchMax = 96;
+struct RankBatchArgs {
+  RankEntry e[kRankBatchMax];
+  int count;
+};
+
+__global__ void __launch_bounds__(256) rank_batched_kernel(const RankBatchArgs args) {
+  int m = 0;
+  while (m < args.count - 1 && blockIdx.x >= args.e[m].block_end) ++m;
+  const RankEntry& d = args.e[m];
+  const uint32_t first = m ? args.e[m - 1].block_end : 0u;
+  const int64_t c = (int64_t)(blockIdx.x - first) * 256 + threadIdx.x;
+  if (c >= d.n_chunks) return;
+  if (d.M == 4) rank_chunk<4>(d.W, c, d.rank);
+  else if (d.M == 8) rank_chunk<8>(d.W, c, d.rank);
+  else rank_chunk<16>(d.W, c, d.rank);
 }
 
 // any leading dimension and alignment: one thread per group, M/2 bytes of ranks each
@@ -94,10 +129,13 @@ rank_mask_kernel(const uint8_t* __restrict__ rank, int64_t O, int64_t K, int N, 
   mask[o * nw + w] = word;
 }
 
+static bool rank_flat_ok(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, const uint8_t* rank) {
+  return ldw == K && (O * K) % 16 == 0 && (((uintptr_t)W | (uintptr_t)rank) & 15u) == 0 &&
+         (O * K / 16 + 255) / 256 <= 0x7FFFFFFF;
+}
+
 hipError_t launch_rank(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int M, uint8_t* rank, hipStream_t s) {
-  const bool flat = ldw == K && (O * K) % 16 == 0 && (((uintptr_t)W | (uintptr_t)rank) & 15u) == 0 &&
-                    (O * K / 16 + 255) / 256 <= 0x7FFFFFFF;
-  if (flat) {
+  if (rank_flat_ok(W, O, K, ldw, rank)) {
     const int64_t n_chunks = O * K / 16;
     const dim3 grid((unsigned)((n_chunks + 255) / 256));
     uint64_t* out = reinterpret_cast<uint64_t*>(rank);
@@ -109,6 +147,36 @@ hipError_t launch_rank(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int M
     if ((n + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
     hipLaunchKernelGGL(rank_general_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, W, O, K, ldw, M, rank);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_rank_batched(const RankDesc* descs, int count, hipStream_t s) {
+  RankBatchArgs args;
+  args.count = 0;
+  uint64_t blocks = 0;
+  auto flush = [&]() {
+    if (args.count) {
+      hipLaunchKernelGGL(rank_batched_kernel, dim3((unsigned)blocks), dim3(256), 0, s, args);
+      args.count = 0;
+      blocks = 0;
+    }
+  };
+  for (int i = 0; i < count; ++i) {
+    const RankDesc& d = descs[i];
+    if (!rank_flat_ok(d.W, d.O, d.K, d.K, d.rank)) {
+      hipError_t e = launch_rank(d.W, d.O, d.K, d.K, d.M, d.rank, s);
+      if (e != hipSuccess) return e;
+      continue;
+    }
+    const int64_t n_chunks = d.O * d.K / 16;
+    const uint64_t nb = (uint64_t)((n_chunks + 255) / 256);
+    if (args.count == kRankBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
+    RankEntry& e = args.e[args.count++];
+    e.W = d.W; e.rank = reinterpret_cast<uint64_t*>(d.rank); e.n_chunks = n_chunks; e.M = (uint32_t)d.M;
+    blocks += nb;
+    e.block_end = (uint32_t)blocks;
+  }
+  flush();
   return hipGetLastError();
 }
 

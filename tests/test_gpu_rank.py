@@ -81,3 +81,15 @@ def test_rank_of_a_benchmark_matrix_serves_all_its_levels():
             v, i = nm.nm_pack_ranked(Wd, rank, N, M)
             v2, i2 = nm.nm_pack(Wd, N, M)
             assert torch.equal(v.view(torch.int16), v2.view(torch.int16)) and torch.equal(i, i2), (N, M)
+
+
+def test_rank_batched_equals_single_calls():
+    # a mix of shapes and group sizes, one of them not contiguous-friendly (goes through its own launch)
+    rng = np.random.default_rng(4300)
+    shapes = [(768, 768, 4), (2304, 768, 8), (301, 384, 16), (23, 40, 8), (3072, 768, 16)]
+    Ws = [dev_bf16(wl.tie_heavy_weights(rng, O, K) if i % 2 else wl.draw_weights(rng, O, K))
+          for i, (O, K, _) in enumerate(shapes)]
+    ranks = nm.nm_rank_batched([(w, M) for w, (_, _, M) in zip(Ws, shapes)])
+    for w, (O, K, M), r in zip(Ws, shapes, ranks):
+        assert torch.equal(r, nm.nm_rank(w, M)), (O, K, M)
+        assert np.array_equal(host_bytes(r), orc.rank_nibbles(orc.nm_rank(host_bits(w), M))), (O, K, M)

@@ -122,6 +122,21 @@ def test_rank_argument_errors_and_sizes(lib):
     assert lib.nm_pack_ranked(FAKE, FAKE, 4, 16, 16, 2, 4, FAKE, FAKE + 2, None) == 4
 
 
+def test_rank_batched_argument_errors(lib):
+    from paper_2409_09708_amd.binding import RankDesc
+    lib.nm_rank_batched.argtypes = [ctypes.POINTER(RankDesc), ctypes.c_int32, ctypes.c_void_p]
+    lib.nm_rank_batched.restype = ctypes.c_int32
+    d = (RankDesc * 1)()
+    assert lib.nm_rank_batched(None, 1, None) == 1
+    assert lib.nm_rank_batched(d, 0, None) == 2
+    d[0] = RankDesc(FAKE, None, 8, 64, 4, 0)
+    assert lib.nm_rank_batched(d, 1, None) == 1
+    d[0] = RankDesc(FAKE, FAKE, 8, 64, 6, 0)
+    assert lib.nm_rank_batched(d, 1, None) == 3
+    d[0] = RankDesc(FAKE, FAKE, 8, 60, 8, 0)
+    assert lib.nm_rank_batched(d, 1, None) == 2
+
+
 def test_pack_batched_argument_errors(lib):
     assert lib.nm_pack_batched(None, 1, None) == 1
     d = (binding.PackDesc * 2)()
