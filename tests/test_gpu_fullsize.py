@@ -137,3 +137,20 @@ def test_pack_prepare_batched_writes_what_the_two_calls_write():
         rows = sample_rows(T, rng)
         Yref, B = orc.nm_linear_from_bits(X[rows], Ws[idx], N, M)
         check_output(host_output(Y[torch.from_numpy(rows).cuda()]), Yref, B, K // M * N, False, str(shapes[idx]))
+
+
+@pytest.mark.parametrize("K,level,out_dtype", [(64, (2, 4), torch.float32), (192, (1, 8), torch.bfloat16),
+                                               (192, (4, 8), torch.float32), (320, (2, 16), torch.bfloat16)])
+def test_persistent_kernel_short_and_odd_reductions(K, level, out_dtype):
+    # one, three and five K steps per tile (the step loop runs in pairs), a ragged last token tile and a
+    # ragged out-feature tile, with bias: 2 x 129 tiles put the layer on the persistent kernel
+    rng = np.random.default_rng(zlib.crc32(f"short-{K}-{level}".encode()))
+    T, O = 128 * 256 + 37, 504
+    X, W = wl.draw_activations(rng, T, K), wl.draw_weights(rng, O, K)
+    bias = rng.standard_normal(O).astype(np.float32)
+    v, i = nm.nm_pack(dev_bf16(W), *level)
+    Y = nm.nm_linear_forward(v, i, K, *level, dev_bf16(X), bias=torch.from_numpy(bias).cuda(), out_dtype=out_dtype)
+    rows = sample_rows(T, rng, n=40)
+    Yref, B = orc.nm_linear_from_bits(X[rows], W, *level, bias=bias)
+    check_output(host_output(Y[torch.from_numpy(rows).cuda()]), Yref, B + np.abs(bias)[None, :],
+                 K // level[1] * level[0] + 1, out_dtype == torch.float32, f"K={K} {level}")
