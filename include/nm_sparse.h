@@ -68,7 +68,8 @@ enum {
   NM_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
   NM_ERR_DTYPE = 5,     /* out_dtype is neither NM_OUT_F32 nor NM_OUT_BF16 */
   NM_ERR_WORKSPACE = 6, /* workspace is NULL or smaller than nm_spmm_workspace_bytes() */
-  NM_ERR_DEVICE = 7     /* a HIP call failed; see nm_last_hip_error() */
+  NM_ERR_DEVICE = 7,    /* a HIP call failed; see nm_last_hip_error() */
+  NM_ERR_EXHAUSTED = 8  /* nm_sample_config ran out of random numbers before a configuration fell into the interval */
 };
 
 enum { NM_OUT_F32 = 0, NM_OUT_BF16 = 1 };
@@ -252,6 +253,32 @@ typedef struct nm_layer_desc {
 } nm_layer_desc;
 
 int32_t nm_pack_prepare_batched(const nm_layer_desc* descs, int32_t count, void* stream);
+
+/*
+ * Host-only helpers of the configuration search (no GPU work, HOST pointers throughout).
+ *
+ * nm_config_cost -- Section 3.2 ("Prioritizing Sparser Subnets"; the appendix on settings: the cost F is the
+ * network's FLOPs): F(alpha) = fixed_cost + sum_l layer_macs[l] * N[l] / M[l], a linear layer at N:M performing
+ * N/M of its dense multiply-accumulates (Section 2).  Returns -1 on a NULL pointer, L <= 0, an illegal level or
+ * a negative layer cost.  With DeiT-B's layers it gives the 17.6G (dense) and 9.2G (uniform 2:4) of Table 1.
+ *
+ * nm_sample_config -- the two-step sampling algorithm (Section 3.2, "Sampling Strategy"): (1) one of the
+ * n_edges - 1 cost intervals [edges[i], edges[i+1]) uniformly (the last one includes its upper end, since
+ * configurations with F = C_upper are admitted); (2) a configuration drawn layer by layer from the current
+ * choice probabilities, repeated until its cost falls into the interval (i.e. from the probabilities
+ * conditioned on the interval).  The random numbers are the caller's: `uniforms` holds n_uniforms numbers in
+ * [0, 1), consumed in order (one for the interval, then L per attempt); a layer's choice is the first whose
+ * cumulative probability exceeds its uniform.
+ *   choice_N, choice_M  the S levels to choose from;  probs  [L, S] row-major, each row summing to 1
+ *   choice  out [L]: index into the S levels;  interval  out;  used  out: uniforms consumed
+ * Returns NM_OK, NM_ERR_NULL / NM_ERR_SHAPE / NM_ERR_LEVEL for bad arguments (edges must increase strictly), or
+ * NM_ERR_EXHAUSTED when the uniforms run out first (choice then holds the last attempt).
+ */
+double nm_config_cost(const double* layer_macs, const int32_t* N, const int32_t* M, int32_t L, double fixed_cost);
+int32_t nm_sample_config(const double* layer_macs, int32_t L, double fixed_cost, const int32_t* choice_N,
+                         const int32_t* choice_M, int32_t S, const double* probs, const double* edges,
+                         int32_t n_edges, const double* uniforms, int64_t n_uniforms, int32_t* choice,
+                         int32_t* interval, int64_t* used);
 
 #ifdef __cplusplus
 }

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     bf16_tensor,
     library_path,
     load_library,
+    nm_config_cost,
     nm_index_bytes,
     nm_linear_forward,
     nm_linear_forward_prepared,
@@ -21,6 +22,7 @@ from .binding import (  # noqa: F401
     nm_pack_ranked,
     nm_prune,
     nm_rank,
+    nm_sample_config,
     nm_rank_batched,
     nm_rank_bytes,
     nm_rank_mask,

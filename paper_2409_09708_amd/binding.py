@@ -22,6 +22,7 @@ EXPORTS = (
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
+    "nm_config_cost", "nm_sample_config",
 )
 
 
@@ -99,6 +100,13 @@ def load_library() -> ctypes.CDLL:
     lib.nm_rank_bytes.argtypes = [c_int64, c_int64]
     lib.nm_rank.restype = c_int32
     lib.nm_rank.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_void_p, c_void_p]
+    c_double_p, c_int32_p = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_int32)
+    lib.nm_config_cost.restype = ctypes.c_double
+    lib.nm_config_cost.argtypes = [c_double_p, c_int32_p, c_int32_p, c_int32, ctypes.c_double]
+    lib.nm_sample_config.restype = c_int32
+    lib.nm_sample_config.argtypes = [c_double_p, c_int32, ctypes.c_double, c_int32_p, c_int32_p, c_int32, c_double_p,
+                                     c_double_p, c_int32, c_double_p, c_int64, c_int32_p, c_int32_p,
+                                     ctypes.POINTER(c_int64)]
     lib.nm_rank_batched.restype = c_int32
     lib.nm_rank_batched.argtypes = [ctypes.POINTER(RankDesc), c_int32, c_void_p]
     lib.nm_rank_mask.restype = c_int32
@@ -187,6 +195,38 @@ def nm_prune(W, N: int, M: int, W_masked=None, stream=None):
         wm_ptr = W_masked.data_ptr()
     _check(load_library().nm_prune(W.data_ptr(), O, K, ldw, N, M, mask.data_ptr(), wm_ptr, _stream_handle(stream)))
     return mask
+
+
+def _doubles(xs):
+    return (ctypes.c_double * len(xs))(*[float(x) for x in xs])
+
+
+def _ints(xs):
+    return (c_int32 * len(xs))(*[int(x) for x in xs])
+
+
+def nm_config_cost(layer_macs, levels, fixed_cost: float = 0.0) -> float:
+    """F(alpha) = fixed_cost + sum_l layer_macs[l] * N_l / M_l (host only)."""
+    L = len(layer_macs)
+    c = load_library().nm_config_cost(_doubles(layer_macs), _ints([n for n, _ in levels]), _ints([m for _, m in levels]),
+                                      L, float(fixed_cost))
+    if c < 0:
+        raise ValueError("illegal level or layer cost")
+    return float(c)
+
+
+def nm_sample_config(layer_macs, fixed_cost, choices, probs, edges, uniforms):
+    """Two-step sampling (host only): (interval, [choice index per layer], uniforms used); raises NmError with
+    status NM_ERR_EXHAUSTED when the uniforms run out."""
+    L, S = len(layer_macs), len(choices)
+    flat = [float(p) for row in probs for p in row]
+    choice = (c_int32 * L)()
+    interval, used = c_int32(0), c_int64(0)
+    _check(load_library().nm_sample_config(_doubles(layer_macs), L, float(fixed_cost), _ints([n for n, _ in choices]),
+                                           _ints([m for _, m in choices]), S, _doubles(flat), _doubles(edges),
+                                           len(edges), _doubles(uniforms), len(uniforms), choice,
+                                           ctypes.byref(interval), ctypes.byref(used)))
+    return int(interval.value), [int(c) for c in choice], int(used.value)
 
 
 def nm_rank_bytes(O: int, K: int) -> int:

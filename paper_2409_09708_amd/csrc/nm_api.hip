@@ -41,6 +41,7 @@ const char* nm_status_string(int32_t status) {
     case NM_ERR_DTYPE: return "unknown output type";
     case NM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case NM_ERR_DEVICE: return "a HIP call failed (see nm_last_hip_error)";
+    case NM_ERR_EXHAUSTED: return "random numbers exhausted before a configuration fell into the interval";
     default: return "unknown status";
   }
 }

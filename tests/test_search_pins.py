@@ -97,3 +97,47 @@ def test_conditional_distribution_matches_exhaustive_enumeration():
         expect = 0.5 * p / mass[i]  # interval uniformly, then the conditional probability
         got = counts.get(alpha, 0) / n
         assert abs(got - expect) < 5 * np.sqrt(expect * (1 - expect) / n) + 1e-9, (alpha, got, expect)
+
+
+# --------------------------------------------------------------------------------------
+# The library's host functions against the checker (no GPU involved: they run anywhere).
+# --------------------------------------------------------------------------------------
+def test_library_cost_matches_the_checker_and_table_1():
+    import paper_2409_09708_amd as nm
+    linear, fixed = deit_b_macs()
+    g = golden()
+    assert round(nm.nm_config_cost(linear, [(4, 4)] * 48, fixed) / 1e9, 1) == g["dense"]
+    assert round(nm.nm_config_cost(linear, [(2, 4)] * 48, fixed) / 1e9, 1) == g["uniform_2_4"]
+    rng = np.random.default_rng(3)
+    levels = [(1, 4), (2, 4), (1, 8), (2, 8), (4, 8), (1, 16), (4, 16)]
+    for _ in range(20):
+        cfg = [levels[i] for i in rng.integers(0, 7, 48)]
+        assert nm.nm_config_cost(linear, cfg, fixed) == so.config_cost(linear, cfg, fixed)
+    with pytest.raises(ValueError):
+        nm.nm_config_cost([1.0], [(3, 2)])
+
+
+def test_library_sampler_matches_the_checker_draw_for_draw():
+    import paper_2409_09708_amd as nm
+    from paper_2409_09708_amd.binding import NmError
+    rng = np.random.default_rng(5)
+    linear, fixed = deit_b_macs()
+    choices = [(1, 4), (2, 4), (4, 4)]
+    probs = rng.dirichlet(np.full(3, 8.0), size=48).tolist()
+    lo = so.config_cost(linear, [(1, 4)] * 48, fixed)
+    hi = 0.5 * so.config_cost(linear, [(4, 4)] * 48, fixed)  # C_upper = 50 % of the dense cost (appendix)
+    edges = so.cost_edges(lo, hi, 6).tolist()
+    seen = 0
+    for _ in range(40):
+        u = rng.random(1 + 48 * 300).tolist()
+        ref = so.two_step_sample(linear, fixed, choices, probs, edges, u)
+        if ref is None:
+            with pytest.raises(NmError) as e:
+                nm.nm_sample_config(linear, fixed, choices, probs, edges, u)
+            assert e.value.status == 8
+        else:
+            assert nm.nm_sample_config(linear, fixed, choices, probs, edges, u) == (ref[0], ref[1], ref[2])
+            seen += 1
+    assert seen >= 5
+    assert nm.nm_sample_config([1.0, 1.0], 0.0, choices, [[0.2, 0.3, 0.5], [0.5, 0.5, 0.0]], [0.0, 2.0],
+                               [0.9, 0.19, 0.49]) == (0, [0, 0], 3)
