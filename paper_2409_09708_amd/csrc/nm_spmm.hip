@@ -290,15 +290,10 @@ __device__ __forceinline__ void wait_loads_outstanding() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-enum { SCHED_SIMPLE = 0, SCHED_PINGPONG = 1 };
-
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, int SCHED>
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
 __global__ void __launch_bounds__(WO * WT * 64)
 nm_gemm_kernel(const GemmArgs a) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
-  constexpr bool PINGPONG = (SCHED == SCHED_PINGPONG);
-  static_assert(!PINGPONG || (C::NW % 8 == 0), "ping-pong needs one wave of each group per SIMD");
-  static_assert(SCHED == SCHED_SIMPLE || SCHED == SCHED_PINGPONG, "schedules of this kernel");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -461,11 +456,11 @@ nm_gemm_kernel(const GemmArgs a) {
   const int nk = (int)(a.K / C::KC);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s)
-    if (s < (SCHED == SCHED_SIMPLE ? STAGES - 1 : STAGES) && s < nk) issue_stage(s, s);
+    if (s < STAGES - 1 && s < nk) issue_stage(s, s);
 
-  if constexpr (SCHED == SCHED_SIMPLE) {
-    // Simple schedule: one barrier per stage; the buffer multiplied in the previous step is refilled
-    // right after the barrier, STAGES-1 stages ahead.
+  // One barrier per stage; the buffer multiplied in the previous step is refilled right after the barrier,
+  // STAGES-1 stages ahead.
+  {
     int buf = 0;
     for (int ks = 0; ks < nk; ++ks) {
       wait_stage((STAGES == 3 && ks + 1 < nk) ? 1 : 0);
@@ -479,51 +474,6 @@ nm_gemm_kernel(const GemmArgs a) {
       }
       if (++buf == STAGES) buf = 0;
     }
-  } else if constexpr (SCHED == SCHED_PINGPONG) {
-    // Ping-pong schedule.  The waves of a block form two groups (one wave of each per SIMD).  Time is
-    // cut into slots separated by block-wide barriers; group 0 reads the fragments of sub-step u in
-    // slot 2u and multiplies in slot 2u+1, group 1 does the same one slot later, so that in every
-    // slot one wave of a SIMD feeds the matrix pipe while the other one uses the LDS.
-    // Stage s occupies its buffer during slots 2sH .. 2sH+2H-1; at the start of slot 2mH (m >= 1) every
-    // wave issues the loads of stage m+STAGES-1 into the buffer stage m-1 has just left, and at the end
-    // of slot 2sH-1 every wave makes sure its share of stage s has landed.
-    const int grp = (wave >= C::NW / 2) ? 1 : 0;
-    {
-      const int issued = nk < STAGES ? nk : STAGES;
-      wait_stage(issued - 1);
-    }
-    __builtin_amdgcn_s_barrier();
-    if (grp) __builtin_amdgcn_s_barrier();  // group 1 sits out slot 0
-    int buf = 0;
-    for (int ks = 0; ks < nk; ++ks) {
-#pragma unroll
-      for (int h = 0; h < H; ++h) {
-        const bool first = (h == 0), last = (h == H - 1);
-        // younger stages in flight when stage ks+1 is awaited at the end of this stage
-        int younger = nk - (ks + 2);
-        if (younger > STAGES - 2) younger = STAGES - 2;
-        if (younger < 0) younger = 0;
-        // both groups run the same sequence; group 1 is simply one barrier behind.  The loads ride
-        // inside the multiply phases: group 0 refills the buffer stage ks-1 has left (with stage
-        // ks+STAGES-1) during its first sub-step of stage ks, group 1 refills this stage's own buffer
-        // (with stage ks+STAGES) during its last sub-step, i.e. both in the slots after 2(ks)H - 1 and
-        // 2(ks+1)H - 1 respectively, when the buffer has been read by everyone.
-        read_frags(buf, h);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (grp && last) wait_stage(younger);
-        __builtin_amdgcn_s_barrier();
-        {
-          int nbuf = buf + STAGES - 1;
-          if (nbuf >= STAGES) nbuf -= STAGES;
-          const bool ld = grp ? (last && ks + STAGES < nk) : (first && ks >= 1 && ks + STAGES - 1 < nk);
-          multiply(ld, grp ? ks + STAGES : ks + STAGES - 1, grp ? buf : nbuf);
-        }
-        if (!grp && last) wait_stage(younger);
-        __builtin_amdgcn_s_barrier();
-      }
-      if (++buf == STAGES) buf = 0;
-    }
-    if (!grp) __builtin_amdgcn_s_barrier();  // group 0 sits out the last slot
   }
 
   // ---- epilogue.  A lane holds out-features o .. o+3 (accumulator element e -> row 4*kb + e of the
@@ -614,12 +564,11 @@ nm_gemm_kernel(const GemmArgs a) {
 // ---------------------------------------------------------------------------------------------
 template <bool SPARSE, int WO_, int WT_, int STAGES_>
 struct StreamCfg {
-  // Tiles are 256 out-features x (128 WT) tokens, a wave's share is 128 tokens wide.
-  //   WO 4, WT 2, 3 stages (4 for the dense form, whose stages are 32 KiB): one block of 8 waves (64 x 128
-  //                         outputs each) per CU, two waves per SIMD
-  //   WO 2, WT 2, 3 stages: one block of 4 waves (128 x 128 each, 512-register budget), one wave per SIMD
-  //   WO 4, WT 1, 2 stages: 4 waves (64 x 128 each) on a 256 x 128 tile; two such blocks share a CU, so
-  //                         that one block's barrier waits and tile write-out run under the other's steps
+  // Tiles are 256 out-features x (128 WT) tokens, a wave's share is 128 tokens wide.  The layout in use is
+  // WO 4, WT 2: one block of 8 waves (64 x 128 outputs each) per CU, two waves per SIMD, three stages (four
+  // for the dense form, whose stages are 32 KiB).  Measured and slower on transformer-sized layers: WO 2
+  // (4 waves of 128 x 128, one per SIMD with the 512-register budget: a lone wave does not hide its own LDS
+  // and issue latency) and WT 1 with two stages (256 x 128 tiles, two blocks of 4 waves per CU).
   static constexpr int WO = WO_, WT = WT_, BO = 256, BT = 128 * WT, OT = BO / (WO * 16), TT = 8;
   static constexpr int NW = WO * WT, NT = NW * 64, STAGES = STAGES_;
   static constexpr int PER_CU = (NW == 4 && STAGES == 2) ? 2 : 1;  // co-resident blocks
@@ -988,7 +937,8 @@ static int pick_tile(int64_t O, int64_t T) {
   const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
   const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
   int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
-  if ((pick == 0 || pick >= 5) && T < 256) pick = 2;
+  if (pick != 0 && pick != 2) pick = 3;
+  if (pick == 0 && T < 256) pick = 2;
   return pick;
 }
 
@@ -998,13 +948,13 @@ bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* spar
   *sparse_form = N <= 2 && N < M;
   if (K % 64) return false;
   const int pk = pick_tile(O, T);
-  return pk == 0 || pk >= 5;
+  return pk == 0;
 }
 
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   if (K % 64) return 0;  // general kernel reads the packed layout itself
   const bool sparse_form = N <= 2 && N < M;
-  if (const int pk = pick_tile(O, T); pk == 0 || pk >= 5) {
+  if (pick_tile(O, T) == 0) {
     const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // stream order, whole 256-row tiles
     return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
   }
@@ -1013,10 +963,10 @@ size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   return sparse_form ? (size_t)(O * K) + (size_t)(O * K / 8) : (size_t)(O * K) * 2;
 }
 
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, int SCHED>
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
 static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
-  auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES, SCHED>;
+  auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES>;
   static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1062,12 +1012,8 @@ template <bool SPARSE>
 static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
     case 0: return launch_stream<SPARSE, 4, 2, SPARSE ? 3 : 4>(g, s);  // dense stages are half the size: four fit
-    case 5: return launch_stream<SPARSE, 2, 2, 3>(g, s);
-    case 6: return launch_stream<SPARSE, 4, 1, 2>(g, s);
-    case 1: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_SIMPLE>(g, s);
-    case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3, SCHED_SIMPLE>(g, s);
-    case 3: return launch_gemm<SPARSE, 2, 2, 2, 2, 3, SCHED_SIMPLE>(g, s);
-    default: return launch_gemm<SPARSE, 2, 4, 8, 4, SPARSE ? 3 : 2, SCHED_PINGPONG>(g, s);
+    case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
+    default: return launch_gemm<SPARSE, 2, 2, 2, 2, 3>(g, s);
   }
 }
 
@@ -1105,7 +1051,7 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
                 (a.bias == nullptr || aligned_to(a.bias, 16));
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
 
-  if (pick == 0 || pick >= 5) {
+  if (pick == 0) {
     // persistent kernel: every level goes through the stream-order pre-pass; it writes Y in 16-byte pieces only
     if (product && !g.vec_store) return launch_general(a, s);  // reads the packed layout itself
     const int64_t o_pad = ((a.O + 255) / 256) * 256;
