@@ -26,6 +26,17 @@ What it computes, and where the paper defines it:
                    the mask of N:M is rank < N.  `rank_nibbles` is its stored
                    form (4 bits per weight).
 
+* `nm_linear_backward` -- Section 3.2, the supernet training loop: the chosen
+                   configuration's sparse weights W(alpha) take part in the
+                   forward pass and the gradient of the loss is taken with
+                   respect to them; Section 3.1 (the weight-update figure): the
+                   sparse matrix of the applied level is what is trained, inside
+                   the shared weight.  For one layer Y = X (W (.) m)^T with the
+                   mask held fixed this is the chain rule: dX = dY (W (.) m),
+                   dW = (dY^T X) (.) m.  The unmasked product dY^T X (every
+                   shared weight receives the gradient of its position) is the
+                   other common choice and is offered as `masked_grad=False`.
+
 Readings where the paper is silent or garbled (all listed in the design notes):
 zeta of Eq. (1) is the N-th LARGEST score; exactly N are kept, equal scores go
 to the lower index; groups are aligned and run along the input (reduction)
@@ -231,6 +242,31 @@ def nm_linear_from_bits(x_bits: np.ndarray, w_bits: np.ndarray, N: int, M: int,
                         bias: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
     """prune then multiply: the whole path for one layer."""
     return nm_linear(x_bits, w_bits, nm_mask(w_bits, N, M), bias)
+
+
+def nm_linear_backward(dy_bits: np.ndarray, x_bits: np.ndarray, w_bits: np.ndarray, mask: np.ndarray,
+                       masked_grad: bool = True) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """Gradients through Y = X . (W (.) m)^T for a given dL/dY (Section 3.2: the gradient is taken
+    with respect to the sparse weights of the chosen configuration; the mask is a constant of the step).
+
+        dX[t, k] = sum_o dY[t, o] * (W (.) m)[o, k]
+        dW[o, k] = m[o, k] * sum_t dY[t, o] * X[t, k]      (masked_grad: only kept weights are trained)
+        dW[o, k] =           sum_t dY[t, o] * X[t, k]      (otherwise)
+
+    Returns dX [T, K], dW [O, K] in fp64 and the bounds BX = |dY| . |W (.) m|, BW = |dY|^T . |X| (masked like
+    dW) that scale the acceptance tolerance.
+    """
+    dY = bf16_bits_to_f64(dy_bits)
+    X = bf16_bits_to_f64(x_bits)
+    Ws = bf16_bits_to_f64(apply_mask(w_bits, mask))
+    dX = dY @ Ws
+    BX = np.abs(dY) @ np.abs(Ws)
+    dW = dY.T @ X
+    BW = np.abs(dY).T @ np.abs(X)
+    if masked_grad:
+        dW = np.where(mask, dW, 0.0)
+        BW = np.where(mask, BW, 0.0)
+    return dX, dW, BX, BW
 
 
 def useful_macs(T: int, O: int, K: int, N: int, M: int) -> int:

@@ -255,6 +255,35 @@ def test_one_token_and_one_row_edges():
         check_output(Y, Yref, B, K // M * N, True, (T, K, O, N, M))
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 8), (2, 16), (4, 8), (3, 4), (8, 8)])
+@pytest.mark.parametrize("shape", [(197, 3072, 768), (197, 768, 3072), (50, 1024, 200), (130, 704, 72), (16, 4096, 1024)])
+def test_few_tokens_long_k(N, M, shape):
+    # few output tiles and a long K (the batch-1 shapes of a transformer block and a decode-like one): the small
+    # tiles over many more K steps than the load pipeline has stages (48, 12, 16, 11, 64), ragged in both
+    # directions
+    T, K, O = shape
+    rng = np.random.default_rng(5200 + N * 17 + M + T + O)
+    X = wl.draw_activations(rng, T, K)
+    W = wl.draw_weights(rng, O, K)
+    bias = rng.standard_normal(O).astype(np.float32)
+    Yref, B = orc.nm_linear_from_bits(X, W, N, M, bias=bias)
+    B = B + np.abs(bias)[None, :]
+    Xd, bd = dev_bf16(X), torch.from_numpy(bias).cuda()
+    v, i = nm.nm_pack(dev_bf16(W), N, M)
+    whole = nm.nm_linear_forward(v, i, K, N, M, Xd, bias=bd)
+    check_output(host_output(whole), Yref, B, K // M * N + 1, True, (N, M, shape))
+    ws = nm.nm_spmm_prepare(v, i, K, N, M, T)
+    for _ in range(2):
+        assert torch.equal(whole, nm.nm_linear_forward_prepared(v, i, K, N, M, Xd, ws, bias=bd))
+    y16 = nm.nm_linear_forward_prepared(v, i, K, N, M, Xd, ws, bias=bd, out_dtype=torch.bfloat16)
+    check_output(host_output(y16), Yref, B, K // M * N + 1, False, (N, M, shape))
+    # an output view whose rows do not split into 16-byte pieces takes the element-wise write-out
+    wide = torch.zeros((T, O + 3), dtype=torch.float32, device="cuda")
+    nm.nm_linear_forward_prepared(v, i, K, N, M, Xd, ws, bias=bd, out=wide[:, 1:O + 1])
+    assert torch.equal(wide[:, 1:O + 1], whole)
+    assert int(wide[:, 0].count_nonzero()) == 0 and int(wide[:, O + 1:].count_nonzero()) == 0
+
+
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (2, 8), (1, 16), (4, 8), (8, 8)])
 def test_prepare_then_prepared_equals_the_single_call(N, M):
     rng = np.random.default_rng(4700 + N + M)
