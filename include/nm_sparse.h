@@ -231,6 +231,37 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * Training products of one sparse layer (Section 3.2: in every step the gradient of the loss is taken with
+ * respect to the sparse weights of the chosen configuration; Section 3.1, the weight-update figure: the sparse
+ * matrix of the applied level is trained inside the shared weight).  With Y = X * (W (.) m)^T and the mask m of
+ * the step held fixed:
+ *
+ *   nm_linear_backward_input    dX[t, k] = sum_o dY[t, o] * Ws[o, k], fp32 accumulation.
+ *       Ws   in   the masked dense weight W (.) m, [O, K], ld ldw (what nm_prune writes to W_masked and what
+ *                 nm_unpack restores from the packed form)
+ *       dY   in   [T, O], ld ldy            dX   out  [T, K], ld ldx, float or bfloat16 (out_dtype)
+ *   nm_linear_backward_weight   dW[o, k] = m[o, k] * sum_t dY[t, o] * X[t, k], fp32 accumulation.
+ *       dY   in   [T, O], ld ldy            X    in   [T, K], ld ldx
+ *       mask in   mask words of the step as nm_prune writes them ([O, ceil(K/32)]); pruned positions receive
+ *                 +0.  NULL = no mask: every shared weight receives the gradient of its position.
+ *       dW   out  [O, K], ld lddw, float or bfloat16 (out_dtype)
+ *       workspace scratch of nm_backward_weight_workspace_bytes(O, K, T) bytes, 256-byte aligned (the token
+ *                 reduction is cut into ranges whose partial sums are added in a fixed order, so results
+ *                 repeat bit for bit); NULL allowed when that size is 0.  Contents undefined afterwards;
+ *                 concurrent calls need distinct workspaces.
+ * The matrix-core kernels need 16-byte aligned operands, leading dimensions that are multiples of 8, K % 8 == 0
+ * and O % 32 == 0 (dX) or O % 8 == 0 (dW); other shapes run a slower general kernel with the same results.
+ * Errors: NM_ERR_NULL, NM_ERR_SHAPE (sizes <= 0, a leading dimension smaller than its row), NM_ERR_DTYPE,
+ * NM_ERR_ALIGN (element alignment), NM_ERR_WORKSPACE, NM_ERR_DEVICE.
+ */
+size_t nm_backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T);
+int32_t nm_linear_backward_input(const nm_bf16* Ws, int64_t O, int64_t K, int64_t ldw, const nm_bf16* dY,
+                                 int64_t T, int64_t ldy, void* dX, int64_t ldx, int32_t out_dtype, void* stream);
+int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64_t ldy, const nm_bf16* X,
+                                  int64_t K, int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw,
+                                  int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * nm_pack_prepare_batched -- for every descriptor nm_pack(mask = NULL) followed by nm_spmm_prepare, in as few
  * launches as the shapes allow: a model's layers are compressed and made ready for their products together
  * (Section 3, configuration alpha = (s^1 ... s^L); Section 3.1: the sparse weights are derived from the shared

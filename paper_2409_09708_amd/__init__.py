@@ -11,6 +11,9 @@ from .binding import (  # noqa: F401
     load_library,
     nm_config_cost,
     nm_index_bytes,
+    nm_backward_weight_workspace_bytes,
+    nm_linear_backward_input,
+    nm_linear_backward_weight,
     nm_linear_forward,
     nm_linear_forward_prepared,
     nm_spmm_prepare,

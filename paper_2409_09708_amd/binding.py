@@ -23,6 +23,7 @@ EXPORTS = (
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
+    "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
 )
 
 
@@ -114,6 +115,14 @@ def load_library() -> ctypes.CDLL:
     lib.nm_pack_ranked.restype = c_int32
     lib.nm_pack_ranked.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p,
                                    c_void_p]
+    lib.nm_backward_weight_workspace_bytes.restype = c_size_t
+    lib.nm_backward_weight_workspace_bytes.argtypes = [c_int64, c_int64, c_int64]
+    lib.nm_linear_backward_input.restype = c_int32
+    lib.nm_linear_backward_input.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
+                                             c_int64, c_int32, c_void_p]
+    lib.nm_linear_backward_weight.restype = c_int32
+    lib.nm_linear_backward_weight.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
+                                              c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
     _LIB = lib
     return lib
 
@@ -467,6 +476,66 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
         st = lib.nm_linear_forward(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx, bias_ptr,
                                    out.data_ptr(), ldy, code, ws_ptr, ws_bytes, _stream_handle(stream))
     _check(st)
+    return out
+
+
+def _out_matrix(out, out_dtype, rows: int, cols: int, device, name: str):
+    torch = _torch()
+    if out is not None:
+        out_dtype = out.dtype
+    out_dtype = out_dtype or torch.float32
+    if out_dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("out dtype must be float32 or bfloat16")
+    if out is None:
+        out = torch.empty((rows, cols), dtype=out_dtype, device=device)
+    r, c, ld = _rows(out, name)
+    if (r, c) != (rows, cols):
+        raise ValueError(f"{name} must be [{rows}, {cols}]")
+    return out, ld, (NM_OUT_F32 if out_dtype == torch.float32 else NM_OUT_BF16)
+
+
+def nm_linear_backward_input(Ws, dY, out_dtype=None, out=None, stream=None):
+    """dX = dY * Ws for the masked dense weight Ws [O, K] and dY [T, O]; float32 (default) or bfloat16 [T, K]."""
+    torch = _torch()
+    _need(Ws, torch.bfloat16, "Ws")
+    _need(dY, torch.bfloat16, "dY")
+    O, K, ldw = _rows(Ws, "Ws")
+    T, OY, ldy = _rows(dY, "dY")
+    if OY != O:
+        raise ValueError("dY must be [T, O]")
+    out, ldx, code = _out_matrix(out, out_dtype, T, K, dY.device, "dX")
+    _check(load_library().nm_linear_backward_input(Ws.data_ptr(), O, K, ldw, dY.data_ptr(), T, ldy, out.data_ptr(), ldx,
+                                                   code, _stream_handle(stream)))
+    return out
+
+
+def nm_backward_weight_workspace_bytes(O: int, K: int, T: int) -> int:
+    return int(load_library().nm_backward_weight_workspace_bytes(O, K, T))
+
+
+def nm_linear_backward_weight(dY, X, mask=None, out_dtype=None, out=None, workspace=None, stream=None):
+    """dW = dY^T * X, with pruned positions zeroed when the step's mask words are given; [O, K]."""
+    torch = _torch()
+    _need(dY, torch.bfloat16, "dY")
+    _need(X, torch.bfloat16, "X")
+    T, O, ldy = _rows(dY, "dY")
+    TX, K, ldx = _rows(X, "X")
+    if TX != T:
+        raise ValueError("dY and X must have the same number of rows")
+    mask_ptr = None
+    if mask is not None:
+        _need(mask, torch.int32, "mask")
+        if tuple(mask.shape) != (O, (K + 31) // 32) or not mask.is_contiguous():
+            raise ValueError("mask must be contiguous [O, ceil(K/32)] words")
+        mask_ptr = mask.data_ptr()
+    out, lddw, code = _out_matrix(out, out_dtype, O, K, dY.device, "dW")
+    need = nm_backward_weight_workspace_bytes(O, K, T)
+    if workspace is None and need:
+        workspace = _workspace(need, dY.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().nm_linear_backward_weight(dY.data_ptr(), T, O, ldy, X.data_ptr(), K, ldx, mask_ptr,
+                                                    out.data_ptr(), lddw, code, ws_ptr, ws_bytes, _stream_handle(stream)))
     return out
 
 

@@ -1,0 +1,514 @@
+// Training products of one sparse linear layer (Section 3.2: the gradient of the loss is taken with
+// respect to the sparse weights of the chosen configuration; Section 3.1, weight-update figure: the
+// sparse matrix of the applied level is what is trained inside the shared weight).  With the mask of
+// the step held fixed and Y = X (W (.) m)^T:
+//
+//   dX[t, k] = sum_o dY[t, o] * (W (.) m)[o, k]            reduction over the out-features
+//   dW[o, k] = sum_t dY[t, o] * X[t, k]   ((.) m[o, k])     reduction over the tokens
+//
+// Both are dense products (the weight is N:M along k, which is an OUTPUT index of dX, so no term of
+// the reduction can be skipped), and in both the reduction index is the ROW index of an operand as
+// it lies in memory: W (.) m is [O, K], dY is [T, O], X is [T, K].  The matrix instruction wants, per
+// lane, 8 consecutive reduction indices of one row.  Instead of transposing operands in HBM, a tile
+// travels global -> LDS as it lies (rows = reduction index) and the fragments are read with the
+// transposing LDS read of gfx950 (ds_read_b64_tr_b16): in each group of 16 lanes, lanes 4e .. 4e+3
+// name the 16 elements of "row" e (4 each), and lane i receives element i of rows 0 .. 3, i.e. four
+// consecutive reduction indices of column i.
+//
+// One kernel serves both products:  C[i, j] = sum_r P[r, i] * Q(j, r), stored as Out[j, i]:
+//   dX: P = W (.) m [r = o, i = k], Q = dY as [j = t, r = o] (reduction contiguous), Out = dX [t, k]
+//   dW: P = X       [r = t, i = k], Q = dY as [r = t, j = o] (reduction = row),       Out = dW [o, k]
+// The token reduction of dW is long and its output small (a few dozen 128 x 128 tiles), so it is cut
+// into `splits` ranges; every block leaves an fp32 partial tile and a second kernel adds the partial
+// tiles in split order (the result does not depend on scheduling), applies the mask and rounds.
+#include "nm_device.h"
+#include "nm_launch.h"
+#include "nm_mma.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace nm {
+
+namespace {
+
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4_t* lds_i16x4_ptr;
+
+struct TGemmArgs {
+  const bf16_t* P;  // [R, I], ld ldp
+  const bf16_t* Q;  // Q_STRIDED: [R, J], else [J, R]; ld ldq
+  int64_t I, J, R, ldp, ldq;
+  void* out;        // splits == 1: Out[J, I], ld ldo
+  int64_t ldo;
+  int out_bf16;
+  int vec_store;    // Out rows split into whole aligned 16-byte pieces
+  int n_i_tiles, n_j_tiles;
+  int splits;       // > 1 (then a multiple of 8): partial tiles go to `partial`
+  float* partial;   // [split][tile][accumulator][thread], 16 bytes per thread
+};
+
+struct TCfg {
+  static constexpr int WI = 2, WJ = 2, IT = 4, JT = 4;
+  static constexpr int NW = WI * WJ, NT = NW * 64;
+  static constexpr int BI = WI * IT * 16, BJ = WJ * JT * 16;  // 128 x 128 outputs per block
+  static constexpr int RS = 32;                                // reduction indices per stage: one instruction deep
+  static constexpr int STAGES = 4;
+  static constexpr int P_BYTES = RS * BI * 2, Q_BYTES = RS * BJ * 2;
+  static constexpr int STAGE = P_BYTES + Q_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE;
+  static constexpr int P_PW = P_BYTES / 1024 / NW, Q_PW = Q_BYTES / 1024 / NW;  // wave-wide loads per wave
+  static constexpr int LPW = P_PW + Q_PW;
+  static constexpr int MMA = IT * JT;
+  static_assert(BI == 128 && BJ == 128 && P_PW == 2 && Q_PW == 2, "tile layout");
+};
+
+// Transposing fragment read from a tile stored as [RS rows (reduction)][128 columns], 256 bytes per row, the
+// 16-byte pieces of row r at slot (piece ^ 2 (r & 3)): the 16 lanes of a group touch four rows, and the
+// swizzle puts their 32-byte runs on different banks.  Lane (c16 = lane % 16, kb = lane / 16) receives the
+// reduction indices 8 kb .. 8 kb + 7 of column 16 * block + c16.
+__device__ __forceinline__ u32x4_t read_transposed(const unsigned char* tile, int block, int c16, int kb) {
+  const int sub = c16 >> 2;  // row inside the group of four; also (row & 3)
+  const int off = (8 * kb + sub) * 256 + ((2 * (block ^ sub) + ((c16 & 3) >> 1)) << 4) + (c16 & 1) * 8;
+  const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off));
+  const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off + 4 * 256));
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+  const u32x2_t l = __builtin_bit_cast(u32x2_t, lo), h = __builtin_bit_cast(u32x2_t, hi);
+  return u32x4_t{l[0], l[1], h[0], h[1]};
+}
+
+template <bool Q_STRIDED>
+__global__ void __launch_bounds__(TCfg::NT, 2)
+nm_tgemm_kernel(const TGemmArgs a) {
+  using C = TCfg;
+  constexpr int IT = C::IT, JT = C::JT, STAGES = C::STAGES;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+  // Block -> (tile, split).  Consecutive block ids land on different XCDs (8, each with its own L2).
+  // One range: every XCD takes a contiguous run of tiles, i fastest, so the blocks that share an L2 share
+  // Q rows.  Split reduction: split s lives on XCD s % 8 with all its tiles, so each range of rows of P and Q
+  // is fetched into one L2 only.
+  const int n_tiles = a.n_i_tiles * a.n_j_tiles;
+  int tile, split = 0;
+  if (a.splits > 1) {
+    const int idx = (int)(blockIdx.x >> 3);
+    split = (int)(blockIdx.x & 7) + 8 * (idx / n_tiles);
+    tile = idx % n_tiles;
+  } else {
+    const int per_xcd = (n_tiles + 7) >> 3;
+    tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (tile >= n_tiles) return;
+  }
+  const int64_t i0 = (int64_t)(tile % a.n_i_tiles) * C::BI;
+  const int64_t j0 = (int64_t)(tile / a.n_i_tiles) * C::BJ;
+
+  // this block's reduction steps
+  const int64_t steps_all = (a.R + C::RS - 1) / C::RS;
+  int64_t step_first = 0, nk = steps_all;
+  if (a.splits > 1) {
+    const int64_t share = steps_all / a.splits, extra = steps_all % a.splits;
+    step_first = split * share + (split < extra ? split : extra);
+    nk = share + (split < extra ? 1 : 0);
+  }
+  const int64_t r_first = step_first * C::RS;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wi = wave % C::WI;
+  const int wj = wave / C::WI;
+  const int c16 = lane & 15;
+  const int kb = lane >> 4;
+
+  // ---- this wave's loads of a stage.  Reduction-major tiles: load n covers rows 4n .. 4n+3, lane -> (row
+  // 4n + lane / 16, slot lane % 16), the slot holds global piece slot ^ 2 (row & 3).  Columns past the edge
+  // re-read the last whole piece of the row (those outputs are never stored).  Rows past R are clamped to
+  // stay inside the operand and zeroed in LDS before use.
+  int p_row[C::P_PW], q_row[C::Q_PW];       // row inside the stage (reduction-major) or inside the tile
+  uint32_t p_col[C::P_PW], q_col[C::Q_PW];  // byte offset inside the row
+  uint32_t p_dst[C::P_PW], q_dst[C::Q_PW];
+  const int64_t p_last_piece = (a.I - i0) / 8 - 1;
+#pragma unroll
+  for (int d = 0; d < C::P_PW; ++d) {
+    const int n = wave + d * C::NW;
+    int64_t piece = (lane & 15) ^ (2 * (lane >> 4));
+    if (piece > p_last_piece) piece = p_last_piece;
+    p_row[d] = 4 * n + (lane >> 4);
+    p_col[d] = (uint32_t)(piece * 16);
+    p_dst[d] = (uint32_t)(n * 1024);
+  }
+  const int64_t q_last_piece = (a.J - j0) / 8 - 1, q_last_row = a.J - 1 - j0;
+#pragma unroll
+  for (int d = 0; d < C::Q_PW; ++d) {
+    const int n = wave + d * C::NW;
+    if (Q_STRIDED) {
+      int64_t piece = (lane & 15) ^ (2 * (lane >> 4));
+      if (piece > q_last_piece) piece = q_last_piece;
+      q_row[d] = 4 * n + (lane >> 4);
+      q_col[d] = (uint32_t)(piece * 16);
+    } else {
+      // [128 rows j][32 reduction indices]: 64 bytes per row, load n covers rows 16n .. 16n+15, lane ->
+      // (row 16n + lane / 4, slot lane % 4), the slot holds piece slot ^ ((row >> 2) & 3)
+      int64_t row = 16 * n + (lane >> 2);
+      const int piece = (lane & 3) ^ (int)((row >> 2) & 3);
+      if (row > q_last_row) row = q_last_row;
+      q_row[d] = (int)row;
+      q_col[d] = (uint32_t)(piece * 16);
+    }
+    q_dst[d] = (uint32_t)(C::P_BYTES + n * 1024);
+  }
+  const bf16_t* p_base = a.P + i0;
+  const bf16_t* q_base = Q_STRIDED ? a.Q + j0 : a.Q + j0 * a.ldq;
+  const uint32_t ldp2 = (uint32_t)(a.ldp * 2), ldq2 = (uint32_t)(a.ldq * 2);
+
+  // the d-th load of the stage that starts at reduction index r into LDS buffer buf
+  auto issue_one = [&](auto d_tag, int64_t r, int buf) {
+    constexpr int d = decltype(d_tag)::value;
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
+    const int rows_left = (int)((a.R - r) < C::RS ? (a.R - r) : C::RS);  // >= 1
+    if constexpr (d < C::P_PW) {
+      const int row = p_row[d] < rows_left ? p_row[d] : rows_left - 1;
+      dma16(make_uniform(p_base + r * a.ldp), (uint32_t)row * ldp2 + p_col[d], lds + p_dst[d]);
+    } else if constexpr (Q_STRIDED) {
+      const int row = q_row[d - C::P_PW] < rows_left ? q_row[d - C::P_PW] : rows_left - 1;
+      dma16(make_uniform(q_base + r * a.ldq), (uint32_t)row * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+    } else {
+      dma16(make_uniform(q_base + r), (uint32_t)q_row[d - C::P_PW] * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+    }
+  };
+  auto issue_stage = [&](int64_t r, int buf) {
+    [&]<int... D>(std::integer_sequence<int, D...>) {
+      (issue_one(std::integral_constant<int, D>{}, r, buf), ...);
+    }(std::make_integer_sequence<int, C::LPW>{});
+  };
+
+  f32x4_t acc[IT][JT];
+#pragma unroll
+  for (int i = 0; i < IT; ++i)
+#pragma unroll
+    for (int j = 0; j < JT; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  u32x4_t pf[IT], qf[JT];
+  auto read_frags = [&](int buf) {
+    const unsigned char* base = smem + buf * C::STAGE;
+#pragma unroll
+    for (int i = 0; i < IT; ++i) pf[i] = read_transposed(base, wi * IT + i, c16, kb);
+#pragma unroll
+    for (int j = 0; j < JT; ++j) {
+      if (Q_STRIDED) {
+        qf[j] = read_transposed(base + C::P_BYTES, wj * JT + j, c16, kb);
+      } else {
+        const int row = (wj * JT + j) * 16 + c16;
+        qf[j] = *reinterpret_cast<const u32x4_t*>(base + C::P_BYTES + row * 64 + ((kb ^ ((c16 >> 2) & 3)) << 4));
+      }
+    }
+  };
+  // 16 matrix instructions; the wave's loads of a later stage are issued between them
+  auto multiply = [&](bool load, int64_t lr, int lbuf) {
+    [&]<int... Q>(std::integer_sequence<int, Q...>) {
+      ([&] {
+        constexpr int j = Q / IT, i = Q % IT;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pf[i]),
+                                                            __builtin_bit_cast(bf16x8_t, qf[j]), acc[i][j], 0, 0, 0);
+        if constexpr (Q % 4 == 3 && Q / 4 < C::LPW) {
+          if (load) issue_one(std::integral_constant<int, Q / 4>{}, lr, lbuf);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }(), ...);
+    }(std::make_integer_sequence<int, C::MMA>{});
+  };
+  auto wait_stage = [&](int younger) {
+    [&]<int... Y>(std::integer_sequence<int, Y...>) {
+      ((younger == Y ? wait_loads_outstanding<Y * C::LPW>() : void()), ...);
+    }(std::make_integer_sequence<int, STAGES - 1>{});
+  };
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nk) issue_stage(r_first + (int64_t)s * C::RS, s);
+
+  // One barrier per stage; the buffer multiplied in the previous step is refilled right after the barrier,
+  // STAGES - 1 stages ahead.
+  {
+    int buf = 0;
+    for (int64_t ks = 0; ks < nk; ++ks) {
+      const int64_t ahead = nk - 1 - ks;  // stages after this one; the loads of at most STAGES - 2 of them are out
+      wait_stage(ahead < STAGES - 2 ? (int)ahead : STAGES - 2);
+      const int64_t r = r_first + ks * C::RS;
+      if (a.R - r < C::RS) {
+        // ragged last stage of the reduction: this wave's own loads have landed; it clears the rows past R
+        // it fetched (reduction-major tiles only; the other form requires R % 32 == 0)
+        const int rows_left = (int)(a.R - r);
+        unsigned char* base = smem + buf * C::STAGE;
+#pragma unroll
+        for (int d = 0; d < C::P_PW; ++d)
+          if (p_row[d] >= rows_left) *reinterpret_cast<u32x4_t*>(base + p_dst[d] + lane * 16) = u32x4_t{0, 0, 0, 0};
+        if (Q_STRIDED) {
+#pragma unroll
+          for (int d = 0; d < C::Q_PW; ++d)
+            if (q_row[d] >= rows_left) *reinterpret_cast<u32x4_t*>(base + q_dst[d] + lane * 16) = u32x4_t{0, 0, 0, 0};
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      }
+      __builtin_amdgcn_s_barrier();
+      int nbuf = buf + STAGES - 1;
+      if (nbuf >= STAGES) nbuf -= STAGES;
+      read_frags(buf);
+      multiply(ks + STAGES - 1 < nk, r + (int64_t)(STAGES - 1) * C::RS, nbuf);
+      if (++buf == STAGES) buf = 0;
+    }
+  }
+
+  // ---- split reduction: the partial tile, 16 bytes per lane and accumulator, fully coalesced
+  if (a.splits > 1) {
+    f32x4_t* mine = reinterpret_cast<f32x4_t*>(a.partial) + ((size_t)split * n_tiles + tile) * (C::MMA * C::NT) + tid;
+#pragma unroll
+    for (int i = 0; i < IT; ++i)
+#pragma unroll
+      for (int j = 0; j < JT; ++j) mine[(i * JT + j) * C::NT] = acc[i][j];
+    return;
+  }
+
+  // ---- write-out.  A lane holds columns i .. i+3 (accumulator element e -> row 4 kb + e of the 16-row block)
+  // of output row j = c16, i.e. 8 or 16 contiguous bytes of an Out row.  For aligned outputs every wave
+  // transposes 16 output rows at a time through its own LDS slice, so that the global stores are 16 bytes
+  // per lane and whole row segments of the wave tile are written contiguously.
+  __builtin_amdgcn_s_barrier();  // every wave is done with the operand stages
+  if (a.vec_store) {
+    constexpr int IW = IT * 16;
+    auto transpose_store = [&](auto out_tag) {
+      using out_t = decltype(out_tag);
+      constexpr int ES = (int)sizeof(out_t);
+      constexpr int RSB = IW * ES + 16;  // padded LDS row
+      constexpr int CPR = IW * ES / 16;  // 16-byte pieces per row
+      constexpr int PASSES = 16 * CPR / 64;
+      static_assert(16 * CPR % 64 == 0 && C::NW * 16 * RSB <= C::LDS_BYTES, "write-out slice");
+      unsigned char* slice = smem + wave * (16 * RSB);
+#pragma unroll
+      for (int j = 0; j < JT; ++j) {
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+          const f32x4_t v = acc[i][j];
+          unsigned char* dst = slice + c16 * RSB + (i * 16 + kb * 4) * ES;
+          if constexpr (ES == 2) {
+            uint2 pk;
+            pk.x = pack_bf16x2(v[0], v[1]);
+            pk.y = pack_bf16x2(v[2], v[3]);
+            *reinterpret_cast<uint2*>(dst) = pk;
+          } else {
+            *reinterpret_cast<f32x4_t*>(dst) = v;
+          }
+        }
+#pragma unroll
+        for (int pss = 0; pss < PASSES; ++pss) {
+          const int q = pss * 64 + lane;
+          const int row = q / CPR, ch = q % CPR;
+          const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(slice + row * RSB + ch * 16);
+          const int64_t jj = j0 + (wj * JT + j) * 16 + row;
+          const int64_t ii = i0 + wi * IW + ch * (16 / ES);
+          if (jj < a.J && ii < a.I)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<out_t*>(a.out) + jj * a.ldo + ii) = piece;
+        }
+      }
+    };
+    if (a.out_bf16) transpose_store(bf16_t{});
+    else transpose_store(float{});
+  } else {
+#pragma unroll
+    for (int j = 0; j < JT; ++j) {
+      const int64_t jj = j0 + (wj * JT + j) * 16 + c16;
+      if (jj >= a.J) continue;
+#pragma unroll
+      for (int i = 0; i < IT; ++i) {
+        const int64_t ii = i0 + (wi * IT + i) * 16 + kb * 4;
+        const f32x4_t v = acc[i][j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (ii + e >= a.I) break;
+          if (a.out_bf16) reinterpret_cast<bf16_t*>(a.out)[jj * a.ldo + ii + e] = (bf16_t)f32_to_bf16_rne(v[e]);
+          else reinterpret_cast<float*>(a.out)[jj * a.ldo + ii + e] = v[e];
+        }
+      }
+    }
+  }
+}
+
+// Sum of the partial tiles in split order, the mask of the step (bit k % 32 of word k / 32 of row o; NULL =
+// every weight receives its gradient) and the rounding.  One lane per accumulator of the tile kernel.
+__global__ void __launch_bounds__(256)
+grad_reduce_kernel(const float* __restrict__ partial, int splits, int n_tiles, int n_i_tiles, int64_t I, int64_t J,
+                   const uint32_t* __restrict__ mask, void* __restrict__ out, int64_t ldo, int out_bf16) {
+  using C = TCfg;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= (int64_t)n_tiles * C::MMA * C::NT) return;
+  const int tid = (int)(id % C::NT);
+  const int q = (int)((id / C::NT) % C::MMA);
+  const int tile = (int)(id / (C::NT * C::MMA));
+  const f32x4_t* src = reinterpret_cast<const f32x4_t*>(partial) + id;
+  const size_t stride = (size_t)n_tiles * (C::MMA * C::NT);
+  f32x4_t sum = src[0];
+  for (int s = 1; s < splits; ++s) sum += src[(size_t)s * stride];
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = wave % C::WI, wj = wave / C::WI;
+  const int i = q / C::JT, j = q % C::JT;
+  const int64_t ii = (int64_t)(tile % n_i_tiles) * C::BI + (wi * C::IT + i) * 16 + (lane >> 4) * 4;
+  const int64_t jj = (int64_t)(tile / n_i_tiles) * C::BJ + (wj * C::JT + j) * 16 + (lane & 15);
+  if (jj >= J || ii >= I) return;
+  if (mask) {
+    const uint32_t w = mask[jj * ((I + 31) / 32) + (ii >> 5)] >> (ii & 31);  // I % 4 == 0: the four bits share a word
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (!((w >> e) & 1u)) sum[e] = 0.f;
+  }
+  if (out_bf16) {
+    bf16_t* dst = reinterpret_cast<bf16_t*>(out) + jj * ldo + ii;
+    if (ii + 3 < I && ((uintptr_t)dst & 7) == 0) {
+      *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3]));
+    } else {
+      for (int e = 0; e < 4 && ii + e < I; ++e) dst[e] = (bf16_t)f32_to_bf16_rne(sum[e]);
+    }
+  } else {
+    float* dst = reinterpret_cast<float*>(out) + jj * ldo + ii;
+    if (ii + 3 < I && ((uintptr_t)dst & 15) == 0) {
+      *reinterpret_cast<f32x4_t*>(dst) = sum;
+    } else {
+      for (int e = 0; e < 4 && ii + e < I; ++e) dst[e] = sum[e];
+    }
+  }
+}
+
+// Any shape and alignment: one lane per output, a plain loop over the reduction.
+__global__ void __launch_bounds__(256)
+backward_input_general_kernel(const bf16_t* __restrict__ Ws, int64_t O, int64_t K, int64_t ldw,
+                              const bf16_t* __restrict__ dY, int64_t T, int64_t ldy, void* __restrict__ dX, int64_t ldx,
+                              int out_bf16) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= T * K) return;
+  const int64_t t = id / K, k = id % K;
+  float acc = 0.f;
+  for (int64_t o = 0; o < O; ++o) acc = fmaf(bf16_to_f32(dY[t * ldy + o]), bf16_to_f32(Ws[o * ldw + k]), acc);
+  if (out_bf16) reinterpret_cast<bf16_t*>(dX)[t * ldx + k] = (bf16_t)f32_to_bf16_rne(acc);
+  else reinterpret_cast<float*>(dX)[t * ldx + k] = acc;
+}
+
+__global__ void __launch_bounds__(256)
+backward_weight_general_kernel(const bf16_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldy,
+                               const bf16_t* __restrict__ X, int64_t K, int64_t ldx, const uint32_t* __restrict__ mask,
+                               void* __restrict__ dW, int64_t lddw, int out_bf16) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * K) return;
+  const int64_t o = id / K, k = id % K;
+  float acc = 0.f;
+  if (!mask || ((mask[o * ((K + 31) / 32) + (k >> 5)] >> (k & 31)) & 1u))
+    for (int64_t t = 0; t < T; ++t) acc = fmaf(bf16_to_f32(dY[t * ldy + o]), bf16_to_f32(X[t * ldx + k]), acc);
+  if (out_bf16) reinterpret_cast<bf16_t*>(dW)[o * lddw + k] = (bf16_t)f32_to_bf16_rne(acc);
+  else reinterpret_cast<float*>(dW)[o * lddw + k] = acc;
+}
+
+inline bool aligned_to(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+template <bool Q_STRIDED>
+hipError_t launch_tgemm(TGemmArgs g, hipStream_t s) {
+  using C = TCfg;
+  auto kern = nm_tgemm_kernel<Q_STRIDED>;
+  static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t n_tiles = (int64_t)g.n_i_tiles * g.n_j_tiles;
+  const int64_t grid = g.splits > 1 ? n_tiles * g.splits : ((n_tiles + 7) / 8) * 8;
+  if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s, g);
+  return hipGetLastError();
+}
+
+// Splits of the token reduction of dW: a multiple of 8 (one XCD each), about two blocks per compute unit of a
+// 256-unit chip, at least four steps per split where the reduction is long enough.
+struct WeightGradPlan {
+  bool tiles;  // the matrix-core kernel takes this shape
+  int n_i_tiles, n_j_tiles, splits;
+};
+WeightGradPlan weight_grad_plan(int64_t O, int64_t K, int64_t T) {
+  WeightGradPlan p{false, 0, 0, 0};
+  if ((O % 8) || (K % 8) || O > (1 << 24) || K > (1 << 22) || T > (1ll << 31)) return p;
+  const int64_t ni = (K + TCfg::BI - 1) / TCfg::BI, nj = (O + TCfg::BJ - 1) / TCfg::BJ;
+  if (ni * nj > (1 << 20)) return p;
+  p.tiles = true;
+  p.n_i_tiles = (int)ni;
+  p.n_j_tiles = (int)nj;
+  const int64_t steps = (T + TCfg::RS - 1) / TCfg::RS;
+  int64_t want = (512 + ni * nj - 1) / (ni * nj);
+  want = ((want + 7) / 8) * 8;
+  int64_t most = (steps / 4 / 8) * 8;
+  if (most < 8) most = 8;
+  if (want > most) want = most;
+  if (want > 64) want = 64;
+  p.splits = (int)want;
+  return p;
+}
+
+}  // namespace
+
+hipError_t launch_backward_input(const bf16_t* Ws, int64_t O, int64_t K, int64_t ldw, const bf16_t* dY, int64_t T,
+                                 int64_t ldy, void* dX, int64_t ldx, int out_bf16, hipStream_t s) {
+  const bool tiles = (O % 32 == 0) && (K % 8 == 0) && (ldw % 8 == 0) && (ldy % 8 == 0) && aligned_to(Ws, 16) &&
+                     aligned_to(dY, 16) && K <= (1 << 24) && T <= (1ll << 31) && ldw <= (1 << 22) && ldy <= (1 << 22);
+  if (!tiles) {
+    if (T * K > 0x7FFFFFFFll * 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(backward_input_general_kernel, dim3((unsigned)((T * K + 255) / 256)), dim3(256), 0, s, Ws, O, K, ldw,
+                       dY, T, ldy, dX, ldx, out_bf16);
+    return hipGetLastError();
+  }
+  TGemmArgs g;
+  g.P = Ws; g.Q = dY; g.I = K; g.J = T; g.R = O; g.ldp = ldw; g.ldq = ldy;
+  g.out = dX; g.ldo = ldx; g.out_bf16 = out_bf16;
+  const int per_piece = out_bf16 ? 8 : 4;
+  g.vec_store = (ldx % per_piece == 0) && aligned_to(dX, 16);  // K % 8 == 0 holds here
+  g.n_i_tiles = (int)((K + TCfg::BI - 1) / TCfg::BI);
+  g.n_j_tiles = (int)((T + TCfg::BJ - 1) / TCfg::BJ);
+  g.splits = 1; g.partial = nullptr;
+  return launch_tgemm<false>(g, s);
+}
+
+size_t backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T) {
+  const WeightGradPlan p = weight_grad_plan(O, K, T);
+  if (!p.tiles) return 0;
+  return (size_t)p.splits * (size_t)p.n_i_tiles * (size_t)p.n_j_tiles * (size_t)(TCfg::BI * TCfg::BJ) * sizeof(float);
+}
+
+hipError_t launch_backward_weight(const bf16_t* dY, int64_t T, int64_t O, int64_t ldy, const bf16_t* X, int64_t K,
+                                  int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw, int out_bf16, void* workspace,
+                                  size_t workspace_bytes, hipStream_t s, bool* workspace_short) {
+  *workspace_short = false;
+  const WeightGradPlan p = weight_grad_plan(O, K, T);
+  const bool tiles = p.tiles && (ldy % 8 == 0) && (ldx % 8 == 0) && aligned_to(dY, 16) && aligned_to(X, 16) &&
+                     ldx <= (1 << 22) && ldy <= (1 << 22);
+  if (!tiles) {
+    if (O * K > 0x7FFFFFFFll * 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(backward_weight_general_kernel, dim3((unsigned)((O * K + 255) / 256)), dim3(256), 0, s, dY, T, O, ldy,
+                       X, K, ldx, mask, dW, lddw, out_bf16);
+    return hipGetLastError();
+  }
+  const size_t need = backward_weight_workspace_bytes(O, K, T);
+  if (workspace == nullptr || workspace_bytes < need || !aligned_to(workspace, 256)) {
+    *workspace_short = true;
+    return hipSuccess;
+  }
+  TGemmArgs g;
+  g.P = X; g.Q = dY; g.I = K; g.J = O; g.R = T; g.ldp = ldx; g.ldq = ldy;
+  g.out = nullptr; g.ldo = 0; g.out_bf16 = 0; g.vec_store = 0;
+  g.n_i_tiles = p.n_i_tiles; g.n_j_tiles = p.n_j_tiles;
+  g.splits = p.splits; g.partial = reinterpret_cast<float*>(workspace);
+  hipError_t e = launch_tgemm<true>(g, s);
+  if (e != hipSuccess) return e;
+  const int64_t n = (int64_t)p.n_i_tiles * p.n_j_tiles * TCfg::MMA * TCfg::NT;
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g.partial, p.splits,
+                     p.n_i_tiles * p.n_j_tiles, p.n_i_tiles, K, O, mask, dW, lddw, out_bf16);
+  return hipGetLastError();
+}
+
+}  // namespace nm

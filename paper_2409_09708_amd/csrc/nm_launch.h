@@ -75,4 +75,13 @@ bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* spar
 enum { SPMM_PREPARE = 1, SPMM_PRODUCT = 2 };
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases);
 
+// nm_grad.hip: training products of a layer.  Ws is the masked dense weight [O, K].
+hipError_t launch_backward_input(const bf16_t* Ws, int64_t O, int64_t K, int64_t ldw, const bf16_t* dY, int64_t T,
+                                 int64_t ldy, void* dX, int64_t ldx, int out_bf16, hipStream_t s);
+size_t backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T);
+// *workspace_short is set when the workspace is required but missing, misaligned or too small
+hipError_t launch_backward_weight(const bf16_t* dY, int64_t T, int64_t O, int64_t ldy, const bf16_t* X, int64_t K,
+                                  int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw, int out_bf16, void* workspace,
+                                  size_t workspace_bytes, hipStream_t s, bool* workspace_short);
+
 }  // namespace nm

@@ -19,6 +19,7 @@
 // Shapes the tiles cannot take (K % 64 != 0, unaligned pointers) run a plain gather kernel.
 #include "nm_device.h"
 #include "nm_launch.h"
+#include "nm_mma.h"
 
 #include <stdlib.h>
 
@@ -26,12 +27,6 @@
 #include <utility>
 
 namespace nm {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-typedef __attribute__((ext_vector_type(8))) uint32_t u32x8_t;
 
 // ---------------------------------------------------------------------------------------------
 // Pre-pass: re-code an N:M weight with N <= 2 as a 2:4 weight (values [O, K/2], one 32-bit
@@ -226,46 +221,6 @@ struct GemmCfg {
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
-// Asynchronous 16-byte (4-byte) per lane global -> LDS copy: lane i's piece lands at lds + 16*i (4*i).
-// `base` is wave-uniform (scalar registers), the lane adds an unsigned 32-bit byte offset; M0 carries
-// the LDS byte address and needs one wait state before the load that reads it.
-typedef uint64_t uniform_ptr_t;
-__device__ __forceinline__ uniform_ptr_t make_uniform(const void* p) {
-  const uint64_t v = (uint64_t)(uintptr_t)p;
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ void dma16(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(lane_byte_offset),
-               "s"(base)
-               : "memory", "m0");
-}
-__device__ __forceinline__ void dma4(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds), "v"(lane_byte_offset),
-               "s"(base)
-               : "memory", "m0");
-}
-// The same with the LDS address given as two uniform terms (stage buffer + place inside the stage).
-__device__ __forceinline__ void dma16_at(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds_stage,
-                                         uint32_t lds_offset) {
-  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(lds_stage), "s"(lds_offset),
-               "v"(lane_byte_offset), "s"(base)
-               : "memory", "m0", "scc");
-}
-__device__ __forceinline__ void dma4_at(uniform_ptr_t base, uint32_t lane_byte_offset, uint32_t lds_stage,
-                                        uint32_t lds_offset) {
-  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(lds_stage), "s"(lds_offset),
-               "v"(lane_byte_offset), "s"(base)
-               : "memory", "m0", "scc");
-}
-// Two floats to a pair of bfloat16 (round to nearest even) with the hardware conversion; lo in bits 0..15.
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  typedef float f32x2_t __attribute__((ext_vector_type(2)));
-  typedef __bf16 hwbf16x2_t __attribute__((ext_vector_type(2)));
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, hwbf16x2_t));
-}
-
 // Accumulator start value of the 16 x 16 block whose four out-features start at o: the bias (so
 // that no load sits between the stores of the epilogue), or zero.
 __device__ __forceinline__ f32x4_t bias_init(const float* bias, int64_t o, int64_t O, bool vec) {
@@ -283,11 +238,6 @@ __device__ __forceinline__ f32x4_t bias_init(const float* bias, int64_t o, int64
     }
   }
   return v;
-}
-
-template <int N>
-__device__ __forceinline__ void wait_loads_outstanding() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>

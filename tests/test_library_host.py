@@ -216,3 +216,46 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_PKG_DIR", str(tmp_path))
     with pytest.raises(RuntimeError, match="missing"):
         binding.load_library()
+
+
+def test_backward_argument_errors(lib):
+    def dx(**kw):
+        a = dict(Ws=FAKE, O=64, K=64, ldw=64, dY=FAKE, T=16, ldy=64, dX=FAKE, ldx=64, dt=0)
+        a.update(kw)
+        return lib.nm_linear_backward_input(a["Ws"], a["O"], a["K"], a["ldw"], a["dY"], a["T"], a["ldy"], a["dX"],
+                                            a["ldx"], a["dt"], None)
+
+    assert dx(Ws=None) == 1 and dx(dY=None) == 1 and dx(dX=None) == 1
+    assert dx(O=0) == 2 and dx(K=-1) == 2 and dx(T=0) == 2
+    assert dx(ldw=32) == 2 and dx(ldy=63) == 2 and dx(ldx=8) == 2
+    assert dx(dt=3) == 5
+    assert dx(Ws=FAKE + 1) == 4 and dx(dX=FAKE + 2) == 4 and dx(dX=FAKE + 2, dt=1) != 4
+
+    def dw(**kw):
+        a = dict(dY=FAKE, T=16, O=64, ldy=64, X=FAKE, K=64, ldx=64, mask=None, dW=FAKE, lddw=64, dt=0, ws=None, wsb=0)
+        a.update(kw)
+        return lib.nm_linear_backward_weight(a["dY"], a["T"], a["O"], a["ldy"], a["X"], a["K"], a["ldx"], a["mask"],
+                                             a["dW"], a["lddw"], a["dt"], a["ws"], a["wsb"], None)
+
+    assert dw(dY=None) == 1 and dw(X=None) == 1 and dw(dW=None) == 1
+    assert dw(T=0) == 2 and dw(O=0) == 2 and dw(K=0) == 2
+    assert dw(ldy=32) == 2 and dw(ldx=63) == 2 and dw(lddw=8) == 2
+    assert dw(dt=-1) == 5
+    assert dw(X=FAKE + 1) == 4 and dw(mask=FAKE + 2) == 4 and dw(dW=FAKE + 2) == 4
+    # the split reduction needs its scratch: missing, short and misaligned workspaces are refused before any launch
+    need = lib.nm_backward_weight_workspace_bytes(64, 64, 16)
+    assert need == 8 * 1 * 128 * 128 * 4  # one tile, the smallest number of ranges
+    assert dw() == 6 and dw(ws=FAKE, wsb=need - 1) == 6 and dw(ws=FAKE + 16, wsb=need) == 6
+
+
+def test_backward_weight_workspace_sizes(lib):
+    f = lib.nm_backward_weight_workspace_bytes
+    tile = 128 * 128 * 4
+    assert f(0, 64, 16) == 0 and f(64, 64, 0) == 0
+    assert f(30, 64, 100) == 0 and f(64, 52, 100) == 0  # the general kernel needs no scratch
+    # DeiT-B at batch 256 (T = 50432: 1576 steps of 32 tokens): 768 x 768 -> 36 tiles, 512 / 36 -> 16 ranges;
+    # 3072 x 768 -> 144 tiles, 8 ranges
+    assert f(768, 768, 50432) == 16 * 36 * tile
+    assert f(3072, 768, 50432) == 8 * 144 * tile and f(768, 3072, 50432) == 8 * 144 * tile
+    # short reductions keep the smallest number of ranges (one per XCD)
+    assert f(768, 768, 197) == 8 * 36 * tile
