@@ -18,7 +18,7 @@
 // One kernel serves both products:  C[i, j] = sum_r P[r, i] * Q(j, r), stored as Out[j, i]:
 //   dX: P = W (.) m [r = o, i = k], Q = dY as [j = t, r = o] (reduction contiguous), Out = dX [t, k]
 //   dW: P = X       [r = t, i = k], Q = dY as [r = t, j = o] (reduction = row),       Out = dW [o, k]
-// The token reduction of dW is long and its output small (a few dozen 128 x 128 tiles), so it is cut
+// The token reduction of dW is long and its output small (a few dozen 128 x 256 tiles), so it is cut
 // into `splits` ranges; every block leaves an fp32 partial tile and a second kernel adds the partial
 // tiles in split order (the result does not depend on scheduling), applies the mask and rounds.
 #include "nm_device.h"
@@ -39,42 +39,58 @@ struct TGemmArgs {
   const bf16_t* P;  // [R, I], ld ldp
   const bf16_t* Q;  // Q_STRIDED: [R, J], else [J, R]; ld ldq
   int64_t I, J, R, ldp, ldq;
-  void* out;        // splits == 1: Out[J, I], ld ldo
+  void* out;        // Out[J, I], ld ldo (when partial is NULL)
   int64_t ldo;
   int out_bf16;
   int vec_store;    // Out rows split into whole aligned 16-byte pieces
   int n_i_tiles, n_j_tiles;
-  int splits;       // > 1 (then a multiple of 8): partial tiles go to `partial`
-  float* partial;   // [split][tile][accumulator][thread], 16 bytes per thread
+  int splits;       // ranges the reduction is cut into (>= 1)
+  float* partial;   // not NULL: fp32 partial tiles [split][tile][accumulator][thread] (16 bytes per thread)
+                    // instead of Out
 };
 
 struct TCfg {
-  static constexpr int WI = 2, WJ = 2, IT = 4, JT = 4;
+  // 4 waves (2 x 2), each 64 (i) x 128 (j) outputs: a wave reads 12 fragments per 32 matrix instructions (the
+  // LDS read rate is what bounds these kernels; 64 x 64 per wave needs 8 per 16).  Two blocks share a compute
+  // unit (72 KiB of LDS each), so one block's barrier and write-out overlap the other's arithmetic.
+  static constexpr int WI = 2, WJ = 2, IT = 4, JT = 8;
   static constexpr int NW = WI * WJ, NT = NW * 64;
-  static constexpr int BI = WI * IT * 16, BJ = WJ * JT * 16;  // 128 x 128 outputs per block
+  static constexpr int BI = WI * IT * 16, BJ = WJ * JT * 16;  // 128 x 256 outputs per block
   static constexpr int RS = 32;                                // reduction indices per stage: one instruction deep
-  static constexpr int STAGES = 4;
+  static constexpr int STAGES = 3;
+  static constexpr int P_ROWB = BI * 2, Q_ROWB = BJ * 2;       // bytes of a row of a reduction-major tile
   static constexpr int P_BYTES = RS * BI * 2, Q_BYTES = RS * BJ * 2;
   static constexpr int STAGE = P_BYTES + Q_BYTES;
   static constexpr int LDS_BYTES = STAGES * STAGE;
   static constexpr int P_PW = P_BYTES / 1024 / NW, Q_PW = Q_BYTES / 1024 / NW;  // wave-wide loads per wave
   static constexpr int LPW = P_PW + Q_PW;
   static constexpr int MMA = IT * JT;
-  static_assert(BI == 128 && BJ == 128 && P_PW == 2 && Q_PW == 2, "tile layout");
+  static_assert(P_PW * NW * 1024 == P_BYTES && Q_PW * NW * 1024 == Q_BYTES && STAGES * LPW < 64, "load split");
+  static_assert(2 * LDS_BYTES <= 160 * 1024, "two blocks per compute unit");
 };
 
-// Transposing fragment read from a tile stored as [RS rows (reduction)][128 columns], 256 bytes per row, the
-// 16-byte pieces of row r at slot (piece ^ 2 (r & 3)): the 16 lanes of a group touch four rows, and the
-// swizzle puts their 32-byte runs on different banks.  Lane (c16 = lane % 16, kb = lane / 16) receives the
-// reduction indices 8 kb .. 8 kb + 7 of column 16 * block + c16.
+// Transposing fragment read from a tile stored as [RS rows (reduction)][ROWB / 2 columns], the 16-byte pieces
+// of row r at slot (piece ^ 2 (r & 3)): the 16 lanes of a group touch four rows, and the swizzle puts their
+// 32-byte runs on different banks.  Lane (c16 = lane % 16, kb = lane / 16) receives the reduction indices
+// 8 kb .. 8 kb + 7 of column 16 * block + c16.
+template <int ROWB>
 __device__ __forceinline__ u32x4_t read_transposed(const unsigned char* tile, int block, int c16, int kb) {
   const int sub = c16 >> 2;  // row inside the group of four; also (row & 3)
-  const int off = (8 * kb + sub) * 256 + ((2 * (block ^ sub) + ((c16 & 3) >> 1)) << 4) + (c16 & 1) * 8;
+  const int off = (8 * kb + sub) * ROWB + ((2 * (block ^ sub) + ((c16 & 3) >> 1)) << 4) + (c16 & 1) * 8;
   const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off));
-  const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off + 4 * 256));
+  const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off + 4 * ROWB));
   typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
   const u32x2_t l = __builtin_bit_cast(u32x2_t, lo), h = __builtin_bit_cast(u32x2_t, hi);
   return u32x4_t{l[0], l[1], h[0], h[1]};
+}
+
+// Where lane `lane` of the n-th wave-wide load (1 KiB of consecutive LDS) of a reduction-major tile reads:
+// row of the stage and 16-byte piece of that row (before the edge clamp).
+template <int ROWB>
+__device__ __forceinline__ void strided_load_place(int n, int lane, int* row, int* piece) {
+  constexpr int PER_ROW = ROWB / 16, ROWS = 1024 / ROWB;
+  *row = n * ROWS + lane / PER_ROW;
+  *piece = (lane % PER_ROW) ^ (2 * (*row & 3));
 }
 
 template <bool Q_STRIDED>
@@ -85,21 +101,17 @@ nm_tgemm_kernel(const TGemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-  // Block -> (tile, split).  Consecutive block ids land on different XCDs (8, each with its own L2).
-  // One range: every XCD takes a contiguous run of tiles, i fastest, so the blocks that share an L2 share
-  // Q rows.  Split reduction: split s lives on XCD s % 8 with all its tiles, so each range of rows of P and Q
-  // is fetched into one L2 only.
+  // Block -> (tile, split).  Consecutive block ids land on different XCDs (8, each with its own L2); every
+  // XCD takes a contiguous run of (split, tile) pairs, tiles fastest and i fastest among the tiles, so the
+  // blocks that share an L2 share rows of Q, and each range of rows of a split reduction is fetched into one
+  // L2 (two where a split straddles a boundary).
   const int n_tiles = a.n_i_tiles * a.n_j_tiles;
-  int tile, split = 0;
-  if (a.splits > 1) {
-    const int idx = (int)(blockIdx.x >> 3);
-    split = (int)(blockIdx.x & 7) + 8 * (idx / n_tiles);
-    tile = idx % n_tiles;
-  } else {
-    const int per_xcd = (n_tiles + 7) >> 3;
-    tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (tile >= n_tiles) return;
-  }
+  const int64_t n_blocks = (int64_t)n_tiles * a.splits;
+  const int64_t per_xcd = (n_blocks + 7) >> 3;
+  const int64_t virt = (int64_t)(blockIdx.x & 7) * per_xcd + (int64_t)(blockIdx.x >> 3);
+  if (virt >= n_blocks) return;
+  const int split = (int)(virt / n_tiles);
+  const int tile = (int)(virt % n_tiles);
   const int64_t i0 = (int64_t)(tile % a.n_i_tiles) * C::BI;
   const int64_t j0 = (int64_t)(tile / a.n_i_tiles) * C::BJ;
 
@@ -121,10 +133,9 @@ nm_tgemm_kernel(const TGemmArgs a) {
   const int c16 = lane & 15;
   const int kb = lane >> 4;
 
-  // ---- this wave's loads of a stage.  Reduction-major tiles: load n covers rows 4n .. 4n+3, lane -> (row
-  // 4n + lane / 16, slot lane % 16), the slot holds global piece slot ^ 2 (row & 3).  Columns past the edge
-  // re-read the last whole piece of the row (those outputs are never stored).  Rows past R are clamped to
-  // stay inside the operand and zeroed in LDS before use.
+  // ---- this wave's loads of a stage.  Columns of a reduction-major tile past the edge re-read the last whole
+  // piece of the row (those outputs are never stored).  Rows past R are clamped to stay inside the operand
+  // and zeroed in LDS before use.
   int p_row[C::P_PW], q_row[C::Q_PW];       // row inside the stage (reduction-major) or inside the tile
   uint32_t p_col[C::P_PW], q_col[C::Q_PW];  // byte offset inside the row
   uint32_t p_dst[C::P_PW], q_dst[C::Q_PW];
@@ -132,9 +143,9 @@ nm_tgemm_kernel(const TGemmArgs a) {
 #pragma unroll
   for (int d = 0; d < C::P_PW; ++d) {
     const int n = wave + d * C::NW;
-    int64_t piece = (lane & 15) ^ (2 * (lane >> 4));
-    if (piece > p_last_piece) piece = p_last_piece;
-    p_row[d] = 4 * n + (lane >> 4);
+    int piece;
+    strided_load_place<C::P_ROWB>(n, lane, &p_row[d], &piece);
+    if (piece > p_last_piece) piece = (int)p_last_piece;
     p_col[d] = (uint32_t)(piece * 16);
     p_dst[d] = (uint32_t)(n * 1024);
   }
@@ -143,12 +154,12 @@ nm_tgemm_kernel(const TGemmArgs a) {
   for (int d = 0; d < C::Q_PW; ++d) {
     const int n = wave + d * C::NW;
     if (Q_STRIDED) {
-      int64_t piece = (lane & 15) ^ (2 * (lane >> 4));
-      if (piece > q_last_piece) piece = q_last_piece;
-      q_row[d] = 4 * n + (lane >> 4);
+      int piece;
+      strided_load_place<C::Q_ROWB>(n, lane, &q_row[d], &piece);
+      if (piece > q_last_piece) piece = (int)q_last_piece;
       q_col[d] = (uint32_t)(piece * 16);
     } else {
-      // [128 rows j][32 reduction indices]: 64 bytes per row, load n covers rows 16n .. 16n+15, lane ->
+      // [BJ rows j][32 reduction indices]: 64 bytes per row, load n covers rows 16n .. 16n+15, lane ->
       // (row 16n + lane / 4, slot lane % 4), the slot holds piece slot ^ ((row >> 2) & 3)
       int64_t row = 16 * n + (lane >> 2);
       const int piece = (lane & 3) ^ (int)((row >> 2) & 3);
@@ -193,18 +204,18 @@ nm_tgemm_kernel(const TGemmArgs a) {
   auto read_frags = [&](int buf) {
     const unsigned char* base = smem + buf * C::STAGE;
 #pragma unroll
-    for (int i = 0; i < IT; ++i) pf[i] = read_transposed(base, wi * IT + i, c16, kb);
+    for (int i = 0; i < IT; ++i) pf[i] = read_transposed<C::P_ROWB>(base, wi * IT + i, c16, kb);
 #pragma unroll
     for (int j = 0; j < JT; ++j) {
       if (Q_STRIDED) {
-        qf[j] = read_transposed(base + C::P_BYTES, wj * JT + j, c16, kb);
+        qf[j] = read_transposed<C::Q_ROWB>(base + C::P_BYTES, wj * JT + j, c16, kb);
       } else {
         const int row = (wj * JT + j) * 16 + c16;
         qf[j] = *reinterpret_cast<const u32x4_t*>(base + C::P_BYTES + row * 64 + ((kb ^ ((c16 >> 2) & 3)) << 4));
       }
     }
   };
-  // 16 matrix instructions; the wave's loads of a later stage are issued between them
+  // 32 matrix instructions; the wave's loads of a later stage are issued between them
   auto multiply = [&](bool load, int64_t lr, int lbuf) {
     [&]<int... Q>(std::integer_sequence<int, Q...>) {
       ([&] {
@@ -261,7 +272,7 @@ nm_tgemm_kernel(const TGemmArgs a) {
   }
 
   // ---- split reduction: the partial tile, 16 bytes per lane and accumulator, fully coalesced
-  if (a.splits > 1) {
+  if (a.partial) {
     f32x4_t* mine = reinterpret_cast<f32x4_t*>(a.partial) + ((size_t)split * n_tiles + tile) * (C::MMA * C::NT) + tid;
 #pragma unroll
     for (int i = 0; i < IT; ++i)
@@ -420,14 +431,15 @@ hipError_t launch_tgemm(TGemmArgs g, hipStream_t s) {
     attr_done = true;
   }
   const int64_t n_tiles = (int64_t)g.n_i_tiles * g.n_j_tiles;
-  const int64_t grid = g.splits > 1 ? n_tiles * g.splits : ((n_tiles + 7) / 8) * 8;
+  const int64_t grid = ((n_tiles * g.splits + 7) / 8) * 8;
   if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s, g);
   return hipGetLastError();
 }
 
-// Splits of the token reduction of dW: a multiple of 8 (one XCD each), about two blocks per compute unit of a
-// 256-unit chip, at least four steps per split where the reduction is long enough.
+// Ranges of the token reduction of dW.  Two blocks fit a compute unit, 512 at once on a 256-unit chip; the
+// smallest count that fills at least 90 % of a whole number of such rounds is taken (else the fullest), with
+// at least four steps per range where the reduction is long enough.
 struct WeightGradPlan {
   bool tiles;  // the matrix-core kernel takes this shape
   int n_i_tiles, n_j_tiles, splits;
@@ -440,14 +452,17 @@ WeightGradPlan weight_grad_plan(int64_t O, int64_t K, int64_t T) {
   p.tiles = true;
   p.n_i_tiles = (int)ni;
   p.n_j_tiles = (int)nj;
-  const int64_t steps = (T + TCfg::RS - 1) / TCfg::RS;
-  int64_t want = (512 + ni * nj - 1) / (ni * nj);
-  want = ((want + 7) / 8) * 8;
-  int64_t most = (steps / 4 / 8) * 8;
-  if (most < 8) most = 8;
-  if (want > most) want = most;
-  if (want > 64) want = 64;
-  p.splits = (int)want;
+  const int64_t steps = (T + TCfg::RS - 1) / TCfg::RS, tiles = ni * nj;
+  int best = 1;
+  double best_fill = 0.0;
+  for (int s = 1; s <= 64; ++s) {
+    if (s > 1 && steps / s < 4) break;
+    const int64_t blocks = tiles * s, rounds = (blocks + 511) / 512;
+    const double fill = (double)blocks / (double)(rounds * 512);
+    if (fill > best_fill + 1e-9) { best = s; best_fill = fill; }
+    if (fill >= 0.9) break;
+  }
+  p.splits = best;
   return p;
 }
 

@@ -244,18 +244,19 @@ def test_backward_argument_errors(lib):
     assert dw(X=FAKE + 1) == 4 and dw(mask=FAKE + 2) == 4 and dw(dW=FAKE + 2) == 4
     # the split reduction needs its scratch: missing, short and misaligned workspaces are refused before any launch
     need = lib.nm_backward_weight_workspace_bytes(64, 64, 16)
-    assert need == 8 * 1 * 128 * 128 * 4  # one tile, the smallest number of ranges
+    assert need == 128 * 256 * 4  # one tile, one range
     assert dw() == 6 and dw(ws=FAKE, wsb=need - 1) == 6 and dw(ws=FAKE + 16, wsb=need) == 6
 
 
 def test_backward_weight_workspace_sizes(lib):
     f = lib.nm_backward_weight_workspace_bytes
-    tile = 128 * 128 * 4
+    tile = 128 * 256 * 4
     assert f(0, 64, 16) == 0 and f(64, 64, 0) == 0
     assert f(30, 64, 100) == 0 and f(64, 52, 100) == 0  # the general kernel needs no scratch
-    # DeiT-B at batch 256 (T = 50432: 1576 steps of 32 tokens): 768 x 768 -> 36 tiles, 512 / 36 -> 16 ranges;
-    # 3072 x 768 -> 144 tiles, 8 ranges
-    assert f(768, 768, 50432) == 16 * 36 * tile
-    assert f(3072, 768, 50432) == 8 * 144 * tile and f(768, 3072, 50432) == 8 * 144 * tile
-    # short reductions keep the smallest number of ranges (one per XCD)
-    assert f(768, 768, 197) == 8 * 36 * tile
+    # DeiT-B at batch 256 (T = 50432: 1576 steps of 32 tokens), 512 blocks at once: 768 x 768 -> 6 x 3 tiles,
+    # 26 ranges (468 blocks, 91 % of a round); 3072 x 768 -> 72 tiles, 7 ranges (504); 2304 x 768 -> 54 tiles, 9
+    assert f(768, 768, 50432) == 26 * 18 * tile
+    assert f(3072, 768, 50432) == 7 * 72 * tile and f(768, 3072, 50432) == 7 * 72 * tile
+    assert f(2304, 768, 50432) == 9 * 54 * tile
+    # a reduction too short for four steps per range is not cut
+    assert f(768, 768, 197) == 18 * tile
