@@ -243,7 +243,45 @@ def main():
                                            "peak": 8000.0, "unit": "GB/s",
                                            "frac": (2.5 * n_weights + packed_bytes) / pr_ms / 1e6 / 8000.0}}}
 
+    # ---- training products of one transformer block (its four layers at their levels): dX = dY (W.m) and
+    # dW = (dY^T X).m, dense matrix-core products of 2*T*O*K FLOPs each; the forward outputs stand in for dY
+    train_layers = list(range(4))
+    masked, words, dXs, dWs, gws = [], [], [], [], []
+    for j in train_layers:
+        L = layers[j]
+        wm = torch.empty_like(Ws[j])
+        words.append(nm.nm_prune(Ws[j], L.N, L.M, W_masked=wm))
+        masked.append(wm)
+        dXs.append(torch.empty((L.T, L.K), dtype=torch.bfloat16, device=dev))
+        dWs.append(torch.empty((L.O, L.K), dtype=torch.float32, device=dev))
+        gws.append(torch.empty((max(nm.nm_backward_weight_workspace_bytes(L.O, L.K, L.T), 256),), dtype=torch.uint8,
+                               device=dev))
+
+    def grad_inputs():
+        for n, j in enumerate(train_layers):
+            nm.nm_linear_backward_input(masked[n], Ys[j], out=dXs[n], stream=stream)
+
+    def grad_weights():
+        for n, j in enumerate(train_layers):
+            nm.nm_linear_backward_weight(Ys[j], Xs[j], mask=words[n], out=dWs[n], workspace=gws[n], stream=stream)
+
+    dx_ms, dw_ms = timed(grad_inputs), timed(grad_weights)
+    block_flops = sum(layers[j].dense_flops for j in train_layers)
+
+    def mfma_roofline(ms):
+        tf = block_flops / ms / 1e9
+        return {"bound": "mfma", "achieved": tf, "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / PEAK_BF16_DENSE_TFLOPS}
+
+    training = {"workload": "one DeiT-B block at batch 256 (qkv, proj, fc1, fc2; T=50432): input gradients in bf16, "
+                            "masked weight gradients in fp32; 2*T*O*K FLOPs per product",
+                "input_gradient": {"ms": dx_ms, "roofline": mfma_roofline(dx_ms)},
+                "weight_gradient": {"ms": dw_ms, "roofline": mfma_roofline(dw_ms)}}
+    del masked, words, dXs, dWs, gws
+
     if args.report:
+        log(f"training products of one block: dX {dx_ms:.3f} ms ({training['input_gradient']['roofline']['achieved']:.0f} "
+            f"TFLOP/s), dW {dw_ms:.3f} ms ({training['weight_gradient']['roofline']['achieved']:.0f} TFLOP/s)")
         log(f"nested levels: rank 48 matrices {rank_ms:.3f} ms ({nested['rank']['roofline']['achieved']:.0f} GB/s), "
             f"pack from ranks {pr_ms:.3f} ms ({nested['pack_ranked']['roofline']['achieved']:.0f} GB/s)")
         log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}")
@@ -278,6 +316,7 @@ def main():
         "pack_ms": pack_ms,
         "roofline": roofline,
         "nested_levels": nested,
+        "training_products": training,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
