@@ -132,6 +132,12 @@ def draw_weights(rng: np.random.Generator, O: int, K: int) -> np.ndarray:
     return f32_to_bf16_bits(w)
 
 
+def draw_int8(rng: np.random.Generator, rows: int, cols: int, spread: float = 40.0) -> np.ndarray:
+    """Quantised operand: round(N(0, spread)) clipped to [-127, 127], int8 [rows, cols]."""
+    v = np.rint(rng.standard_normal((rows, cols), dtype=np.float32) * np.float32(spread))
+    return np.clip(v, -127, 127).astype(np.int8)
+
+
 def draw_layers(layers: Sequence[Layer], seed: int = 0) -> Iterator[Tuple[Layer, np.ndarray, np.ndarray]]:
     """Yield (layer, X bits, W bits) in layer order from one generator: X then W per layer."""
     rng = np.random.default_rng(seed)
