@@ -66,13 +66,13 @@ enum {
   NM_ERR_SHAPE = 2,     /* O, K or T <= 0; K % M != 0; a leading dimension smaller than the row; count <= 0 */
   NM_ERR_LEVEL = 3,     /* M not in {4, 8, 16} or N outside [1, M] */
   NM_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
-  NM_ERR_DTYPE = 5,     /* out_dtype is neither NM_OUT_F32 nor NM_OUT_BF16 */
+  NM_ERR_DTYPE = 5,     /* out_dtype is not one the call offers */
   NM_ERR_WORKSPACE = 6, /* workspace is NULL or smaller than nm_spmm_workspace_bytes() */
   NM_ERR_DEVICE = 7,    /* a HIP call failed; see nm_last_hip_error() */
   NM_ERR_EXHAUSTED = 8  /* nm_sample_config ran out of random numbers before a configuration fell into the interval */
 };
 
-enum { NM_OUT_F32 = 0, NM_OUT_BF16 = 1 };
+enum { NM_OUT_F32 = 0, NM_OUT_BF16 = 1, NM_OUT_I32 = 2 /* int8 calls only: the raw integer sums */ };
 
 /* Text for a status code (static storage, never NULL). */
 const char* nm_status_string(int32_t status);
@@ -260,6 +260,42 @@ int32_t nm_linear_backward_input(const nm_bf16* Ws, int64_t O, int64_t K, int64_
 int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64_t ldy, const nm_bf16* X,
                                   int64_t K, int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw,
                                   int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * int8 form of the layer (Section 4, the post-training-quantisation experiment of Table 6: 8-bit quantisation on
+ * top of the sparse networks; Section 3.1: any saliency may produce the mask):
+ *
+ *   acc[t, o] = sum_k m[o, k] * Wq[o, k] * Xq[t, k]                 exact int32 sum
+ *   Y[t, o]   = fma(float(acc[t, o]), x_scale * w_scale[o], bias[o])   (fp32; or acc itself for NM_OUT_I32)
+ *
+ *   Wq       in   dense int8 weight [O, K], ld ldw.  Only positions whose mask bit is set are used; what the
+ *                 others hold is ignored (a symmetric quantiser leaves pruned weights at 0 anyway).
+ *   mask     in   mask words [O, ceil(K/32)] of level N:M as nm_prune writes them for the float weight, or from
+ *                 any other saliency; it must be legal for the level (nm_mask_check == 0), otherwise kept
+ *                 weights beyond two per run of four may be dropped at levels with N <= 2.
+ *   Xq       in   int8 [T, K], ld ldx
+ *   x_scale, w_scale ([O], NULL = 1), bias ([O], NULL = 0)  fp32 rescaling, not used for NM_OUT_I32
+ *   Y        out  [T, O], ld ldy: float, bfloat16 (round to nearest even) or int32
+ *   workspace scratch of nm_i8_workspace_bytes(O, K, N, M) bytes, 256-byte aligned (NULL allowed when 0): the
+ *             weight compressed to matrix-core operand order (values + 2-bit selectors at N <= 2, masked dense
+ *             otherwise).
+ * nm_linear_forward_i8 = nm_i8_prepare (weight only, once per weight) + nm_linear_forward_i8_prepared (the
+ * product; the workspace is only read).  The matrix-core kernels need K % 128 == 0, 16-byte aligned Wq and Xq
+ * and ldw, ldx multiples of 16; other shapes run a general kernel on Wq and mask with the same results.
+ * K * 127 * 128 must stay below 2^31 (K <= 132096) for the integer sum not to wrap.
+ * Errors as for nm_linear_forward.
+ */
+size_t nm_i8_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M);
+int32_t nm_linear_forward_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N,
+                             int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
+                             const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                             void* workspace, size_t workspace_bytes, void* stream);
+int32_t nm_i8_prepare(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N,
+                      int32_t M, void* workspace, size_t workspace_bytes, void* stream);
+int32_t nm_linear_forward_i8_prepared(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask,
+                                      int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
+                                      const float* w_scale, const float* bias, void* Y, int64_t ldy,
+                                      int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * nm_pack_prepare_batched -- for every descriptor nm_pack(mask = NULL) followed by nm_spmm_prepare, in as few

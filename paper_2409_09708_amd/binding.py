@@ -15,7 +15,7 @@ _LIB = None
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 
 NM_OK = 0
-NM_OUT_F32, NM_OUT_BF16 = 0, 1
+NM_OUT_F32, NM_OUT_BF16, NM_OUT_I32 = 0, 1, 2
 
 EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
@@ -24,6 +24,7 @@ EXPORTS = (
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
     "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
+    "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
 )
 
 
@@ -123,6 +124,17 @@ def load_library() -> ctypes.CDLL:
     lib.nm_linear_backward_weight.restype = c_int32
     lib.nm_linear_backward_weight.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
                                               c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_i8_workspace_bytes.restype = c_size_t
+    lib.nm_i8_workspace_bytes.argtypes = [c_int64, c_int64, c_int32, c_int32]
+    i8_args = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_void_p, c_int64, c_int64,
+               ctypes.c_float, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_linear_forward_i8.restype = c_int32
+    lib.nm_linear_forward_i8.argtypes = i8_args
+    lib.nm_linear_forward_i8_prepared.restype = c_int32
+    lib.nm_linear_forward_i8_prepared.argtypes = i8_args
+    lib.nm_i8_prepare.restype = c_int32
+    lib.nm_i8_prepare.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_void_p, c_size_t,
+                                  c_void_p]
     _LIB = lib
     return lib
 
@@ -537,6 +549,85 @@ def nm_linear_backward_weight(dY, X, mask=None, out_dtype=None, out=None, worksp
     _check(load_library().nm_linear_backward_weight(dY.data_ptr(), T, O, ldy, X.data_ptr(), K, ldx, mask_ptr,
                                                     out.data_ptr(), lddw, code, ws_ptr, ws_bytes, _stream_handle(stream)))
     return out
+
+
+def nm_i8_workspace_bytes(O: int, K: int, N: int, M: int) -> int:
+    return int(load_library().nm_i8_workspace_bytes(O, K, N, M))
+
+
+def _i8_weight(Wq, mask):
+    torch = _torch()
+    _need(Wq, torch.int8, "Wq")
+    _need(mask, torch.int32, "mask")
+    O, K, ldw = _rows(Wq, "Wq")
+    if tuple(mask.shape) != (O, (K + 31) // 32) or not mask.is_contiguous():
+        raise ValueError("mask must be contiguous [O, ceil(K/32)] words")
+    return O, K, ldw
+
+
+def nm_i8_prepare(Wq, mask, N: int, M: int, workspace=None, stream=None):
+    """Compress the int8 weight into matrix-core operand order; returns the workspace (None if none is needed)."""
+    torch = _torch()
+    O, K, ldw = _i8_weight(Wq, mask)
+    need = nm_i8_workspace_bytes(O, K, N, M)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=Wq.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().nm_i8_prepare(Wq.data_ptr(), O, K, ldw, mask.data_ptr(), N, M, ws_ptr, ws_bytes,
+                                        _stream_handle(stream)))
+    return workspace
+
+
+def nm_linear_forward_i8(Wq, mask, N: int, M: int, Xq, x_scale: float = 1.0, w_scale=None, bias=None, out_dtype=None,
+                         out=None, workspace=None, stream=None, _prepared=False):
+    """Y = x_scale * w_scale[o] * (Xq . (Wq (.) m)^T) + bias from int8 operands: float32 (default), bfloat16, or
+    the exact int32 sums (out dtype int32)."""
+    torch = _torch()
+    O, K, ldw = _i8_weight(Wq, mask)
+    _need(Xq, torch.int8, "Xq")
+    T, KX, ldx = _rows(Xq, "Xq")
+    if KX != K:
+        raise ValueError("Xq must be [T, K]")
+    if out is not None:
+        out_dtype = out.dtype
+    out_dtype = out_dtype or torch.float32
+    codes = {torch.float32: NM_OUT_F32, torch.bfloat16: NM_OUT_BF16, torch.int32: NM_OUT_I32}
+    if out_dtype not in codes:
+        raise ValueError("out dtype must be float32, bfloat16 or int32")
+    if out is None:
+        out = torch.empty((T, O), dtype=out_dtype, device=Xq.device)
+    TY, OY, ldy = _rows(out, "out")
+    if (TY, OY) != (T, O):
+        raise ValueError("out must be [T, O]")
+    ptrs = []
+    for t, name in ((w_scale, "w_scale"), (bias, "bias")):
+        if t is None:
+            ptrs.append(None)
+            continue
+        _need(t, torch.float32, name)
+        if t.numel() != O or not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous [O]")
+        ptrs.append(t.data_ptr())
+    need = nm_i8_workspace_bytes(O, K, N, M)
+    if workspace is None and need:
+        if _prepared:
+            raise ValueError("a prepared call needs the workspace nm_i8_prepare filled")
+        workspace = _workspace(need, Xq.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    lib = load_library()
+    fn = lib.nm_linear_forward_i8_prepared if _prepared else lib.nm_linear_forward_i8
+    _check(fn(Wq.data_ptr(), O, K, ldw, mask.data_ptr(), N, M, Xq.data_ptr(), T, ldx, float(x_scale), ptrs[0], ptrs[1],
+              out.data_ptr(), ldy, codes[out_dtype], ws_ptr, ws_bytes, _stream_handle(stream)))
+    return out
+
+
+def nm_linear_forward_i8_prepared(Wq, mask, N: int, M: int, Xq, workspace, x_scale: float = 1.0, w_scale=None, bias=None,
+                                  out_dtype=None, out=None, stream=None):
+    """The product alone, from a workspace filled by nm_i8_prepare."""
+    return nm_linear_forward_i8(Wq, mask, N, M, Xq, x_scale, w_scale, bias, out_dtype, out, workspace, stream,
+                                _prepared=True)
 
 
 def nm_spmm(values, indices, K: int, N: int, M: int, X, out_dtype=None, out=None, workspace=None, stream=None):

@@ -203,6 +203,28 @@ int32_t spmm_entry(const nm_bf16* values, const uint32_t* indices, int64_t O, in
   return device_status(e);
 }
 
+int32_t i8_entry(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N, int32_t M,
+                 const int8_t* Xq, int64_t T, int64_t ldx, float x_scale, const float* w_scale, const float* bias, void* Y,
+                 int64_t ldy, int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream, int phases) {
+  const bool product = phases & nm::SPMM_PRODUCT;
+  if (!Wq || !mask || (product && (!Xq || !Y))) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (T <= 0 || T > (int64_t)1 << 31 || ldw < K) return NM_ERR_SHAPE;
+  if (product && (ldx < K || ldy < O)) return NM_ERR_SHAPE;
+  if (out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16 && out_dtype != NM_OUT_I32) return NM_ERR_DTYPE;
+  if (!aligned(mask, 4) || !aligned(w_scale, 4) || !aligned(bias, 4) || !aligned(Y, out_dtype == NM_OUT_BF16 ? 2 : 4))
+    return NM_ERR_ALIGN;
+  nm::I8LinearArgs a;
+  a.Wq = Wq; a.ldw = ldw; a.mask = mask; a.O = O; a.K = K; a.N = N; a.M = M;
+  a.X = Xq; a.T = T; a.ldx = ldx; a.x_scale = x_scale; a.w_scale = w_scale; a.bias = bias;
+  a.Y = Y; a.ldy = ldy; a.out_kind = out_dtype;
+  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  bool workspace_short = false;
+  hipError_t e = nm::launch_linear_i8(a, (hipStream_t)stream, &workspace_short, phases);
+  if (workspace_short) return NM_ERR_WORKSPACE;
+  return device_status(e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -267,6 +289,33 @@ int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64
                                             workspace_bytes, (hipStream_t)stream, &workspace_short);
   if (workspace_short) return NM_ERR_WORKSPACE;
   return device_status(e);
+}
+
+size_t nm_i8_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M) {
+  if (check_weight(O, K, N, M) != NM_OK) return 0;
+  return nm::i8_workspace_bytes(O, K, N, M);
+}
+
+int32_t nm_linear_forward_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N,
+                             int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale, const float* w_scale,
+                             const float* bias, void* Y, int64_t ldy, int32_t out_dtype, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  return i8_entry(Wq, O, K, ldw, mask, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype, workspace,
+                  workspace_bytes, stream, nm::SPMM_PREPARE | nm::SPMM_PRODUCT);
+}
+
+int32_t nm_i8_prepare(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N, int32_t M,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  return i8_entry(Wq, O, K, ldw, mask, N, M, nullptr, 1, K, 1.f, nullptr, nullptr, nullptr, O, NM_OUT_F32, workspace,
+                  workspace_bytes, stream, nm::SPMM_PREPARE);
+}
+
+int32_t nm_linear_forward_i8_prepared(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask,
+                                      int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
+                                      const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  return i8_entry(Wq, O, K, ldw, mask, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype, workspace,
+                  workspace_bytes, stream, nm::SPMM_PRODUCT);
 }
 
 }  // extern "C"

@@ -84,4 +84,25 @@ hipError_t launch_backward_weight(const bf16_t* dY, int64_t T, int64_t O, int64_
                                   int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw, int out_bf16, void* workspace,
                                   size_t workspace_bytes, hipStream_t s, bool* workspace_short);
 
+// nm_int8.hip: the int8 layer.  Phases as for launch_spmm.
+struct I8LinearArgs {
+  const int8_t* Wq;      // dense int8 weight [O, K], ld ldw
+  int64_t ldw;
+  const uint32_t* mask;  // mask words [O, ceil(K/32)]
+  int64_t O, K;
+  int N, M;
+  const int8_t* X;
+  int64_t T, ldx;
+  float x_scale;
+  const float* w_scale;  // nullable
+  const float* bias;     // nullable
+  void* Y;
+  int64_t ldy;
+  int out_kind;          // 0 float, 1 bfloat16, 2 int32 accumulators
+  void* workspace;
+  size_t workspace_bytes;
+};
+size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M);
+hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspace_short, int phases);
+
 }  // namespace nm

@@ -1,0 +1,168 @@
+"""GPU parity of the int8 layer (Section 4, Table 6: 8-bit quantisation on top of the sparse networks): the
+integer sums from the HIP library must equal the CPU checker's bit for bit; the rescaled outputs within the
+rounding of one fp32 multiply-add (and of the bfloat16 store)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_09708_amd as nm
+from oracle import nm_int8_oracle as q
+from oracle import nm_oracle as orc
+from paper_2409_09708_amd import workloads as wl
+from gpu_util import dev_bf16, dev_words, host_output
+
+pytestmark = pytest.mark.gpu
+
+LEVELS = [(1, 4), (2, 4), (3, 4), (1, 8), (2, 8), (4, 8), (8, 8), (1, 16), (2, 16), (4, 16)]
+
+
+def random_mask(rng, O, K, N, M):
+    keys = rng.random((O, K // M, M))
+    order = np.argsort(keys, axis=2)
+    m = np.zeros((O, K // M, M), dtype=bool)
+    np.put_along_axis(m, order[:, :, :N], True, axis=2)
+    return m.reshape(O, K)
+
+
+def magnitude_mask(wq, N, M):
+    """Mask of the float weight the integers stand for (integers up to 127 are exact in bfloat16)."""
+    return orc.nm_mask(wl.f32_to_bf16_bits(wq.astype(np.float32)), N, M)
+
+
+def dev_i8(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_scaled(Y, Yref, acc, scale_row, bias, bf16_out, what):
+    # fp32: one product x_scale * w_scale, one conversion of the integer and one fused multiply-add
+    mag = np.abs(acc) * np.abs(scale_row)[None, :] + (0 if bias is None else np.abs(bias)[None, :])
+    tol = mag * (2.0 ** -22 + (2.0 ** -8 if bf16_out else 0.0)) + 1e-30
+    err = np.abs(Y - Yref)
+    assert np.all(err <= tol), (what, float((err / tol).max()))
+
+
+@pytest.mark.parametrize("N,M", LEVELS)
+@pytest.mark.parametrize("mask_kind", ["magnitude", "random"])
+def test_integer_sums_bit_exact_tiled(N, M, mask_kind):
+    # several tiles with ragged edges: T = 591, O = 328, K = 384 (three K steps)
+    rng = np.random.default_rng(7000 + N * 17 + M)
+    T, K, O = 591, 384, 328
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = magnitude_mask(wq, N, M) if mask_kind == "magnitude" else random_mask(rng, O, K, N, M)
+    ref = q.nm_accumulate_i8(xq, wq, mask)
+    words = dev_words(orc.mask_to_words(mask))
+    acc = nm.nm_linear_forward_i8(dev_i8(wq), words, N, M, dev_i8(xq), out_dtype=torch.int32)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref)
+
+
+def test_mask_from_the_float_weights_pruning_call():
+    # the quantisation flow: prune the float weight on the device, quantise (here: the integers themselves),
+    # multiply with the mask words nm_prune wrote
+    rng = np.random.default_rng(7100)
+    T, K, O, N, M = 200, 256, 136, 2, 8
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    wf = dev_bf16(wl.f32_to_bf16_bits(wq.astype(np.float32)))
+    words = nm.nm_prune(wf, N, M)
+    acc = nm.nm_linear_forward_i8(dev_i8(wq), words, N, M, dev_i8(xq), out_dtype=torch.int32)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), q.nm_accumulate_i8(xq, wq, magnitude_mask(wq, N, M)))
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 8), (4, 8)])
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_rescaled_outputs(N, M, out_dtype):
+    rng = np.random.default_rng(7200 + N + M)
+    T, K, O = 300, 256, 200
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = magnitude_mask(wq, N, M)
+    x_scale = 0.0173
+    w_scale = (0.001 + 0.002 * rng.random(O)).astype(np.float32)
+    bias = rng.standard_normal(O).astype(np.float32)
+    acc = q.nm_accumulate_i8(xq, wq, mask)
+    x_scale32 = float(np.float32(x_scale))
+    Yref = q.nm_linear_i8(xq, wq, mask, x_scale32, w_scale, bias)
+    words = dev_words(orc.mask_to_words(mask))
+    Y = nm.nm_linear_forward_i8(dev_i8(wq), words, N, M, dev_i8(xq), x_scale=x_scale, w_scale=torch.from_numpy(w_scale).cuda(),
+                                bias=torch.from_numpy(bias).cuda(), out_dtype=out_dtype)
+    check_scaled(host_output(Y), Yref, acc, x_scale32 * w_scale.astype(np.float64), bias, out_dtype == torch.bfloat16,
+                 (N, M))
+    # no scales, no bias: the integers as floats
+    Y1 = nm.nm_linear_forward_i8(dev_i8(wq), words, N, M, dev_i8(xq), out_dtype=torch.float32)
+    assert np.array_equal(Y1.cpu().numpy().astype(np.float64), acc.astype(np.float32).astype(np.float64))
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 16), (4, 8)])
+def test_large_tile_path_and_prepared_calls(N, M):
+    # at least 256 tiles of 128 x 128 with ragged edges; a prepared workspace serves repeated products unchanged
+    rng = np.random.default_rng(7300 + N + M)
+    T, K, O = 16 * 128 + 37, 256, 16 * 128 + 36
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = random_mask(rng, O, K, N, M)
+    words = dev_words(orc.mask_to_words(mask))
+    Wd, Xd = dev_i8(wq), dev_i8(xq)
+    whole = nm.nm_linear_forward_i8(Wd, words, N, M, Xd, out_dtype=torch.int32)
+    assert np.array_equal(whole.cpu().numpy().astype(np.int64), q.nm_accumulate_i8(xq, wq, mask))
+    ws = nm.nm_i8_prepare(Wd, words, N, M)
+    assert ws.numel() == nm.nm_i8_workspace_bytes(O, K, N, M)
+    snapshot = ws.clone()
+    for _ in range(2):
+        assert torch.equal(nm.nm_linear_forward_i8_prepared(Wd, words, N, M, Xd, ws, out_dtype=torch.int32), whole)
+    assert torch.equal(ws, snapshot)
+
+
+def test_pruned_positions_are_ignored_whatever_they_hold():
+    rng = np.random.default_rng(7400)
+    T, K, O = 70, 128, 72
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    for (N, M) in [(1, 4), (4, 8)]:
+        mask = random_mask(rng, O, K, N, M)
+        dirty = wq.copy()
+        dirty[~mask] = -128
+        words = dev_words(orc.mask_to_words(mask))
+        a = nm.nm_linear_forward_i8(dev_i8(wq), words, N, M, dev_i8(xq), out_dtype=torch.int32)
+        b = nm.nm_linear_forward_i8(dev_i8(dirty), words, N, M, dev_i8(xq), out_dtype=torch.int32)
+        assert torch.equal(a, b)
+        assert np.array_equal(a.cpu().numpy().astype(np.int64), q.nm_accumulate_i8(xq, wq, mask))
+
+
+def test_extreme_values_and_edges():
+    # -128 everywhere over K = 1024 kept weights: 2^24 per output, far beyond int16; one token; one row
+    K = 1024
+    xq = np.full((1, K), -128, dtype=np.int8)
+    wq = np.full((1, K), -128, dtype=np.int8)
+    mask = np.ones((1, K), dtype=bool)
+    acc = nm.nm_linear_forward_i8(dev_i8(wq), dev_words(orc.mask_to_words(mask)), 4, 4, dev_i8(xq), out_dtype=torch.int32)
+    assert int(acc[0, 0]) == 128 * 128 * K
+
+
+def test_general_shapes_and_views():
+    # K not a multiple of 128, operands as views of wider buffers, an output view without 16-byte rows
+    rng = np.random.default_rng(7500)
+    for (T, K, O, N, M, pad) in [(33, 48, 20, 1, 8, 0), (65, 128, 40, 2, 4, 3), (65, 256, 40, 2, 4, 16), (9, 16, 3, 4, 16, 0)]:
+        xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+        mask = random_mask(rng, O, K, N, M)
+        ref = q.nm_accumulate_i8(xq, wq, mask)
+        Wbig = torch.zeros((O, K + 16), dtype=torch.int8, device="cuda")
+        Wbig[:, :K] = dev_i8(wq)
+        Xbig = torch.zeros((T, K + 32), dtype=torch.int8, device="cuda")
+        Xbig[:, :K] = dev_i8(xq)
+        out = torch.full((T, O + 2 * pad + 1), 7, dtype=torch.int32, device="cuda")
+        view = out[:, pad:pad + O]
+        nm.nm_linear_forward_i8(Wbig[:, :K], dev_words(orc.mask_to_words(mask)), N, M, Xbig[:, :K], out=view)
+        assert np.array_equal(view.cpu().numpy().astype(np.int64), ref), (T, K, O, N, M, pad)
+        assert torch.all(out[:, :pad] == 7) and torch.all(out[:, pad + O:] == 7)
+
+
+def test_deit_b_fc1_at_batch256_sampled():
+    # T = 50432, 768 -> 3072 at 2:4 and 4:8 in the configuration the benchmark times (bfloat16 output is checked
+    # through the exact integers of sampled token rows)
+    T, K, O = 256 * 197, 768, 3072
+    rng = np.random.default_rng(7600)
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    Xd, Wd = dev_i8(xq), dev_i8(wq)
+    rows = np.unique(np.concatenate([np.arange(16), np.arange(T - 16, T), rng.integers(16, T - 16, size=32)]))
+    for (N, M) in [(2, 4), (4, 8)]:
+        mask = magnitude_mask(wq, N, M)
+        words = dev_words(orc.mask_to_words(mask))
+        acc = nm.nm_linear_forward_i8(Wd, words, N, M, Xd, out_dtype=torch.int32)
+        got = acc[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.int64)
+        assert np.array_equal(got, q.nm_accumulate_i8(xq[rows], wq, mask)), (N, M)

@@ -260,3 +260,30 @@ def test_backward_weight_workspace_sizes(lib):
     assert f(2304, 768, 50432) == 9 * 54 * tile
     # a reduction too short for four steps per range is not cut
     assert f(768, 768, 197) == 18 * tile
+
+
+def test_int8_argument_errors_and_sizes(lib):
+    f = lib.nm_i8_workspace_bytes
+    assert f(768, 768, 2, 4) == 768 * 768 // 2 + 768 * 768 // 8   # values + 2-bit selectors
+    assert f(768, 768, 1, 16) == 768 * 768 // 2 + 768 * 768 // 8  # every level with N <= 2 takes the 2:4 form
+    assert f(768, 768, 4, 8) == 768 * 768 and f(768, 768, 8, 8) == 768 * 768  # masked dense copy
+    assert f(64, 48, 1, 8) == 0                                   # general kernel
+    assert f(64, 64, 3, 2) == 0 and f(0, 64, 2, 4) == 0
+
+    def call(**kw):
+        a = dict(Wq=FAKE, O=64, K=128, ldw=128, mask=FAKE, N=2, M=4, Xq=FAKE, T=16, ldx=128, Y=FAKE, ldy=64, dt=2,
+                 ws=FAKE, wsb=1 << 20)
+        a.update(kw)
+        return lib.nm_linear_forward_i8(a["Wq"], a["O"], a["K"], a["ldw"], a["mask"], a["N"], a["M"], a["Xq"], a["T"],
+                                        a["ldx"], 1.0, None, None, a["Y"], a["ldy"], a["dt"], a["ws"], a["wsb"], None)
+
+    assert call(Wq=None) == 1 and call(mask=None) == 1 and call(Xq=None) == 1 and call(Y=None) == 1
+    assert call(N=5, M=4) == 3 and call(M=2) == 3
+    assert call(K=130) == 2 and call(T=0) == 2 and call(ldw=64) == 2 and call(ldx=64) == 2 and call(ldy=8) == 2
+    assert call(dt=3) == 5
+    assert call(mask=FAKE + 2) == 4 and call(Y=FAKE + 2) == 4 and call(Y=FAKE + 2, dt=1) != 4
+    need = lib.nm_i8_workspace_bytes(64, 128, 2, 4)
+    assert call(ws=None, wsb=0) == 6 and call(wsb=need - 1) == 6 and call(ws=FAKE + 16) == 6
+    assert lib.nm_i8_prepare(None, 64, 128, 128, FAKE, 2, 4, FAKE, need, None) == 1
+    assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, None, 0, None) == 6
+    assert lib.nm_i8_prepare(FAKE, 64, 48, 48, FAKE, 1, 8, None, 0, None) == 0  # nothing to prepare
