@@ -20,6 +20,8 @@
 #include "nm_launch.h"
 #include "nm_mma.h"
 
+#include <stdlib.h>
+
 #include <type_traits>
 #include <utility>
 
@@ -126,7 +128,7 @@ struct I8Cfg {
   static constexpr int A_PW = (A_LOADS + NW - 1) / NW;
   static constexpr int S_PW = SPARSE ? (S_LOADS + NW - 1) / NW : 0;
   static constexpr int LPW = X_PW + A_PW + S_PW;
-  static_assert(STAGES == 3 && STAGES * LPW < 64 && LDS_BYTES <= 160 * 1024, "stages");
+  static_assert((STAGES == 2 || STAGES == 3) && STAGES * LPW < 64 && LDS_BYTES <= 160 * 1024, "stages");
   static_assert(!SPARSE || S_BYTES % 1024 == 0, "whole selector loads");
 };
 
@@ -282,7 +284,7 @@ nm_i8_gemm_kernel(const I8Args a) {
   {
     int buf = 0;
     for (int ks = 0; ks < nk; ++ks) {
-      if (ks + 1 < nk) wait_loads_outstanding<C::LPW>();
+      if (STAGES == 3 && ks + 1 < nk) wait_loads_outstanding<C::LPW>();  // one younger stage may still be in flight
       else wait_loads_outstanding<0>();
       __builtin_amdgcn_s_barrier();
       int nbuf = buf + STAGES - 1;
@@ -423,8 +425,12 @@ hipError_t launch_i8_gemm(I8Args g, hipStream_t s) {
 
 template <bool SPARSE>
 hipError_t dispatch_i8(const I8Args& g, hipStream_t s) {
-  const int64_t tiles_big = ((g.O + 127) / 128) * ((g.T + 127) / 128);
-  if (tiles_big >= 256) return launch_i8_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
+  static const int forced = getenv("NM_I8_TILE") ? atoi(getenv("NM_I8_TILE")) : 0;  // tuning aid
+  const int64_t tiles_big = ((g.O + 255) / 256) * ((g.T + 255) / 256);
+  const int64_t tiles_mid = ((g.O + 127) / 128) * ((g.T + 127) / 128);
+  int pick = forced ? forced : (tiles_big >= 256 ? 3 : (tiles_mid >= 256 ? 2 : 1));
+  if (pick == 3) return launch_i8_gemm<SPARSE, 4, 2, 4, 8, SPARSE ? 3 : 2>(g, s);
+  if (pick == 2) return launch_i8_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
   return launch_i8_gemm<SPARSE, 2, 2, 2, 2, 3>(g, s);
 }
 

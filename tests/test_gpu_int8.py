@@ -91,10 +91,12 @@ def test_rescaled_outputs(N, M, out_dtype):
 
 
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 16), (4, 8)])
-def test_large_tile_path_and_prepared_calls(N, M):
-    # at least 256 tiles of 128 x 128 with ragged edges; a prepared workspace serves repeated products unchanged
-    rng = np.random.default_rng(7300 + N + M)
-    T, K, O = 16 * 128 + 37, 256, 16 * 128 + 36
+@pytest.mark.parametrize("edge", [128, 256])
+def test_large_tile_paths_and_prepared_calls(N, M, edge):
+    # at least 256 tiles of 128 x 128, and of 256 x 256, with ragged edges (the two larger tile shapes); a prepared
+    # workspace serves repeated products unchanged
+    rng = np.random.default_rng(7300 + N + M + edge)
+    T, K, O = 16 * edge + 37, 256, 16 * edge + 36
     xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
     mask = random_mask(rng, O, K, N, M)
     words = dev_words(orc.mask_to_words(mask))
