@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_DENSE_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
+PEAK_INT8_DENSE_TOPS = 5000.0    # MI355X dense int8 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -279,9 +280,39 @@ def main():
                 "weight_gradient": {"ms": dw_ms, "roofline": mfma_roofline(dw_ms)}}
     del masked, words, dXs, dWs, gws
 
+    # ---- int8 form of the same block (8-bit quantisation on top of the sparse weights): the masks are those of
+    # the float weights, the int8 operands synthetic; useful operations 2*T*O*K*N/M per product, bf16 output
+    q_masks = [nm.nm_prune(Ws[j], layers[j].N, layers[j].M) for j in train_layers]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    q_w = [torch.randint(-127, 128, (layers[j].O, layers[j].K), device=dev, dtype=torch.int8, generator=gen)
+           for j in train_layers]
+    q_x = [torch.randint(-127, 128, (layers[j].T, layers[j].K), device=dev, dtype=torch.int8, generator=gen)
+           for j in train_layers]
+    q_scale = [torch.full((layers[j].O,), 1e-4, dtype=torch.float32, device=dev) for j in train_layers]
+    q_ws = [nm.nm_i8_prepare(q_w[n], q_masks[n], layers[j].N, layers[j].M) for n, j in enumerate(train_layers)]
+
+    def int8_products():
+        for n, j in enumerate(train_layers):
+            L = layers[j]
+            nm.nm_linear_forward_i8_prepared(q_w[n], q_masks[n], L.N, L.M, q_x[n], q_ws[n], x_scale=0.02,
+                                             w_scale=q_scale[n], out=Ys[j], stream=stream)
+
+    q_ms = timed(int8_products)
+    q_useful = sum(layers[j].useful_flops for j in train_layers)
+    q_tops = q_useful / q_ms / 1e9
+    int8 = {"workload": "one DeiT-B block at batch 256 (qkv, proj, fc1, fc2 at their seed-0 levels), int8 operands, "
+                        "int32 sums rescaled to bf16; useful operations 2*T*O*K*N/M",
+            "ms": q_ms, "dense_equivalent_tops": block_flops / q_ms / 1e9,
+            "roofline": {"bound": "mfma", "achieved": q_tops, "peak": PEAK_INT8_DENSE_TOPS, "unit": "TOP/s",
+                         "frac": q_tops / PEAK_INT8_DENSE_TOPS}}
+    del q_masks, q_w, q_x, q_scale, q_ws
+
     if args.report:
         log(f"training products of one block: dX {dx_ms:.3f} ms ({training['input_gradient']['roofline']['achieved']:.0f} "
             f"TFLOP/s), dW {dw_ms:.3f} ms ({training['weight_gradient']['roofline']['achieved']:.0f} TFLOP/s)")
+        log(f"int8 products of one block: {q_ms:.3f} ms ({q_tops:.0f} useful TOP/s, "
+            f"{int8['dense_equivalent_tops']:.0f} dense-equivalent)")
         log(f"nested levels: rank 48 matrices {rank_ms:.3f} ms ({nested['rank']['roofline']['achieved']:.0f} GB/s), "
             f"pack from ranks {pr_ms:.3f} ms ({nested['pack_ranked']['roofline']['achieved']:.0f} GB/s)")
         log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}")
@@ -317,6 +348,7 @@ def main():
         "roofline": roofline,
         "nested_levels": nested,
         "training_products": training,
+        "int8_products": int8,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
