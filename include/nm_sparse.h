@@ -240,6 +240,9 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
  *       Ws   in   the masked dense weight W (.) m, [O, K], ld ldw (what nm_prune writes to W_masked and what
  *                 nm_unpack restores from the packed form)
  *       dY   in   [T, O], ld ldy            dX   out  [T, K], ld ldx, float or bfloat16 (out_dtype)
+ *       workspace scratch of nm_backward_input_workspace_bytes(O, K, T) bytes, 256-byte aligned (large layers:
+ *                 the weight is first written transposed in matrix-core operand order, then the product is
+ *                 the forward one); NULL allowed when that size is 0.  Contents undefined afterwards.
  *   nm_linear_backward_weight   dW[o, k] = m[o, k] * sum_t dY[t, o] * X[t, k], fp32 accumulation.
  *       dY   in   [T, O], ld ldy            X    in   [T, K], ld ldx
  *       mask in   mask words of the step as nm_prune writes them ([O, ceil(K/32)]); pruned positions receive
@@ -254,9 +257,11 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
  * Errors: NM_ERR_NULL, NM_ERR_SHAPE (sizes <= 0, a leading dimension smaller than its row), NM_ERR_DTYPE,
  * NM_ERR_ALIGN (element alignment), NM_ERR_WORKSPACE, NM_ERR_DEVICE.
  */
+size_t nm_backward_input_workspace_bytes(int64_t O, int64_t K, int64_t T);
 size_t nm_backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T);
 int32_t nm_linear_backward_input(const nm_bf16* Ws, int64_t O, int64_t K, int64_t ldw, const nm_bf16* dY,
-                                 int64_t T, int64_t ldy, void* dX, int64_t ldx, int32_t out_dtype, void* stream);
+                                 int64_t T, int64_t ldy, void* dX, int64_t ldx, int32_t out_dtype,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64_t ldy, const nm_bf16* X,
                                   int64_t K, int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw,
                                   int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);

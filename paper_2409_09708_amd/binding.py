@@ -23,7 +23,7 @@ EXPORTS = (
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
-    "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
+    "nm_backward_input_workspace_bytes", "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
     "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
 )
 
@@ -119,8 +119,10 @@ def load_library() -> ctypes.CDLL:
     lib.nm_backward_weight_workspace_bytes.restype = c_size_t
     lib.nm_backward_weight_workspace_bytes.argtypes = [c_int64, c_int64, c_int64]
     lib.nm_linear_backward_input.restype = c_int32
+    lib.nm_backward_input_workspace_bytes.restype = c_size_t
+    lib.nm_backward_input_workspace_bytes.argtypes = [c_int64, c_int64, c_int64]
     lib.nm_linear_backward_input.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
-                                             c_int64, c_int32, c_void_p]
+                                             c_int64, c_int32, c_void_p, c_size_t, c_void_p]
     lib.nm_linear_backward_weight.restype = c_int32
     lib.nm_linear_backward_weight.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
                                               c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
@@ -506,7 +508,11 @@ def _out_matrix(out, out_dtype, rows: int, cols: int, device, name: str):
     return out, ld, (NM_OUT_F32 if out_dtype == torch.float32 else NM_OUT_BF16)
 
 
-def nm_linear_backward_input(Ws, dY, out_dtype=None, out=None, stream=None):
+def nm_backward_input_workspace_bytes(O: int, K: int, T: int) -> int:
+    return int(load_library().nm_backward_input_workspace_bytes(O, K, T))
+
+
+def nm_linear_backward_input(Ws, dY, out_dtype=None, out=None, workspace=None, stream=None):
     """dX = dY * Ws for the masked dense weight Ws [O, K] and dY [T, O]; float32 (default) or bfloat16 [T, K]."""
     torch = _torch()
     _need(Ws, torch.bfloat16, "Ws")
@@ -516,8 +522,13 @@ def nm_linear_backward_input(Ws, dY, out_dtype=None, out=None, stream=None):
     if OY != O:
         raise ValueError("dY must be [T, O]")
     out, ldx, code = _out_matrix(out, out_dtype, T, K, dY.device, "dX")
+    need = nm_backward_input_workspace_bytes(O, K, T)
+    if workspace is None and need:
+        workspace = _workspace(need, dY.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load_library().nm_linear_backward_input(Ws.data_ptr(), O, K, ldw, dY.data_ptr(), T, ldy, out.data_ptr(), ldx,
-                                                   code, _stream_handle(stream)))
+                                                   code, ws_ptr, ws_bytes, _stream_handle(stream)))
     return out
 
 

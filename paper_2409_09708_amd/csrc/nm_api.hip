@@ -262,16 +262,25 @@ size_t nm_backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T) {
   return nm::backward_weight_workspace_bytes(O, K, T);
 }
 
+size_t nm_backward_input_workspace_bytes(int64_t O, int64_t K, int64_t T) {
+  if (O <= 0 || K <= 0 || T <= 0) return 0;
+  return nm::backward_input_workspace_bytes(O, K, T);
+}
+
 int32_t nm_linear_backward_input(const nm_bf16* Ws, int64_t O, int64_t K, int64_t ldw, const nm_bf16* dY, int64_t T,
-                                 int64_t ldy, void* dX, int64_t ldx, int32_t out_dtype, void* stream) {
+                                 int64_t ldy, void* dX, int64_t ldx, int32_t out_dtype, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
   if (!Ws || !dY || !dX) return NM_ERR_NULL;
   if (O <= 0 || K <= 0 || T <= 0 || O > (int64_t)1 << 31 || K > (int64_t)1 << 31 || T > (int64_t)1 << 31)
     return NM_ERR_SHAPE;
   if (ldw < K || ldy < O || ldx < K) return NM_ERR_SHAPE;
   if (out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16) return NM_ERR_DTYPE;
   if (!aligned(Ws, 2) || !aligned(dY, 2) || !aligned(dX, out_dtype == NM_OUT_F32 ? 4 : 2)) return NM_ERR_ALIGN;
-  return device_status(nm::launch_backward_input(Ws, O, K, ldw, dY, T, ldy, dX, ldx, out_dtype == NM_OUT_BF16,
-                                                 (hipStream_t)stream));
+  bool workspace_short = false;
+  hipError_t e = nm::launch_backward_input(Ws, O, K, ldw, dY, T, ldy, dX, ldx, out_dtype == NM_OUT_BF16, workspace,
+                                           workspace_bytes, (hipStream_t)stream, &workspace_short);
+  if (workspace_short) return NM_ERR_WORKSPACE;
+  return device_status(e);
 }
 
 int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64_t ldy, const nm_bf16* X, int64_t K,

@@ -468,8 +468,28 @@ WeightGradPlan weight_grad_plan(int64_t O, int64_t K, int64_t T) {
 
 }  // namespace
 
+size_t backward_input_workspace_bytes(int64_t O, int64_t K, int64_t T) {
+  return dense_transposed_workspace_bytes(O, K, T);
+}
+
 hipError_t launch_backward_input(const bf16_t* Ws, int64_t O, int64_t K, int64_t ldw, const bf16_t* dY, int64_t T,
-                                 int64_t ldy, void* dX, int64_t ldx, int out_bf16, hipStream_t s) {
+                                 int64_t ldy, void* dX, int64_t ldx, int out_bf16, void* workspace,
+                                 size_t workspace_bytes, hipStream_t s, bool* workspace_short) {
+  *workspace_short = false;
+  // Large layers: dX = dY * Ws is the forward product of a layer whose weight is Ws^T, so once the weight has
+  // been written transposed into stream order (a pass over the weight only) the persistent dense kernel of the
+  // forward path computes it.
+  const size_t need = backward_input_workspace_bytes(O, K, T);
+  if (need) {
+    if (workspace == nullptr || workspace_bytes < need || !aligned_to(workspace, 256)) {
+      *workspace_short = true;
+      return hipSuccess;
+    }
+    bool taken = false;
+    hipError_t e = launch_dense_transposed(Ws, O, K, ldw, dY, T, ldy, dX, ldx, out_bf16, workspace, workspace_bytes, s,
+                                           &taken);
+    if (e != hipSuccess || taken) return e;
+  }
   const bool tiles = (O % 32 == 0) && (K % 8 == 0) && (ldw % 8 == 0) && (ldy % 8 == 0) && aligned_to(Ws, 16) &&
                      aligned_to(dY, 16) && K <= (1 << 24) && T <= (1ll << 31) && ldw <= (1 << 22) && ldy <= (1 << 22);
   if (!tiles) {

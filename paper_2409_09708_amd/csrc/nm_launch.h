@@ -75,9 +75,19 @@ bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* spar
 enum { SPMM_PREPARE = 1, SPMM_PRODUCT = 2 };
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases);
 
+// Out[t, i] = sum_r Q[t, r] * Ws[r, i] on the persistent dense product kernel (weight transposed into stream
+// order in the workspace first); *taken stays false, and nothing is launched, when the shape, the alignment or
+// the workspace do not allow it.
+size_t dense_transposed_workspace_bytes(int64_t R, int64_t I, int64_t T);
+hipError_t launch_dense_transposed(const bf16_t* Ws, int64_t R, int64_t I, int64_t ldw, const bf16_t* Q, int64_t T,
+                                   int64_t ldq, void* Out, int64_t ldo, int out_bf16, void* workspace,
+                                   size_t workspace_bytes, hipStream_t s, bool* taken);
+
 // nm_grad.hip: training products of a layer.  Ws is the masked dense weight [O, K].
+size_t backward_input_workspace_bytes(int64_t O, int64_t K, int64_t T);
 hipError_t launch_backward_input(const bf16_t* Ws, int64_t O, int64_t K, int64_t ldw, const bf16_t* dY, int64_t T,
-                                 int64_t ldy, void* dX, int64_t ldx, int out_bf16, hipStream_t s);
+                                 int64_t ldy, void* dX, int64_t ldx, int out_bf16, void* workspace,
+                                 size_t workspace_bytes, hipStream_t s, bool* workspace_short);
 size_t backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T);
 // *workspace_short is set when the workspace is required but missing, misaligned or too small
 hipError_t launch_backward_weight(const bf16_t* dY, int64_t T, int64_t O, int64_t ldy, const bf16_t* X, int64_t K,

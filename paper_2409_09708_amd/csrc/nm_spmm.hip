@@ -169,6 +169,23 @@ expand_stream_kernel(const bf16_t* __restrict__ values, const uint32_t* __restri
       make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
 }
 
+// dense form of a TRANSPOSED weight: the operand rows are the columns of Ws [R, I] (row-major, ld ldw), the
+// reduction runs over its rows.  One lane per (column i, 8 consecutive reduction rows); lanes run along i, so
+// each of the 8 reads of a wave is one contiguous row segment.  Columns past I (up to the tile edge) are zero.
+__global__ void __launch_bounds__(256)
+transpose_stream_kernel(const bf16_t* __restrict__ Ws, int64_t R, int64_t I, int64_t ldw, int64_t I_pad,
+                        unsigned char* __restrict__ dense_s) {
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= I_pad * (R / 8)) return;
+  const int64_t i = id % I_pad, pc = id / I_pad;
+  uint32_t w[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w[e] = i < I ? (uint32_t)Ws[(pc * 8 + e) * ldw + i] : 0u;
+  const int64_t nk = R / 32, ks = pc >> 2;
+  *reinterpret_cast<uint4*>(dense_s + stream_piece_offset(i, ks, (int)(pc & 3), nk)) =
+      make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Tiled matrix-core product.
 //
@@ -973,6 +990,40 @@ static hipError_t launch_general(const SpmmArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(spmm_general_kernel, dim3((unsigned)(n_o_tiles * n_t_tiles)), dim3(256), 0, s, a.values, a.indices,
                      a.O, a.K, a.N, a.M, a.X, a.T, a.ldx, a.bias, a.Y, a.ldy, a.out_bf16, n_o_tiles);
   return hipGetLastError();
+}
+
+// Out[t, i] = sum_r Q[t, r] * Ws[r, i] on the persistent dense kernel: the weight is written transposed into
+// stream order first (a pass over the weight only), then it is an ordinary product with I out-features and a
+// reduction of R.  Shapes: enough 256 x 256 tiles, R % 64 == 0, Out rows in whole aligned 16-byte pieces.
+size_t dense_transposed_workspace_bytes(int64_t R, int64_t I, int64_t T) {
+  if ((R % 64) || pick_tile(I, T) != 0) return 0;
+  return (size_t)(((I + 255) / 256) * 256) * (size_t)R * 2;
+}
+
+hipError_t launch_dense_transposed(const bf16_t* Ws, int64_t R, int64_t I, int64_t ldw, const bf16_t* Q, int64_t T,
+                                   int64_t ldq, void* Out, int64_t ldo, int out_bf16, void* workspace,
+                                   size_t workspace_bytes, hipStream_t s, bool* taken) {
+  *taken = false;
+  const size_t need = dense_transposed_workspace_bytes(R, I, T);
+  const int per_piece = out_bf16 ? 8 : 4;
+  if (!need || workspace == nullptr || workspace_bytes < need || !aligned_to(workspace, 256)) return hipSuccess;
+  if (!aligned_to(Q, 16) || (ldq % 8) || !aligned_to(Ws, 2) || (ldo % per_piece) || !aligned_to(Out, 16) || (I % per_piece))
+    return hipSuccess;
+  if (I > (1 << 24) || T > (1ll << 31) || ldq > (1 << 22) || R > (1 << 22)) return hipSuccess;
+  const int64_t i_pad = ((I + 255) / 256) * 256;
+  const int64_t n = i_pad * (R / 8);
+  hipLaunchKernelGGL(transpose_stream_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Ws, R, I, ldw, i_pad,
+                     reinterpret_cast<unsigned char*>(workspace));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  GemmArgs g;
+  g.A = reinterpret_cast<const bf16_t*>(workspace); g.sel = nullptr;
+  g.X = Q; g.bias = nullptr; g.Y = Out;
+  g.O = I; g.K = R; g.T = T; g.ldx = ldq; g.ldy = ldo;
+  g.n_o_tiles = g.n_t_tiles = 0;
+  g.out_bf16 = out_bf16; g.vec_store = 1;
+  *taken = true;
+  return dispatch_gemm<false>(g, 0, s);
 }
 
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases) {

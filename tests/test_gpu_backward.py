@@ -43,6 +43,28 @@ def test_input_gradient_tiles(N, M, out_dtype):
     assert torch.equal(nm.nm_linear_backward_input(back, dev_bf16(dY), out_dtype=out_dtype), dX)
 
 
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_input_gradient_large_layers(out_dtype):
+    # enough 256 x 256 output tiles for the persistent kernel of the forward path (the weight is written
+    # transposed into its operand order first): ragged in both output directions, K not a multiple of the tile
+    T, K, O, N, M = 16 * 256 + 37, 16 * 256 + 8, 128, 2, 8
+    assert nm.nm_backward_input_workspace_bytes(O, K, T) == 17 * 256 * O * 2
+    X, W, dY, mask = draw(6150, T, K, O, N, M)
+    dXref, _, BX, _ = orc.nm_linear_backward(dY, X, W, mask)
+    Ws = dev_bf16(orc.apply_mask(W, mask))
+    dX = nm.nm_linear_backward_input(Ws, dev_bf16(dY), out_dtype=out_dtype)
+    check_output(host_output(dX), dXref, BX, O, out_dtype == torch.float32, "large")
+    # a leading dimension larger than the row, on both operands and the output
+    Ws_big = torch.zeros((O, K + 8), dtype=torch.bfloat16, device="cuda")
+    Ws_big[:, :K] = Ws
+    dY_big = torch.zeros((T, O + 8), dtype=torch.bfloat16, device="cuda")
+    dY_big[:, :O] = dev_bf16(dY)
+    out = torch.full((T, K + 16), 7.0, dtype=out_dtype, device="cuda")
+    nm.nm_linear_backward_input(Ws_big[:, :K], dY_big[:, :O], out=out[:, 8:8 + K])
+    assert torch.equal(out[:, 8:8 + K], dX)
+    assert torch.all(out[:, :8] == 7.0) and torch.all(out[:, 8 + K:] == 7.0)
+
+
 def test_input_gradient_views_and_general_shapes():
     # operands and output as views of wider buffers; an output view without 16-byte rows; and shapes the
     # matrix-core kernel does not take (O % 32 != 0, K % 8 != 0) on the general kernel

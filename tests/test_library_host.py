@@ -223,13 +223,21 @@ def test_backward_argument_errors(lib):
         a = dict(Ws=FAKE, O=64, K=64, ldw=64, dY=FAKE, T=16, ldy=64, dX=FAKE, ldx=64, dt=0)
         a.update(kw)
         return lib.nm_linear_backward_input(a["Ws"], a["O"], a["K"], a["ldw"], a["dY"], a["T"], a["ldy"], a["dX"],
-                                            a["ldx"], a["dt"], None)
+                                            a["ldx"], a["dt"], a.get("ws"), a.get("wsb", 0), None)
 
     assert dx(Ws=None) == 1 and dx(dY=None) == 1 and dx(dX=None) == 1
     assert dx(O=0) == 2 and dx(K=-1) == 2 and dx(T=0) == 2
     assert dx(ldw=32) == 2 and dx(ldy=63) == 2 and dx(ldx=8) == 2
     assert dx(dt=3) == 5
     assert dx(Ws=FAKE + 1) == 4 and dx(dX=FAKE + 2) == 4 and dx(dX=FAKE + 2, dt=1) != 4
+    # large layers go through the forward path's kernel with the weight transposed into the scratch
+    big = dict(O=768, K=3072, ldw=3072, T=50432, ldy=768, ldx=3072)
+    need = lib.nm_backward_input_workspace_bytes(768, 3072, 50432)
+    assert need == 3072 * 768 * 2
+    assert lib.nm_backward_input_workspace_bytes(768, 3000, 50432) == 3072 * 768 * 2  # columns padded to whole tiles
+    assert lib.nm_backward_input_workspace_bytes(768, 3072, 197) == 0                 # few tokens: tiled kernel
+    assert lib.nm_backward_input_workspace_bytes(800, 3072, 50432) == 0               # O % 64 != 0: tiled kernel
+    assert dx(**big) == 6 and dx(ws=FAKE, wsb=need - 1, **big) == 6 and dx(ws=FAKE + 16, wsb=need, **big) == 6
 
     def dw(**kw):
         a = dict(dY=FAKE, T=16, O=64, ldy=64, X=FAKE, K=64, ldx=64, mask=None, dW=FAKE, lddw=64, dt=0, ws=None, wsb=0)
