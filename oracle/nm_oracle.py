@@ -10,6 +10,8 @@ What it computes, and where the paper defines it:
 * `nm_mask`      -- Section 3.1, "Dynamic Masking", Eq. (1): in every group of M
                    consecutive weights keep the N with the largest saliency,
                    saliency = weight magnitude (the paper's default).
+* `nm_mask_from_scores` -- the same selection with the saliency given as numbers (Section
+                   3.1 names the Taylor score as an alternative to the magnitude).
 * `apply_mask`   -- Section 3.1: a weight whose mask value is 0 is set to zero.
 * `nm_pack` / `nm_unpack` -- Section 1 and Section 2 (Fig. 2, upper part): the
                    compressed form stores the kept values and, for each, a
@@ -90,6 +92,28 @@ def nm_mask(w_bits: np.ndarray, N: int, M: int) -> np.ndarray:
         raise ValueError("K must be a multiple of M")
     key = saliency_key(w_bits).reshape(O, K // M, M)
     order = np.argsort(-key, axis=-1, kind="stable")  # stable: equal keys stay in position order
+    mask = np.zeros((O, K // M, M), dtype=bool)
+    np.put_along_axis(mask, order[..., :N], True, axis=-1)
+    return mask.reshape(O, K)
+
+
+def nm_mask_from_scores(scores: np.ndarray, N: int, M: int) -> np.ndarray:
+    """Eq. (1) with a saliency supplied from outside (Section 3.1: rho may be the weight magnitude, a Taylor
+    score, ...): boolean mask [O, K] keeping, in every aligned group of M, the N positions with the largest
+    score; equal scores go to the lower index; -0 equals +0; a NaN score ranks above every number (kept first,
+    like the NaN weights of the magnitude rule).  Scores are compared as float32.
+    """
+    check_level(N, M)
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    O, K = s.shape
+    if K % M:
+        raise ValueError("K must be a multiple of M")
+    g = s.reshape(O, K // M, M)
+    nan = np.isnan(g)
+    val = np.where(nan, np.float32(0), g).astype(np.float64)
+    # sort key: NaN first, then descending value; a stable sort keeps position order among equals
+    key = np.where(nan, -np.inf, -val)
+    order = np.argsort(key, axis=-1, kind="stable")
     mask = np.zeros((O, K // M, M), dtype=bool)
     np.put_along_axis(mask, order[..., :N], True, axis=-1)
     return mask.reshape(O, K)

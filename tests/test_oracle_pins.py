@@ -395,3 +395,46 @@ def test_rank_nibbles_round_trip_and_layout():
     nib = orc.rank_nibbles(rank)
     assert nib.tolist() == [[0x30, 0x21, 0xEF, 0x90]]
     assert np.array_equal(orc.nibbles_to_rank(nib), rank)
+
+
+# ------------------------------------------------------------------ masks from a supplied saliency (Section 3.1)
+
+def test_score_mask_equals_the_magnitude_mask_when_the_score_is_the_magnitude():
+    rng = np.random.default_rng(81)
+    for (N, M) in [(1, 4), (2, 4), (3, 8), (4, 16), (8, 8)]:
+        W = wl.tie_heavy_weights(rng, 12, 4 * M)
+        score = np.abs(orc.bf16_bits_to_f64(W)).astype(np.float32)  # exact: bfloat16 magnitudes are float32 numbers
+        assert np.array_equal(orc.nm_mask_from_scores(score, N, M), orc.nm_mask(W, N, M))
+
+
+def test_score_mask_brute_force_and_monotone_invariance():
+    import itertools
+    rng = np.random.default_rng(82)
+    for (N, M) in [(1, 4), (2, 4), (2, 8), (3, 8)]:
+        s = rng.integers(-3, 4, size=(20, M)).astype(np.float32)  # many ties, negative scores too
+        mask = orc.nm_mask_from_scores(s, N, M)
+        for row, m in zip(s, mask):
+            assert m.sum() == N
+            kept = tuple(np.flatnonzero(m))
+            # threshold property, and among all sets with it the lexicographically smallest
+            best = None
+            for c in itertools.combinations(range(M), N):
+                out = [i for i in range(M) if i not in c]
+                if all(row[i] >= row[j] for i in c for j in out):
+                    best = c if best is None else min(best, c)
+            assert kept == best
+        # a strictly increasing map of the scores changes nothing
+        assert np.array_equal(orc.nm_mask_from_scores(2.0 * s + 1.0, N, M), mask)
+        assert np.array_equal(orc.nm_mask_from_scores(np.exp(s), N, M), mask)
+
+
+def test_score_mask_special_values_and_a_taylor_example():
+    # -0 ties +0 (lower index wins); NaN ranks first; -inf last
+    s = np.array([[-0.0, 0.0, -1.0, -np.inf], [1.0, np.nan, 2.0, np.inf]], dtype=np.float32)
+    assert orc.nm_mask_from_scores(s, 1, 4).tolist() == [[True, False, False, False], [False, True, False, False]]
+    assert orc.nm_mask_from_scores(s, 2, 4).tolist() == [[True, True, False, False], [False, True, False, True]]
+    # first-order Taylor saliency |w * g| of one group: w = (4, -1, 2, 0.5), g = (0.1, -3, 1, 8) -> (0.4, 3, 2, 4):
+    # the largest weight is pruned, which the magnitude rule would keep
+    w = np.array([[4.0, -1.0, 2.0, 0.5]])
+    g = np.array([[0.1, -3.0, 1.0, 8.0]])
+    assert orc.nm_mask_from_scores(np.abs(w * g), 2, 4).tolist() == [[False, True, False, True]]
