@@ -267,6 +267,18 @@ int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64
                                   int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * nm_prune_scored -- Eq. (1) with a saliency supplied by the caller (Section 3.1: rho can be the weight magnitude,
+ * a Taylor score, ...): in every aligned group of M the N positions with the largest score are kept.
+ *   score  in   float [O, K], ld lds, 4-byte aligned.  Equal scores go to the lower index; -0 equals +0; a NaN
+ *               ranks above every number.
+ *   mask   out  [O, ceil(K/32)] words as nm_prune writes them; feed them to nm_pack(mask), nm_mask_check,
+ *               nm_linear_backward_weight or the int8 calls.
+ * With score = |W| it writes the mask nm_prune writes.
+ */
+int32_t nm_prune_scored(const float* score, int64_t O, int64_t K, int64_t lds, int32_t N, int32_t M,
+                        uint32_t* mask, void* stream);
+
+/*
  * int8 form of the layer (Section 4, the post-training-quantisation experiment of Table 6: 8-bit quantisation on
  * top of the sparse networks; Section 3.1: any saliency may produce the mask):
  *

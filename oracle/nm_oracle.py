@@ -111,9 +111,11 @@ def nm_mask_from_scores(scores: np.ndarray, N: int, M: int) -> np.ndarray:
     g = s.reshape(O, K // M, M)
     nan = np.isnan(g)
     val = np.where(nan, np.float32(0), g).astype(np.float64)
-    # sort key: NaN first, then descending value; a stable sort keeps position order among equals
-    key = np.where(nan, -np.inf, -val)
-    order = np.argsort(key, axis=-1, kind="stable")
+    # NaN first, then descending value, then ascending position: stable sorts compose, minor key first
+    by_value = np.argsort(-val, axis=-1, kind="stable")
+    nan_sorted = np.take_along_axis(nan, by_value, axis=-1)
+    nan_first = np.argsort(~nan_sorted, axis=-1, kind="stable")
+    order = np.take_along_axis(by_value, nan_first, axis=-1)
     mask = np.zeros((O, K // M, M), dtype=bool)
     np.put_along_axis(mask, order[..., :N], True, axis=-1)
     return mask.reshape(O, K)

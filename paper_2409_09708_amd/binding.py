@@ -24,7 +24,7 @@ EXPORTS = (
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
     "nm_backward_input_workspace_bytes", "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
-    "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
+    "nm_prune_scored", "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
 )
 
 
@@ -126,6 +126,8 @@ def load_library() -> ctypes.CDLL:
     lib.nm_linear_backward_weight.restype = c_int32
     lib.nm_linear_backward_weight.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
                                               c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_prune_scored.restype = c_int32
+    lib.nm_prune_scored.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
     lib.nm_i8_workspace_bytes.restype = c_size_t
     lib.nm_i8_workspace_bytes.argtypes = [c_int64, c_int64, c_int32, c_int32]
     i8_args = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_void_p, c_int64, c_int64,
@@ -217,6 +219,16 @@ def nm_prune(W, N: int, M: int, W_masked=None, stream=None):
             raise ValueError("W_masked must have the shape and leading dimension of W")
         wm_ptr = W_masked.data_ptr()
     _check(load_library().nm_prune(W.data_ptr(), O, K, ldw, N, M, mask.data_ptr(), wm_ptr, _stream_handle(stream)))
+    return mask
+
+
+def nm_prune_scored(score, N: int, M: int, stream=None):
+    """Mask words [O, ceil(K/32)] (int32) keeping the N largest of every M scores (float32 [O, K])."""
+    torch = _torch()
+    _need(score, torch.float32, "score")
+    O, K, lds = _rows(score, "score")
+    mask = torch.empty((O, (K + 31) // 32), dtype=torch.int32, device=score.device)
+    _check(load_library().nm_prune_scored(score.data_ptr(), O, K, lds, N, M, mask.data_ptr(), _stream_handle(stream)))
     return mask
 
 

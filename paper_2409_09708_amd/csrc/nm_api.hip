@@ -327,4 +327,13 @@ int32_t nm_linear_forward_i8_prepared(const int8_t* Wq, int64_t O, int64_t K, in
                   workspace_bytes, stream, nm::SPMM_PRODUCT);
 }
 
+int32_t nm_prune_scored(const float* score, int64_t O, int64_t K, int64_t lds, int32_t N, int32_t M, uint32_t* mask,
+                        void* stream) {
+  if (!score || !mask) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (lds < K) return NM_ERR_SHAPE;
+  if (!aligned(score, 4) || !aligned(mask, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_score_mask(score, O, K, lds, N, M, mask, (hipStream_t)stream));
+}
+
 }  // extern "C"

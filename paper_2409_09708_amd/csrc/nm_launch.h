@@ -49,6 +49,8 @@ struct RankDesc {
   int32_t M, reserved;
 };
 hipError_t launch_rank_batched(const RankDesc* descs, int count, hipStream_t s);
+hipError_t launch_score_mask(const float* score, int64_t O, int64_t K, int64_t lds, int N, int M, uint32_t* mask,
+                             hipStream_t s);
 hipError_t launch_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int N, uint32_t* mask, hipStream_t s);
 
 // nm_spmm.hip

@@ -129,6 +129,44 @@ rank_mask_kernel(const uint8_t* __restrict__ rank, int64_t O, int64_t K, int N, 
   mask[o * nw + w] = word;
 }
 
+// Mask words of level N:M from a supplied saliency (Section 3.1: rho may be any score): one lane per mask word.
+// Order inside a group: NaN first, then descending value (-0 = +0), then ascending position; a weight is kept
+// when fewer than N members of its group come before it.
+__device__ __forceinline__ uint32_t score_key(float v) {
+  // unsigned key that increases with the score; every NaN maps above +inf
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0xFFFFFFFFu;
+  if (u == 0x80000000u) u = 0u;  // -0 ties +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ void __launch_bounds__(256)
+score_mask_kernel(const float* __restrict__ score, int64_t O, int64_t K, int64_t lds, int N, int M,
+                  uint32_t* __restrict__ mask) {
+  const int64_t nw = mask_words_per_row(K);
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * nw) return;
+  const int64_t o = id / nw, w = id % nw;
+  const int64_t k_end = (w * 32 + 32 < K) ? w * 32 + 32 : K;
+  const float* row = score + o * lds;
+  uint32_t word = 0;
+  for (int64_t g = w * 32; g < k_end; g += M) {  // M divides 32 and K, so groups never straddle a word
+    uint32_t key[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) key[i] = i < M ? score_key(row[g + i]) : 0u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (i >= M) break;
+      int before = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (j < M) before += (key[j] > key[i] || (key[j] == key[i] && j < i)) ? 1 : 0;
+      word |= (before < N ? 1u : 0u) << ((g + i) & 31);
+    }
+  }
+  mask[o * nw + w] = word;
+}
+
 static bool rank_flat_ok(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, const uint8_t* rank) {
   return ldw == K && (O * K) % 16 == 0 && (((uintptr_t)W | (uintptr_t)rank) & 15u) == 0 &&
          (O * K / 16 + 255) / 256 <= 0x7FFFFFFF;
@@ -184,6 +222,14 @@ hipError_t launch_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int N, ui
   const int64_t n = O * mask_words_per_row(K);
   if ((n + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipLaunchKernelGGL(rank_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, rank, O, K, N, mask);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_mask(const float* score, int64_t O, int64_t K, int64_t lds, int N, int M, uint32_t* mask,
+                             hipStream_t s) {
+  const int64_t n = O * mask_words_per_row(K);
+  if ((n + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(score_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, score, O, K, lds, N, M, mask);
   return hipGetLastError();
 }
 

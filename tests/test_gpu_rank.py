@@ -93,3 +93,39 @@ def test_rank_batched_equals_single_calls():
     for w, (O, K, M), r in zip(Ws, shapes, ranks):
         assert torch.equal(r, nm.nm_rank(w, M)), (O, K, M)
         assert np.array_equal(host_bytes(r), orc.rank_nibbles(orc.nm_rank(host_bits(w), M))), (O, K, M)
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (3, 8), (4, 8), (4, 16), (16, 16)])
+def test_mask_from_a_supplied_saliency(N, M):
+    # Section 3.1: any saliency may rank the weights.  Random scores with many ties, signed zeros, infinities and
+    # NaN; K not a multiple of 32; a leading dimension larger than the row
+    rng = np.random.default_rng(900 + N + M)
+    O, K = 37, 5 * M if M < 16 else 3 * M
+    s = rng.integers(-4, 5, size=(O, K + 8)).astype(np.float32)
+    s[rng.random(s.shape) < 0.05] = np.nan
+    s[rng.random(s.shape) < 0.05] = -0.0
+    s[rng.random(s.shape) < 0.03] = np.inf
+    s[rng.random(s.shape) < 0.03] = -np.inf
+    ref = orc.nm_mask_from_scores(s[:, :K], N, M)
+    words = nm.nm_prune_scored(torch.from_numpy(s).cuda()[:, :K], N, M)
+    assert np.array_equal(host_words(words), orc.mask_to_words(ref))
+    assert nm.nm_mask_check(words, K, N, M) == 0
+
+
+def test_taylor_saliency_mask_feeds_the_packing_call():
+    # first-order Taylor saliency |w * g| (Section 3.1 names it as an alternative to the magnitude): the mask
+    # it gives packs to the bytes the checker packs with the same mask, and with score = |w| it is nm_prune's mask
+    rng = np.random.default_rng(901)
+    O, K, N, M = 64, 256, 2, 8
+    W = wl.draw_weights(rng, O, K)
+    g = rng.standard_normal((O, K)).astype(np.float32)
+    wf = orc.bf16_bits_to_f64(W).astype(np.float32)
+    score = np.abs(wf * g)
+    ref = orc.nm_mask_from_scores(score, N, M)
+    words = nm.nm_prune_scored(torch.from_numpy(score).cuda(), N, M)
+    assert np.array_equal(host_words(words), orc.mask_to_words(ref))
+    v, i = nm.nm_pack(dev_bf16(W), N, M, mask=words)
+    vals, idx = orc.nm_pack(W, ref, N, M)
+    assert np.array_equal(host_bits(v), vals) and np.array_equal(host_words(i), idx)
+    same = nm.nm_prune_scored(torch.from_numpy(np.abs(wf)).cuda(), N, M)
+    assert torch.equal(same, nm.nm_prune(dev_bf16(W), N, M))

@@ -295,3 +295,12 @@ def test_int8_argument_errors_and_sizes(lib):
     assert lib.nm_i8_prepare(None, 64, 128, 128, FAKE, 2, 4, FAKE, need, None) == 1
     assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, None, 0, None) == 6
     assert lib.nm_i8_prepare(FAKE, 64, 48, 48, FAKE, 1, 8, None, 0, None) == 0  # nothing to prepare
+
+
+def test_prune_scored_argument_errors(lib):
+    f = lib.nm_prune_scored
+    assert f(None, 4, 16, 16, 2, 4, FAKE, None) == 1 and f(FAKE, 4, 16, 16, 2, 4, None, None) == 1
+    assert f(FAKE, 4, 16, 16, 5, 4, FAKE, None) == 3 and f(FAKE, 4, 16, 16, 2, 5, FAKE, None) == 3
+    assert f(FAKE, 4, 18, 18, 2, 4, FAKE, None) == 2 and f(FAKE, 0, 16, 16, 2, 4, FAKE, None) == 2
+    assert f(FAKE, 4, 16, 12, 2, 4, FAKE, None) == 2
+    assert f(FAKE + 2, 4, 16, 16, 2, 4, FAKE, None) == 4 and f(FAKE, 4, 16, 16, 2, 4, FAKE + 2, None) == 4

@@ -433,6 +433,10 @@ def test_score_mask_special_values_and_a_taylor_example():
     s = np.array([[-0.0, 0.0, -1.0, -np.inf], [1.0, np.nan, 2.0, np.inf]], dtype=np.float32)
     assert orc.nm_mask_from_scores(s, 1, 4).tolist() == [[True, False, False, False], [False, True, False, False]]
     assert orc.nm_mask_from_scores(s, 2, 4).tolist() == [[True, True, False, False], [False, True, False, True]]
+    # a NaN ranks above +inf wherever it stands
+    t = np.array([[np.inf, 5.0, np.nan, np.inf]], dtype=np.float32)
+    assert orc.nm_mask_from_scores(t, 1, 4).tolist() == [[False, False, True, False]]
+    assert orc.nm_mask_from_scores(t, 2, 4).tolist() == [[True, False, True, False]]
     # first-order Taylor saliency |w * g| of one group: w = (4, -1, 2, 0.5), g = (0.1, -3, 1, 8) -> (0.4, 3, 2, 4):
     # the largest weight is pruned, which the magnitude rule would keep
     w = np.array([[4.0, -1.0, 2.0, 0.5]])
