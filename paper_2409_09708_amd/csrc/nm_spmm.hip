@@ -558,9 +558,32 @@ struct StreamCfg {
   static_assert(LDS_BYTES * PER_CU <= 160 * 1024 && STAGES * (LPW + 1) < 64, "LDS budget and vmcnt range");
 };
 
+// One launch serves a list of layers of the same operand form: their tiles form one list (layer after layer),
+// which the blocks share as they share the tiles of a single layer.  A stack of independent products then ends
+// in ONE partial round of tiles instead of one per layer (591 tiles on 256 compute units are 2.3 rounds and
+// cost 3).  The table travels in the kernel arguments.
+struct StreamLayer {
+  const bf16_t* A;      // stream-order values (2:4 form) or dense weight
+  const uint32_t* sel;  // stream-order selectors (2:4 form)
+  const bf16_t* X;
+  const float* bias;    // nullable
+  void* Y;
+  int32_t O, T, nk, ldx, ldy;  // nk: K steps of the form (K / 64 or K / 32)
+  int32_t n_o_tiles;
+  int32_t tile_begin, tile_end;  // this layer's range in the launch's tile list
+  int32_t out_bf16;
+  int32_t reserved;
+};
+constexpr int kStreamLayersMax = 48;
+struct StreamGroup {
+  int32_t count, n_tiles;
+  StreamLayer layer[kStreamLayersMax];
+};
+static_assert(sizeof(StreamGroup) <= 4096, "the table must fit the kernel argument segment");
+
 template <bool SPARSE, int WO_, int WT_, int STAGES_>
 __global__ void __launch_bounds__(WO_ * WT_ * 64, (WO_ * WT_ == 4 && STAGES_ == 2) ? 2 : (WO_ * WT_) / 4)
-nm_stream_kernel(const GemmArgs a) {
+nm_stream_kernel(const StreamGroup g) {
   using C = StreamCfg<SPARSE, WO_, WT_, STAGES_>;
   constexpr int OT = C::OT, TT = C::TT, STAGES = C::STAGES;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -569,7 +592,7 @@ nm_stream_kernel(const GemmArgs a) {
   // ---- this block's tiles: every XCD (block id mod 8) owns a contiguous range of tiles, out-feature
   // tiles fastest, and its blocks take them round-robin, so that the blocks sharing an L2 work on
   // neighbouring tiles (same X rows) at the same time
-  const int n_tiles = a.n_o_tiles * a.n_t_tiles;
+  const int n_tiles = g.n_tiles;
   const int per_xcd = (n_tiles + 7) >> 3;
   const int slots = (int)(gridDim.x >> 3);
   const int xcd_first = (int)(blockIdx.x & 7) * per_xcd;
@@ -586,60 +609,74 @@ nm_stream_kernel(const GemmArgs a) {
   const int r16 = lane & 15;
   const int kb = lane >> 4;
 
-  // ---- fixed per-lane source offsets and per-wave LDS destinations of this wave's loads.  The W piece a
-  // load brings is the one of 16-row group (wave + 8 i) of the tile: group and lane are folded into the
-  // lane offset, so every load of a stage uses one of three running base pointers.
+  // ---- per-lane source offsets (they depend on the layer: its row pitch and K steps) and per-wave LDS
+  // destinations of this wave's loads.  The W piece a load brings is the one of 16-row group (wave + 8 i) of
+  // the tile: group and lane are folded into the lane offset, so every load of a stage uses one of three
+  // running base pointers.
   uint32_t x_voff[C::X_PW], w_voff[C::A_PW];
   uint32_t x_dst[C::X_PW], a_dst[C::A_PW];
 #pragma unroll
-  for (int i = 0; i < C::X_PW; ++i) {
-    const int j = wave + i * C::NW;
-    int row, c;
-    if (SPARSE) { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (row & 7); }
-    else { row = 16 * j + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
-    x_voff[i] = (uint32_t)(((int64_t)row * a.ldx + c * 8) * 2);
-    x_dst[i] = (uint32_t)(j * 1024);
-  }
-  const int nk = (int)(a.K / C::KSTEP);
+  for (int i = 0; i < C::X_PW; ++i) x_dst[i] = (uint32_t)((wave + i * C::NW) * 1024);
 #pragma unroll
-  for (int i = 0; i < C::A_PW; ++i) {
-    const int grp = wave + i * C::NW;
-    w_voff[i] = ((uint32_t)(grp * nk) << 10) + (uint32_t)(lane * 16);  // < 16 * 2^16 * 2^10
-    a_dst[i] = (uint32_t)(C::X_BYTES + grp * 1024);
-  }
+  for (int i = 0; i < C::A_PW; ++i) a_dst[i] = (uint32_t)(C::X_BYTES + (wave + i * C::NW) * 1024);
+  auto layer_offsets = [&](int ldx, int nk) {
+#pragma unroll
+    for (int i = 0; i < C::X_PW; ++i) {
+      const int j = wave + i * C::NW;
+      int row, c;
+      if (SPARSE) { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (row & 7); }
+      else { row = 16 * j + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
+      x_voff[i] = (uint32_t)(((int64_t)row * ldx + c * 8) * 2);
+    }
+#pragma unroll
+    for (int i = 0; i < C::A_PW; ++i)
+      w_voff[i] = ((uint32_t)((wave + i * C::NW) * nk) << 10) + (uint32_t)(lane * 16);  // < 16 * 2^16 * 2^10
+  };
   uint32_t s_voff[C::S_PW > 0 ? C::S_PW : 1], s_dst[C::S_PW > 0 ? C::S_PW : 1];
 #pragma unroll
   for (int i = 0; i < C::S_PW; ++i) {
     s_voff[i] = (uint32_t)((wave + i * C::NW) * 256 + lane * 4);
     s_dst[i] = (uint32_t)(C::X_BYTES + C::A_BYTES + (wave + i * C::NW) * 256);
   }
-  const bool bias_wave = a.bias != nullptr && wave == 0;  // wave 0 also fetches the tiles' bias slices
 
-  // ---- tile origins; load cursor = the stage to be issued next (tile number in this block, k step) as
-  // running pointers: X rows of the tile at the step's k, W and selector blocks of the step
-  auto tile_origin = [&](int n, int& o_tile, int64_t& t_lo, int64_t& t0) {
+  // ---- the block's n-th tile: its layer (tiles come in ascending order, so the search resumes where it
+  // stopped), out-feature tile and token rows.  A ragged last token tile is shifted back inside X.
+  auto tile_place = [&](int n, int& layer, int& o_tile, int64_t& t_lo, int64_t& t0) {
     const int tile = first + n * slots;
-    o_tile = tile % a.n_o_tiles;
-    t_lo = (int64_t)(tile / a.n_o_tiles) * C::BT;
-    t0 = t_lo + C::BT <= a.T ? t_lo : a.T - C::BT;
+    while (tile >= g.layer[layer].tile_end) ++layer;
+    const int local = tile - g.layer[layer].tile_begin;
+    const int n_o = g.layer[layer].n_o_tiles;
+    o_tile = local % n_o;
+    t_lo = (int64_t)(local / n_o) * C::BT;
+    const int64_t T = g.layer[layer].T;
+    t0 = t_lo + C::BT <= T ? t_lo : T - C::BT;
   };
-  const unsigned char* const w_all = reinterpret_cast<const unsigned char*>(a.A);
-  const unsigned char* const s_all = reinterpret_cast<const unsigned char*>(a.sel);
-  int ld_n = 0, ld_ks = 0;
+
+  // ---- load cursor = the stage to be issued next (tile number in this block, k step) as running pointers: X
+  // rows of the tile at the step's k, W and selector blocks of the step
+  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_layer = 0, ld_offsets_of = -1;
   uint32_t ld_bias_voff = 0;
+  const float* ld_bias = nullptr;
   const unsigned char* ld_x = nullptr;
   const unsigned char* ld_w = nullptr;
   const unsigned char* ld_s = nullptr;
   auto cursor_tile = [&](int n) {
     int o_tile;
     int64_t t_lo, t0;
-    tile_origin(n, o_tile, t_lo, t0);
-    ld_x = reinterpret_cast<const unsigned char*>(a.X + t0 * a.ldx);
-    ld_w = w_all + (((int64_t)o_tile * 16 * nk) << 10);
-    ld_s = SPARSE ? s_all + (((int64_t)o_tile * nk) << 11) : nullptr;
+    tile_place(n, ld_layer, o_tile, t_lo, t0);
+    const StreamLayer& L = g.layer[ld_layer];
+    ld_nk = L.nk;
+    if (ld_offsets_of != ld_layer) {
+      layer_offsets(L.ldx, ld_nk);
+      ld_offsets_of = ld_layer;
+    }
+    ld_x = reinterpret_cast<const unsigned char*>(L.X + t0 * L.ldx);
+    ld_w = reinterpret_cast<const unsigned char*>(L.A) + (((int64_t)o_tile * 16 * ld_nk) << 10);
+    ld_s = SPARSE ? reinterpret_cast<const unsigned char*>(L.sel) + (((int64_t)o_tile * ld_nk) << 11) : nullptr;
     // bias[o0 + 4 lane ..]: past the last out-feature re-read the last four (never stored)
     const int64_t ob = (int64_t)o_tile * C::BO + lane * 4;
-    ld_bias_voff = (uint32_t)((ob + 4 <= a.O ? ob : a.O - 4) * 4);
+    ld_bias = L.bias;
+    ld_bias_voff = (uint32_t)((ob + 4 <= L.O ? ob : L.O - 4) * 4);
     ld_n = n;
     ld_ks = 0;
   };
@@ -649,7 +686,7 @@ nm_stream_kernel(const GemmArgs a) {
     if (SPARSE) ld_s += 2048;
     // past the block's last stage the cursor walks the last tile again: the step below then needs no
     // conditions (the surplus stages land in buffers nobody reads any more)
-    if (++ld_ks == nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
+    if (++ld_ks == ld_nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
   };
   // the d-th of this wave's LPW loads of the cursor's stage into the stage buffer at LDS offset stage_off
   auto issue_one = [&](auto d_tag, uint32_t stage_off) {
@@ -658,8 +695,8 @@ nm_stream_kernel(const GemmArgs a) {
     if constexpr (d == 0) {
       // a tile's first stage brings the tile's bias slice along (older than the stage's own loads, so
       // every wait that covers the stage covers it); slice s belongs to stage buffer s
-      if (bias_wave && ld_ks == 0)
-        dma16(make_uniform(a.bias), ld_bias_voff,
+      if (wave == 0 && ld_bias != nullptr && ld_ks == 0)  // wave 0 also fetches the tiles' bias slices
+        dma16(make_uniform(ld_bias), ld_bias_voff,
               __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)C::BIAS0 + stage_off / (uint32_t)C::STAGE * (C::BO * 4)));
     }
     if constexpr (d < C::X_PW) {
@@ -790,16 +827,19 @@ nm_stream_kernel(const GemmArgs a) {
     cur_off = nxt_off;
   };
 
+  int cp_layer = 0;
   for (int n = 0; n < my_tiles; ++n) {
     int o_tile;
     int64_t t_lo, t0;
-    tile_origin(n, o_tile, t_lo, t0);
+    tile_place(n, cp_layer, o_tile, t_lo, t0);
+    const StreamLayer& L = g.layer[cp_layer];
+    const int nk = L.nk;
     const int64_t o0 = (int64_t)o_tile * C::BO;
 #pragma unroll
     for (int i = 0; i < OT; ++i) {
       // the accumulators start from the bias, which came with the tile's first stage
       f32x4_t b = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      if (a.bias != nullptr)
+      if (L.bias != nullptr)
         b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + cur_off / (uint32_t)C::STAGE * (C::BO * 4) +
                                               (wo * C::OW + i * 16 + kb * 4) * 4);
 #pragma unroll
@@ -828,7 +868,7 @@ nm_stream_kernel(const GemmArgs a) {
     for (int j = 0; j < TT; ++j) {
       const int64_t t = t0 + wt * 128 + j * 16 + r16;
       const bool row_ok = t >= t_lo;
-      if (a.out_bf16) {
+      if (L.out_bf16) {
 #pragma unroll
         for (int ip = 0; ip < OT / 2; ++ip) {
           const f32x4_t v0 = acc[2 * ip][j], v1 = acc[2 * ip + 1][j];
@@ -839,16 +879,16 @@ nm_stream_kernel(const GemmArgs a) {
           const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
           const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
           const int64_t o = o0 + wo * C::OW + (2 * ip + (kb & 1)) * 16 + (kb >> 1) * 8;
-          if (row_ok && o < a.O)
-            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(a.Y) + t * a.ldy + o) =
+          if (row_ok && o < L.O)
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(L.Y) + t * L.ldy + o) =
                 u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
         }
       } else {
 #pragma unroll
         for (int i = 0; i < OT; ++i) {
           const int64_t o = o0 + wo * C::OW + i * 16 + kb * 4;
-          if (row_ok && o < a.O)
-            *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(a.Y) + t * a.ldy + o) = acc[i][j];
+          if (row_ok && o < L.O)
+            *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(L.Y) + t * L.ldy + o) = acc[i][j];
         }
       }
     }
@@ -892,7 +932,7 @@ static bool tiles_ok(int64_t K, const void* X, int64_t ldx, const void* values, 
   if (K % 64) return false;
   if (!aligned_to(X, 16) || (ldx % 8)) return false;
   if (!aligned_to(values, 16) || !aligned_to(indices, 8)) return false;
-  if (O > (1 << 24) || T > (1ll << 31)) return false;
+  if (O > (1 << 24) || T >= (1ll << 31)) return false;
   if (ldx > (1 << 22) || K > (1 << 22)) return false;  // per-lane byte offsets inside a tile stay below 2^32
   return true;
 }
@@ -950,10 +990,10 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <bool SPARSE, int WO_, int WT_, int STAGES_>
-static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
-  using C = StreamCfg<SPARSE, WO_, WT_, STAGES_>;
-  auto kern = nm_stream_kernel<SPARSE, WO_, WT_, STAGES_>;
+template <bool SPARSE>
+static hipError_t launch_stream_group(const StreamGroup& grp, hipStream_t s) {
+  using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4>;  // dense stages are half the size: four fit
+  auto kern = nm_stream_kernel<SPARSE, 4, 2, SPARSE ? 3 : 4>;
   static int n_cu = 0;  // filled once; a race only repeats the query
   if (!n_cu) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -964,21 +1004,43 @@ static hipError_t launch_stream(GemmArgs g, hipStream_t s) {
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     n_cu = cus > 8 ? (cus / 8) * 8 : 8;
   }
-  g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
-  g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
-  const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
-  if (n_tiles > 0x7FFFFFF0) return hipErrorInvalidValue;
-  const int64_t want = ((n_tiles + 7) / 8) * 8;
+  const int64_t want = (((int64_t)grp.n_tiles + 7) / 8) * 8;
   const int64_t resident = (int64_t)n_cu * C::PER_CU;  // persistent blocks: as many as fit at once
   const unsigned grid = (unsigned)(want < resident ? want : resident);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, s, g);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, s, grp);
   return hipGetLastError();
+}
+
+// Appends a layer to the table of a launch; false when its tiles would overflow the list.
+template <bool SPARSE>
+static bool group_append(StreamGroup& grp, const GemmArgs& g) {
+  using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4>;
+  const int64_t n_o = (g.O + C::BO - 1) / C::BO, n_t = (g.T + C::BT - 1) / C::BT;
+  const int64_t end = (int64_t)grp.n_tiles + n_o * n_t;
+  if (grp.count >= kStreamLayersMax || end > 0x7FFFFFF0) return false;
+  StreamLayer& L = grp.layer[grp.count++];
+  L.A = g.A; L.sel = g.sel; L.X = g.X; L.bias = g.bias; L.Y = g.Y;
+  L.O = (int32_t)g.O; L.T = (int32_t)g.T; L.nk = (int32_t)(g.K / C::KSTEP);
+  L.ldx = (int32_t)g.ldx; L.ldy = (int32_t)g.ldy;
+  L.n_o_tiles = (int32_t)n_o;
+  L.tile_begin = grp.n_tiles; L.tile_end = (int32_t)end;
+  L.out_bf16 = g.out_bf16; L.reserved = 0;
+  grp.n_tiles = (int32_t)end;
+  return true;
+}
+
+template <bool SPARSE>
+static hipError_t launch_stream(const GemmArgs& g, hipStream_t s) {
+  StreamGroup grp;
+  grp.count = 0; grp.n_tiles = 0;
+  if (!group_append<SPARSE>(grp, g)) return hipErrorInvalidValue;
+  return launch_stream_group<SPARSE>(grp, s);
 }
 
 template <bool SPARSE>
 static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
-    case 0: return launch_stream<SPARSE, 4, 2, SPARSE ? 3 : 4>(g, s);  // dense stages are half the size: four fit
+    case 0: return launch_stream<SPARSE>(g, s);
     case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
     default: return launch_gemm<SPARSE, 2, 2, 2, 2, 3>(g, s);
   }
@@ -1009,7 +1071,7 @@ hipError_t launch_dense_transposed(const bf16_t* Ws, int64_t R, int64_t I, int64
   if (!need || workspace == nullptr || workspace_bytes < need || !aligned_to(workspace, 256)) return hipSuccess;
   if (!aligned_to(Q, 16) || (ldq % 8) || !aligned_to(Ws, 2) || (ldo % per_piece) || !aligned_to(Out, 16) || (I % per_piece))
     return hipSuccess;
-  if (I > (1 << 24) || T > (1ll << 31) || ldq > (1 << 22) || R > (1 << 22)) return hipSuccess;
+  if (I > (1 << 24) || T >= (1ll << 31) || ldq > (1 << 22) || R > (1 << 22) || ldo > 0x7FFFFFFF) return hipSuccess;
   const int64_t i_pad = ((I + 255) / 256) * 256;
   const int64_t n = i_pad * (R / 8);
   hipLaunchKernelGGL(transpose_stream_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Ws, R, I, ldw, i_pad,
@@ -1054,7 +1116,7 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
 
   if (pick == 0) {
     // persistent kernel: every level goes through the stream-order pre-pass; it writes Y in 16-byte pieces only
-    if (product && !g.vec_store) return launch_general(a, s);  // reads the packed layout itself
+    if (product && (!g.vec_store || a.ldy > 0x7FFFFFFF)) return launch_general(a, s);  // reads the packed layout itself
     const int64_t o_pad = ((a.O + 255) / 256) * 256;
     if (sparse_form) {
       unsigned char* vals_s = ws;
