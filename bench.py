@@ -113,8 +113,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="streams the 48 independent products of a step are issued on")
+    ap.add_argument("--schedule", default="batched", choices=("batched", "streams", "single"),
+                    help="how the 48 independent products of a step are launched")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true", help="per-layer table on stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -151,17 +151,25 @@ def main():
     stream = torch.cuda.current_stream()
     pack_args = [(W, L.N, L.M, L.T) for W, L in zip(Ws, layers)]
 
-    # The 48 products of a step are independent (every layer has its own input), so they are issued alternately
-    # on two streams of equal priority: a persistent product kernel ends with a partial round of tiles (591 tiles
-    # on 256 compute units = 2.3 rounds for the 768-wide layers), and the next kernel's blocks start on the
-    # compute units that fall idle instead of waiting for the whole grid to drain.
-    side = torch.cuda.Stream(device=dev) if args.streams == 2 else None
+    # The 48 products of a step are independent (every layer has its own input).  A persistent product kernel
+    # ends with a partial round of tiles (591 tiles on 256 compute units = 2.3 rounds for the 768-wide layers,
+    # which then cost 3), so the step hands all of them to the library at once: layers of one operand form share
+    # a launch whose blocks walk the tiles of all of them as one list (2 launches instead of 48).
+    # --schedule streams: one launch per layer, alternating between two streams of equal priority, so that the
+    # next kernel's blocks start on the compute units that fall idle.  --schedule single: one launch per layer,
+    # one stream.
+    side = torch.cuda.Stream(device=dev) if args.schedule == "streams" else None
     packed_ready, side_done = torch.cuda.Event(), torch.cuda.Event()
+    descs = nm.forward_descs([(v, i, L.K, L.N, L.M, X, ws, None, Y)
+                              for L, (v, i), X, Y, ws in zip(layers, packed, Xs, Ys, workspaces)])
 
     def step():
         # the whole path: select + pack all 48 weights and write their operand-order forms (one launch), then
         # the 48 products at each layer's own level
         nm.nm_pack_prepare_batched(pack_args, stream=stream, out=packed, workspaces=workspaces)
+        if args.schedule == "batched":
+            nm.nm_linear_forward_prepared_batched(descs, stream=stream)
+            return
         if side is not None:
             packed_ready.record(stream)
             side.wait_event(packed_ready)
@@ -357,7 +365,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "deit_b_linear_stack_batch256: 48 linears, T=50432, layer-wise N:M seed 0 from "
                                "{1:4,2:4,1:8,2:8,4:8,1:16,4:16}; step = select + pack 48 weights (one launch) + 48 sparse products, bf16 out",
-                   "tokens": T, "layers": len(layers), "product_streams": args.streams},
+                   "tokens": T, "layers": len(layers), "product_schedule": args.schedule},
         "pct_of_bf16_dense_peak": 100.0 * useful / dt / 1e12 / PEAK_BF16_DENSE_TFLOPS,
         "dense_equivalent_tflops": dense / dt / 1e12,
         "pack_ms": pack_ms,

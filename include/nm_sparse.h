@@ -231,6 +231,33 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * nm_linear_forward_prepared_batched -- nm_linear_forward_prepared for every descriptor, in as few launches as
+ * the shapes allow: large layers of the same operand form (N <= 2, or N > 2) share one launch of the persistent
+ * product kernel, whose blocks walk the tiles of all of them as one list.  For the independent products of a
+ * stack of layers (each with its own input; Section 3: one level per layer) this removes the partial last round
+ * of tiles every single launch ends with.  Results are bit-identical to the single calls.
+ *   descs  HOST array of `count` descriptors, read before the call returns.  Fields as the arguments of
+ *          nm_linear_forward_prepared; the outputs must not overlap each other or any input.
+ * Errors as for nm_linear_forward_prepared (the first offending descriptor decides); nothing is launched on an
+ * argument error or a short workspace.
+ */
+typedef struct nm_forward_desc {
+  const nm_bf16* values;    /* device, packed layer (values, indices) at level N:M */
+  const uint32_t* indices;
+  int64_t O, K;
+  int32_t N, M;
+  const nm_bf16* X;         /* device, [T, K], ld ldx */
+  int64_t T, ldx;
+  const float* bias;        /* device, [O] or NULL */
+  void* Y;                  /* device, out, [T, O], ld ldy */
+  int64_t ldy;
+  int32_t out_dtype, reserved;
+  void* workspace;          /* filled by nm_spmm_prepare / nm_pack_prepare_batched for this layer and T */
+  size_t workspace_bytes;
+} nm_forward_desc;
+int32_t nm_linear_forward_prepared_batched(const nm_forward_desc* descs, int32_t count, void* stream);
+
+/*
  * Training products of one sparse layer (Section 3.2: in every step the gradient of the loss is taken with
  * respect to the sparse weights of the chosen configuration; Section 3.1, the weight-update figure: the sparse
  * matrix of the applied level is trained inside the shared weight).  With Y = X * (W (.) m)^T and the mask m of

@@ -24,7 +24,7 @@ EXPORTS = (
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
     "nm_backward_input_workspace_bytes", "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
-    "nm_prune_scored", "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
+    "nm_linear_forward_prepared_batched", "nm_prune_scored", "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
 )
 
 
@@ -43,6 +43,13 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("W", c_void_p), ("values", c_void_p), ("indices", c_void_p),
                 ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32),
                 ("T", c_int64), ("workspace", c_void_p), ("workspace_bytes", c_size_t)]
+
+
+class ForwardDesc(ctypes.Structure):
+    _fields_ = [("values", c_void_p), ("indices", c_void_p), ("O", c_int64), ("K", c_int64), ("N", c_int32),
+                ("M", c_int32), ("X", c_void_p), ("T", c_int64), ("ldx", c_int64), ("bias", c_void_p), ("Y", c_void_p),
+                ("ldy", c_int64), ("out_dtype", c_int32), ("reserved", c_int32), ("workspace", c_void_p),
+                ("workspace_bytes", c_size_t)]
 
 
 class RankDesc(ctypes.Structure):
@@ -126,6 +133,8 @@ def load_library() -> ctypes.CDLL:
     lib.nm_linear_backward_weight.restype = c_int32
     lib.nm_linear_backward_weight.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p,
                                               c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_linear_forward_prepared_batched.restype = c_int32
+    lib.nm_linear_forward_prepared_batched.argtypes = [ctypes.POINTER(ForwardDesc), c_int32, c_void_p]
     lib.nm_prune_scored.restype = c_int32
     lib.nm_prune_scored.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
     lib.nm_i8_workspace_bytes.restype = c_size_t
@@ -572,6 +581,46 @@ def nm_linear_backward_weight(dY, X, mask=None, out_dtype=None, out=None, worksp
     _check(load_library().nm_linear_backward_weight(dY.data_ptr(), T, O, ldy, X.data_ptr(), K, ldx, mask_ptr,
                                                     out.data_ptr(), lddw, code, ws_ptr, ws_bytes, _stream_handle(stream)))
     return out
+
+
+def forward_descs(layers):
+    """The descriptor array of nm_linear_forward_prepared_batched for a list of
+    (values, indices, K, N, M, X, workspace, bias or None, out); build it once when the buffers stay put."""
+    torch = _torch()
+    descs = (ForwardDesc * len(layers))()
+    for n, (values, indices, K, N, M, X, workspace, bias, out) in enumerate(layers):
+        _need(values, torch.bfloat16, "values")
+        _need(indices, torch.int32, "indices")
+        _need(X, torch.bfloat16, "X")
+        if not values.is_contiguous() or not indices.is_contiguous():
+            raise ValueError("packed tensors must be contiguous")
+        O = int(values.shape[0])
+        T, KX, ldx = _rows(X, "X")
+        if KX != K:
+            raise ValueError("X must be [T, K]")
+        if out.dtype not in (torch.float32, torch.bfloat16):
+            raise ValueError("out dtype must be float32 or bfloat16")
+        TY, OY, ldy = _rows(out, "out")
+        if (TY, OY) != (T, O):
+            raise ValueError("out must be [T, O]")
+        bias_ptr = None
+        if bias is not None:
+            _need(bias, torch.float32, "bias")
+            if bias.numel() != O or not bias.is_contiguous():
+                raise ValueError("bias must be contiguous [O]")
+            bias_ptr = bias.data_ptr()
+        descs[n] = ForwardDesc(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx, bias_ptr,
+                               out.data_ptr(), ldy, NM_OUT_F32 if out.dtype == torch.float32 else NM_OUT_BF16, 0,
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() * workspace.element_size() if workspace is not None else 0)
+    return descs
+
+
+def nm_linear_forward_prepared_batched(layers, stream=None):
+    """The products of many prepared layers in as few launches as their shapes allow; `layers` is a list of
+    (values, indices, K, N, M, X, workspace, bias or None, out) or an array made by forward_descs."""
+    descs = layers if isinstance(layers, ctypes.Array) else forward_descs(layers)
+    _check(load_library().nm_linear_forward_prepared_batched(descs, len(descs), _stream_handle(stream)))
 
 
 def nm_i8_workspace_bytes(O: int, K: int, N: int, M: int) -> int:

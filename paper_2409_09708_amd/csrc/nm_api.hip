@@ -180,10 +180,10 @@ int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int
 
 namespace {
 
-int32_t spmm_entry(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+// validation shared by the product calls; fills the launch arguments
+int32_t spmm_check(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
                    const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
-                   void* workspace, size_t workspace_bytes, void* stream, int phases) {
-  const bool product = phases & nm::SPMM_PRODUCT;
+                   void* workspace, size_t workspace_bytes, bool product, nm::SpmmArgs* a) {
   if (!values || !indices || (product && (!X || !Y))) return NM_ERR_NULL;
   if (int32_t s = check_weight(O, K, N, M)) return s;
   if (T <= 0 || T > (int64_t)1 << 31) return NM_ERR_SHAPE;
@@ -192,11 +192,20 @@ int32_t spmm_entry(const nm_bf16* values, const uint32_t* indices, int64_t O, in
   if (!aligned(values, 2) || !aligned(indices, 4) || !aligned(X, 2) || !aligned(bias, 4) ||
       !aligned(Y, out_dtype == NM_OUT_F32 ? 4 : 2))
     return NM_ERR_ALIGN;
+  a->values = values; a->indices = indices; a->O = O; a->K = K; a->N = N; a->M = M;
+  a->X = X; a->T = T; a->ldx = product ? ldx : K; a->bias = bias; a->Y = Y; a->ldy = ldy;
+  a->out_bf16 = (out_dtype == NM_OUT_BF16);
+  a->workspace = workspace; a->workspace_bytes = workspace_bytes;
+  return NM_OK;
+}
+
+int32_t spmm_entry(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                   const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                   void* workspace, size_t workspace_bytes, void* stream, int phases) {
   nm::SpmmArgs a;
-  a.values = values; a.indices = indices; a.O = O; a.K = K; a.N = N; a.M = M;
-  a.X = X; a.T = T; a.ldx = product ? ldx : K; a.bias = bias; a.Y = Y; a.ldy = ldy;
-  a.out_bf16 = (out_dtype == NM_OUT_BF16);
-  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  if (int32_t st = spmm_check(values, indices, O, K, N, M, X, T, ldx, bias, Y, ldy, out_dtype, workspace, workspace_bytes,
+                              phases & nm::SPMM_PRODUCT, &a))
+    return st;
   bool workspace_short = false;
   hipError_t e = nm::launch_spmm(a, (hipStream_t)stream, &workspace_short, phases);
   if (workspace_short) return NM_ERR_WORKSPACE;
@@ -334,6 +343,28 @@ int32_t nm_prune_scored(const float* score, int64_t O, int64_t K, int64_t lds, i
   if (lds < K) return NM_ERR_SHAPE;
   if (!aligned(score, 4) || !aligned(mask, 4)) return NM_ERR_ALIGN;
   return device_status(nm::launch_score_mask(score, O, K, lds, N, M, mask, (hipStream_t)stream));
+}
+
+int32_t nm_linear_forward_prepared_batched(const nm_forward_desc* descs, int32_t count, void* stream) {
+  if (!descs) return NM_ERR_NULL;
+  if (count <= 0) return NM_ERR_SHAPE;
+  constexpr int kChunk = 64;  // descriptors converted at a time (no allocation)
+  nm::SpmmArgs layers[kChunk];
+  auto convert = [&](int32_t i, nm::SpmmArgs* a) {
+    const nm_forward_desc& d = descs[i];
+    return spmm_check(d.values, d.indices, d.O, d.K, d.N, d.M, d.X, d.T, d.ldx, d.bias, d.Y, d.ldy, d.out_dtype,
+                      d.workspace, d.workspace_bytes, true, a);
+  };
+  for (int32_t i = 0; i < count; ++i) {  // every argument error is reported before anything is launched
+    if (int32_t st = convert(i, &layers[0])) return st;
+    if (nm::spmm_workspace_short(layers[0])) return NM_ERR_WORKSPACE;
+  }
+  for (int32_t first = 0; first < count; first += kChunk) {
+    const int n = count - first < kChunk ? count - first : kChunk;
+    for (int i = 0; i < n; ++i) convert(first + i, &layers[i]);
+    if (int32_t st = device_status(nm::launch_spmm_batched(layers, n, (hipStream_t)stream))) return st;
+  }
+  return NM_OK;
 }
 
 }  // extern "C"

@@ -76,6 +76,10 @@ bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* spar
 // missing, misaligned or too small (nothing is launched then)
 enum { SPMM_PREPARE = 1, SPMM_PRODUCT = 2 };
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases);
+// the products (SPMM_PRODUCT) of many prepared layers, sharing launches where the shapes allow
+// (the caller has checked the workspaces with spmm_workspace_short)
+bool spmm_workspace_short(const SpmmArgs& a);
+hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s);
 
 // Out[t, i] = sum_r Q[t, r] * Ws[r, i] on the persistent dense product kernel (weight transposed into stream
 // order in the workspace first); *taken stays false, and nothing is launched, when the shape, the alignment or

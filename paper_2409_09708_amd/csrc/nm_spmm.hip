@@ -570,7 +570,8 @@ struct StreamLayer {
   void* Y;
   int32_t O, T, nk, ldx, ldy;  // nk: K steps of the form (K / 64 or K / 32)
   int32_t n_o_tiles;
-  int32_t tile_begin, tile_end;  // this layer's range in the launch's tile list
+  int32_t n_tiles;               // tiles of this layer
+  int32_t reserved0;
   int32_t out_bf16;
   int32_t reserved;
 };
@@ -589,18 +590,23 @@ nm_stream_kernel(const StreamGroup g) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-  // ---- this block's tiles: every XCD (block id mod 8) owns a contiguous range of tiles, out-feature
-  // tiles fastest, and its blocks take them round-robin, so that the blocks sharing an L2 work on
-  // neighbouring tiles (same X rows) at the same time
-  const int n_tiles = g.n_tiles;
-  const int per_xcd = (n_tiles + 7) >> 3;
+  // ---- this block's tiles: every XCD (block id mod 8) owns a contiguous eighth of the tiles of EVERY layer,
+  // out-feature tiles fastest; its list is those ranges layer after layer, and its blocks take the entries
+  // round-robin.  So the blocks sharing an L2 work on neighbouring tiles (same X rows) at the same time, and
+  // every XCD gets the same share of each layer's work, whatever the layers' K.
+  const int xcd = (int)(blockIdx.x & 7);
   const int slots = (int)(gridDim.x >> 3);
-  const int xcd_first = (int)(blockIdx.x & 7) * per_xcd;
-  int xcd_end = xcd_first + per_xcd;
-  if (xcd_end > n_tiles) xcd_end = n_tiles;
-  const int first = xcd_first + (int)(blockIdx.x >> 3);
-  if (first >= xcd_end) return;
-  const int my_tiles = (xcd_end - first + slots - 1) / slots;
+  auto xcd_share = [&](int layer) {  // how many tiles of the layer this XCD owns
+    const int n = g.layer[layer].n_tiles;
+    const int per = (n + 7) >> 3;
+    const int left = n - xcd * per;
+    return left < 0 ? 0 : (left < per ? left : per);
+  };
+  int entries = 0;
+  for (int l = 0; l < g.count; ++l) entries += xcd_share(l);
+  const int first = (int)(blockIdx.x >> 3);
+  if (first >= entries) return;
+  const int my_tiles = (entries - first + slots - 1) / slots;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -641,20 +647,26 @@ nm_stream_kernel(const StreamGroup g) {
 
   // ---- the block's n-th tile: its layer (tiles come in ascending order, so the search resumes where it
   // stopped), out-feature tile and token rows.  A ragged last token tile is shifted back inside X.
-  auto tile_place = [&](int n, int& layer, int& o_tile, int64_t& t_lo, int64_t& t0) {
-    const int tile = first + n * slots;
-    while (tile >= g.layer[layer].tile_end) ++layer;
-    const int local = tile - g.layer[layer].tile_begin;
-    const int n_o = g.layer[layer].n_o_tiles;
+  struct ListPos { int layer, begin; };  // a layer and the XCD-list entry its range starts at
+  auto tile_place = [&](int n, ListPos& at, int& o_tile, int64_t& t_lo, int64_t& t0) {
+    const int entry = first + n * slots;
+    int share = xcd_share(at.layer);
+    while (entry >= at.begin + share) {
+      at.begin += share;
+      share = xcd_share(++at.layer);
+    }
+    const int local = xcd * ((g.layer[at.layer].n_tiles + 7) >> 3) + (entry - at.begin);
+    const int n_o = g.layer[at.layer].n_o_tiles;
     o_tile = local % n_o;
     t_lo = (int64_t)(local / n_o) * C::BT;
-    const int64_t T = g.layer[layer].T;
+    const int64_t T = g.layer[at.layer].T;
     t0 = t_lo + C::BT <= T ? t_lo : T - C::BT;
   };
 
   // ---- load cursor = the stage to be issued next (tile number in this block, k step) as running pointers: X
   // rows of the tile at the step's k, W and selector blocks of the step
-  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_layer = 0, ld_offsets_of = -1;
+  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_offsets_of = -1;
+  ListPos ld_at{0, 0};
   uint32_t ld_bias_voff = 0;
   const float* ld_bias = nullptr;
   const unsigned char* ld_x = nullptr;
@@ -663,7 +675,8 @@ nm_stream_kernel(const StreamGroup g) {
   auto cursor_tile = [&](int n) {
     int o_tile;
     int64_t t_lo, t0;
-    tile_place(n, ld_layer, o_tile, t_lo, t0);
+    tile_place(n, ld_at, o_tile, t_lo, t0);
+    const int ld_layer = ld_at.layer;
     const StreamLayer& L = g.layer[ld_layer];
     ld_nk = L.nk;
     if (ld_offsets_of != ld_layer) {
@@ -827,12 +840,12 @@ nm_stream_kernel(const StreamGroup g) {
     cur_off = nxt_off;
   };
 
-  int cp_layer = 0;
+  ListPos cp_at{0, 0};
   for (int n = 0; n < my_tiles; ++n) {
     int o_tile;
     int64_t t_lo, t0;
-    tile_place(n, cp_layer, o_tile, t_lo, t0);
-    const StreamLayer& L = g.layer[cp_layer];
+    tile_place(n, cp_at, o_tile, t_lo, t0);
+    const StreamLayer& L = g.layer[cp_at.layer];
     const int nk = L.nk;
     const int64_t o0 = (int64_t)o_tile * C::BO;
 #pragma unroll
@@ -1023,7 +1036,7 @@ static bool group_append(StreamGroup& grp, const GemmArgs& g) {
   L.O = (int32_t)g.O; L.T = (int32_t)g.T; L.nk = (int32_t)(g.K / C::KSTEP);
   L.ldx = (int32_t)g.ldx; L.ldy = (int32_t)g.ldy;
   L.n_o_tiles = (int32_t)n_o;
-  L.tile_begin = grp.n_tiles; L.tile_end = (int32_t)end;
+  L.n_tiles = (int32_t)(n_o * n_t); L.reserved0 = 0;
   L.out_bf16 = g.out_bf16; L.reserved = 0;
   grp.n_tiles = (int32_t)end;
   return true;
@@ -1189,6 +1202,65 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
     g.A = wd;
   }
   return product ? dispatch_gemm<false>(g, pick, s) : hipSuccess;
+}
+
+// The product of a prepared layer on the persistent kernel, as a table entry: false when this layer takes
+// another path (too few tiles, a shape or alignment the kernel does not handle).
+static bool stream_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form) {
+  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T) || pick_tile(a.O, a.T) != 0) return false;
+  const int per_piece = a.out_bf16 ? 8 : 4;
+  const bool vec = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
+                   (a.bias == nullptr || aligned_to(a.bias, 16));
+  if (!vec || a.ldy > 0x7FFFFFFF) return false;
+  *sparse_form = a.N <= 2 && a.N < a.M;
+  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
+  const int64_t o_pad = ((a.O + 255) / 256) * 256;
+  g->A = reinterpret_cast<const bf16_t*>(ws);
+  g->sel = *sparse_form ? reinterpret_cast<const uint32_t*>(ws + (size_t)o_pad * (size_t)a.K) : nullptr;
+  g->X = a.X; g->bias = a.bias; g->Y = a.Y;
+  g->O = a.O; g->K = a.K; g->T = a.T; g->ldx = a.ldx; g->ldy = a.ldy;
+  g->n_o_tiles = g->n_t_tiles = 0;
+  g->out_bf16 = a.out_bf16; g->vec_store = 1;
+  return true;
+}
+
+// Products of many prepared layers: those the persistent kernel takes share launches (one table per operand
+// form, flushed when full), the others are launched one by one.  Results are those of the single calls.
+bool spmm_workspace_short(const SpmmArgs& a) {
+  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;  // the gather kernel needs none
+  const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
+  return need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256));
+}
+
+hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s) {
+  StreamGroup sparse_grp, dense_grp;
+  sparse_grp.count = dense_grp.count = 0;
+  sparse_grp.n_tiles = dense_grp.n_tiles = 0;
+  hipError_t e = hipSuccess;
+  auto flush = [&](StreamGroup& grp, bool sparse) {
+    if (grp.count == 0) return hipSuccess;
+    const hipError_t r = sparse ? launch_stream_group<true>(grp, s) : launch_stream_group<false>(grp, s);
+    grp.count = 0; grp.n_tiles = 0;
+    return r;
+  };
+  for (int i = 0; i < count; ++i) {
+    GemmArgs g;
+    bool sparse_form = false;
+    if (stream_entry(layers[i], &g, &sparse_form)) {
+      StreamGroup& grp = sparse_form ? sparse_grp : dense_grp;
+      bool ok = sparse_form ? group_append<true>(grp, g) : group_append<false>(grp, g);
+      if (!ok) {
+        if ((e = flush(grp, sparse_form)) != hipSuccess) return e;
+        ok = sparse_form ? group_append<true>(grp, g) : group_append<false>(grp, g);
+        if (!ok) return hipErrorInvalidValue;
+      }
+    } else {
+      bool short_ws = false;
+      if ((e = launch_spmm(layers[i], s, &short_ws, SPMM_PRODUCT)) != hipSuccess) return e;
+    }
+  }
+  if ((e = flush(sparse_grp, true)) != hipSuccess) return e;
+  return flush(dense_grp, false);
 }
 
 }  // namespace nm

@@ -154,3 +154,41 @@ def test_persistent_kernel_short_and_odd_reductions(K, level, out_dtype):
     Yref, B = orc.nm_linear_from_bits(X[rows], W, *level, bias=bias)
     check_output(host_output(Y[torch.from_numpy(rows).cuda()]), Yref, B + np.abs(bias)[None, :],
                  K // level[1] * level[0] + 1, out_dtype == torch.float32, f"K={K} {level}")
+
+
+def test_batched_products_equal_the_single_calls():
+    # the stack's launch configuration: all products of a block in one call.  Layers of both operand forms, with
+    # different K (12 and 48 steps, and 24 / 96 for the dense form), a ragged out-feature tile, a bias, fp32 and
+    # bf16 outputs; plus a layer too small for the persistent kernel and one the general kernel takes.  The
+    # batched call must write the bytes the single calls write.
+    rng = np.random.default_rng(4242)
+    T = 256 * 197
+    specs = [(768, 768, 2, 4, torch.bfloat16, False), (768, 3000, 1, 8, torch.bfloat16, True),
+             (3072, 768, 2, 8, torch.float32, False), (768, 2304, 4, 8, torch.bfloat16, False),
+             (3072, 768, 4, 16, torch.bfloat16, True), (768, 768, 1, 16, torch.bfloat16, False)]
+    entries, singles = [], []
+    for (K, O, N, M, dt, with_bias) in specs:
+        X = dev_bf16(wl.draw_activations(rng, T, K))
+        v, i = nm.nm_pack(dev_bf16(wl.draw_weights(rng, O, K)), N, M)
+        ws = nm.nm_spmm_prepare(v, i, K, N, M, T)
+        bias = torch.from_numpy(rng.standard_normal(O).astype(np.float32)).cuda() if with_bias else None
+        singles.append(nm.nm_linear_forward_prepared(v, i, K, N, M, X, ws, bias=bias, out_dtype=dt))
+        entries.append((v, i, K, N, M, X, ws, bias, torch.zeros((T, O), dtype=dt, device="cuda")))
+    # a few tokens only (tiled kernel) and K not a multiple of 64 (general kernel)
+    for (Ts, K, O, N, M) in [(197, 768, 768, 2, 4), (64, 48, 40, 1, 8)]:
+        X = dev_bf16(wl.draw_activations(rng, Ts, K))
+        v, i = nm.nm_pack(dev_bf16(wl.draw_weights(rng, O, K)), N, M)
+        ws = nm.nm_spmm_prepare(v, i, K, N, M, Ts)
+        singles.append(nm.nm_linear_forward_prepared(v, i, K, N, M, X, ws))
+        entries.append((v, i, K, N, M, X, ws, None, torch.zeros((Ts, O), dtype=torch.float32, device="cuda")))
+    nm.nm_linear_forward_prepared_batched(entries)
+    torch.cuda.synchronize()
+    for e, ref in zip(entries, singles):
+        assert torch.equal(e[-1], ref)
+    # and again through a prebuilt descriptor array (what a serving loop keeps)
+    for e in entries:
+        e[-1].zero_()
+    descs = nm.forward_descs(entries)
+    nm.nm_linear_forward_prepared_batched(descs)
+    for e, ref in zip(entries, singles):
+        assert torch.equal(e[-1], ref)

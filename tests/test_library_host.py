@@ -304,3 +304,26 @@ def test_prune_scored_argument_errors(lib):
     assert f(FAKE, 4, 18, 18, 2, 4, FAKE, None) == 2 and f(FAKE, 0, 16, 16, 2, 4, FAKE, None) == 2
     assert f(FAKE, 4, 16, 12, 2, 4, FAKE, None) == 2
     assert f(FAKE + 2, 4, 16, 16, 2, 4, FAKE, None) == 4 and f(FAKE, 4, 16, 16, 2, 4, FAKE + 2, None) == 4
+
+
+def test_forward_batched_argument_errors(lib):
+    D = binding.ForwardDesc
+    ok = dict(values=FAKE, indices=FAKE, O=64, K=64, N=2, M=4, X=FAKE, T=16, ldx=64, bias=None, Y=FAKE, ldy=64,
+              out_dtype=0, reserved=0, workspace=None, workspace_bytes=0)
+
+    def run(*overrides):
+        d = (D * len(overrides))()
+        for n, kw in enumerate(overrides):
+            d[n] = D(**dict(ok, **kw))
+        return lib.nm_linear_forward_prepared_batched(d, len(overrides), None)
+
+    assert lib.nm_linear_forward_prepared_batched(None, 1, None) == 1
+    d = (D * 1)()
+    d[0] = D(**ok)
+    assert lib.nm_linear_forward_prepared_batched(d, 0, None) == 2
+    # the first offending descriptor decides, whatever follows it
+    assert run({}, dict(values=None)) == 1 and run({}, dict(X=None)) == 1 and run({}, dict(Y=None)) == 1
+    assert run({}, dict(N=3, M=2)) == 3 and run({}, dict(K=66)) == 2 and run({}, dict(ldy=8)) == 2
+    assert run({}, dict(out_dtype=2)) == 5 and run({}, dict(Y=FAKE + 2)) == 4
+    assert run({}, dict(N=1, M=8)) == 6  # a level that needs a prepared workspace
+    assert run({}, dict(N=1, M=8, workspace=FAKE, workspace_bytes=16)) == 6
