@@ -286,62 +286,16 @@ nm_tgemm_kernel(const TGemmArgs a) {
   // transposes 16 output rows at a time through its own LDS slice, so that the global stores are 16 bytes
   // per lane and whole row segments of the wave tile are written contiguously.
   __builtin_amdgcn_s_barrier();  // every wave is done with the operand stages
+  auto get = [&](int i, int j) { return __builtin_bit_cast(u32x4_t, acc[i][j]); };
+  const int64_t row0 = j0 + wj * JT * 16, col0 = i0 + wi * IT * 16;
+  static_assert(C::NW * wave_tile_slice_bytes<IT, 4>() <= C::LDS_BYTES, "write-out slices");
   if (a.vec_store) {
-    constexpr int IW = IT * 16;
-    auto transpose_store = [&](auto out_tag) {
-      using out_t = decltype(out_tag);
-      constexpr int ES = (int)sizeof(out_t);
-      constexpr int RSB = IW * ES + 16;  // padded LDS row
-      constexpr int CPR = IW * ES / 16;  // 16-byte pieces per row
-      constexpr int PASSES = 16 * CPR / 64;
-      static_assert(16 * CPR % 64 == 0 && C::NW * 16 * RSB <= C::LDS_BYTES, "write-out slice");
-      unsigned char* slice = smem + wave * (16 * RSB);
-#pragma unroll
-      for (int j = 0; j < JT; ++j) {
-#pragma unroll
-        for (int i = 0; i < IT; ++i) {
-          const f32x4_t v = acc[i][j];
-          unsigned char* dst = slice + c16 * RSB + (i * 16 + kb * 4) * ES;
-          if constexpr (ES == 2) {
-            uint2 pk;
-            pk.x = pack_bf16x2(v[0], v[1]);
-            pk.y = pack_bf16x2(v[2], v[3]);
-            *reinterpret_cast<uint2*>(dst) = pk;
-          } else {
-            *reinterpret_cast<f32x4_t*>(dst) = v;
-          }
-        }
-#pragma unroll
-        for (int pss = 0; pss < PASSES; ++pss) {
-          const int q = pss * 64 + lane;
-          const int row = q / CPR, ch = q % CPR;
-          const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(slice + row * RSB + ch * 16);
-          const int64_t jj = j0 + (wj * JT + j) * 16 + row;
-          const int64_t ii = i0 + wi * IW + ch * (16 / ES);
-          if (jj < a.J && ii < a.I)
-            *reinterpret_cast<u32x4_t*>(reinterpret_cast<out_t*>(a.out) + jj * a.ldo + ii) = piece;
-        }
-      }
-    };
-    if (a.out_bf16) transpose_store(bf16_t{});
-    else transpose_store(float{});
+    if (a.out_bf16)
+      write_wave_tile_pieces<IT, JT, 2>(smem + wave * wave_tile_slice_bytes<IT, 2>(), lane, get, a.out, a.ldo, row0, col0, a.J, a.I);
+    else
+      write_wave_tile_pieces<IT, JT, 4>(smem + wave * wave_tile_slice_bytes<IT, 4>(), lane, get, a.out, a.ldo, row0, col0, a.J, a.I);
   } else {
-#pragma unroll
-    for (int j = 0; j < JT; ++j) {
-      const int64_t jj = j0 + (wj * JT + j) * 16 + c16;
-      if (jj >= a.J) continue;
-#pragma unroll
-      for (int i = 0; i < IT; ++i) {
-        const int64_t ii = i0 + (wi * IT + i) * 16 + kb * 4;
-        const f32x4_t v = acc[i][j];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (ii + e >= a.I) break;
-          if (a.out_bf16) reinterpret_cast<bf16_t*>(a.out)[jj * a.ldo + ii + e] = (bf16_t)f32_to_bf16_rne(v[e]);
-          else reinterpret_cast<float*>(a.out)[jj * a.ldo + ii + e] = v[e];
-        }
-      }
-    }
+    write_wave_tile_elements<IT, JT>(lane, get, a.out, a.ldo, row0, col0, a.J, a.I, a.out_bf16 != 0);
   }
 }
 

@@ -320,63 +320,16 @@ nm_i8_gemm_kernel(const I8Args a) {
       for (int e = 0; e < 4; ++e) acc[i][j][e] = (int)__float_as_uint(fmaf((float)acc[i][j][e], sc[e], bi[e]));
   }
   __builtin_amdgcn_s_barrier();  // every wave is done with the operand stages
+  auto get = [&](int i, int j) { return __builtin_bit_cast(u32x4_t, acc[i][j]); };
+  const int64_t row0 = t0 + wt * TT * 16, col0 = o0 + wo * OT * 16;
+  static_assert(C::NW * wave_tile_slice_bytes<OT, 4>() <= C::LDS_BYTES, "write-out slices");
   if (a.vec_store) {
-    constexpr int OW = OT * 16;
-    auto transpose_store = [&](auto es_tag) {
-      constexpr int ES = decltype(es_tag)::value;  // bytes per output element
-      constexpr int RS = OW * ES + 16;              // padded LDS row
-      constexpr int CPR = OW * ES / 16;             // 16-byte pieces per row
-      constexpr int PASSES = (16 * CPR + 63) / 64;
-      static_assert(C::NW * 16 * RS <= C::LDS_BYTES, "write-out slice");
-      unsigned char* slice = smem + wave * (16 * RS);
-#pragma unroll
-      for (int j = 0; j < TT; ++j) {
-#pragma unroll
-        for (int i = 0; i < OT; ++i) {
-          const u32x4_t v = __builtin_bit_cast(u32x4_t, acc[i][j]);
-          unsigned char* dst = slice + r16 * RS + (i * 16 + kb * 4) * ES;
-          if constexpr (ES == 2) {
-            uint2 pk;
-            pk.x = pack_bf16x2(__uint_as_float(v[0]), __uint_as_float(v[1]));
-            pk.y = pack_bf16x2(__uint_as_float(v[2]), __uint_as_float(v[3]));
-            *reinterpret_cast<uint2*>(dst) = pk;
-          } else {
-            *reinterpret_cast<u32x4_t*>(dst) = v;
-          }
-        }
-#pragma unroll
-        for (int pss = 0; pss < PASSES; ++pss) {
-          const int q = pss * 64 + lane;
-          const int row = q / CPR, ch = q % CPR;
-          if (row < 16) {
-            const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(slice + row * RS + ch * 16);
-            const int64_t t = t0 + (wt * TT + j) * 16 + row;
-            const int64_t o = o0 + wo * OW + ch * (16 / ES);
-            if (t < a.T && o < a.O)
-              *reinterpret_cast<u32x4_t*>(reinterpret_cast<unsigned char*>(a.Y) + (t * a.ldy + o) * ES) = piece;
-          }
-        }
-      }
-    };
-    if (a.out_kind == 1) transpose_store(std::integral_constant<int, 2>{});
-    else transpose_store(std::integral_constant<int, 4>{});
+    if (a.out_kind == 1)
+      write_wave_tile_pieces<OT, TT, 2>(smem + wave * wave_tile_slice_bytes<OT, 2>(), lane, get, a.Y, a.ldy, row0, col0, a.T, a.O);
+    else
+      write_wave_tile_pieces<OT, TT, 4>(smem + wave * wave_tile_slice_bytes<OT, 4>(), lane, get, a.Y, a.ldy, row0, col0, a.T, a.O);
   } else {
-#pragma unroll
-    for (int j = 0; j < TT; ++j) {
-      const int64_t t = t0 + (wt * TT + j) * 16 + r16;
-      if (t >= a.T) continue;
-#pragma unroll
-      for (int i = 0; i < OT; ++i) {
-        const int64_t o = o0 + (wo * OT + i) * 16 + kb * 4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (o + e >= a.O) break;
-          const uint32_t v = (uint32_t)acc[i][j][e];
-          if (a.out_kind == 1) reinterpret_cast<bf16_t*>(a.Y)[t * a.ldy + o + e] = (bf16_t)f32_to_bf16_rne(__uint_as_float(v));
-          else reinterpret_cast<uint32_t*>(a.Y)[t * a.ldy + o + e] = v;
-        }
-      }
-    }
+    write_wave_tile_elements<OT, TT>(lane, get, a.Y, a.ldy, row0, col0, a.T, a.O, a.out_kind == 1);
   }
 }
 

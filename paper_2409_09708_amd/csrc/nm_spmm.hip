@@ -448,63 +448,16 @@ nm_gemm_kernel(const GemmArgs a) {
   // wave transposes 16 tokens at a time through its own LDS slice so that the global stores are
   // 16 bytes per lane and whole row segments of the wave tile (OW elements) are written contiguously.
   __builtin_amdgcn_s_barrier();  // every wave is done with the operand stages
+  auto get = [&](int i, int j) { return __builtin_bit_cast(u32x4_t, acc[i][j]); };
+  const int64_t row0 = t0 + wt * TT * 16, col0 = o0 + wo * OT * 16;
+  static_assert(C::NW * wave_tile_slice_bytes<OT, 4>() <= C::LDS_BYTES, "write-out slices");
   if (a.vec_store) {
-    constexpr int OW = OT * 16;
-    auto transpose_store = [&](auto out_tag) {
-      using out_t = decltype(out_tag);
-      constexpr int ES = (int)sizeof(out_t);
-      constexpr int RS = OW * ES + 16;        // padded LDS row: 16-byte slots of consecutive tokens differ in bank
-      constexpr int CPR = OW * ES / 16;       // 16-byte pieces per row
-      constexpr int PASSES = 16 * CPR / 64;
-      static_assert(16 * CPR % 64 == 0 && C::NW * 16 * RS <= C::LDS_BYTES, "epilogue slice");
-      unsigned char* slice = smem + wave * (16 * RS);
-#pragma unroll
-      for (int j = 0; j < TT; ++j) {
-#pragma unroll
-        for (int i = 0; i < OT; ++i) {
-          const f32x4_t v = acc[i][j];
-          unsigned char* dst = slice + r16 * RS + (i * 16 + kb * 4) * ES;
-          if constexpr (ES == 2) {
-            uint2 pk;
-            pk.x = pack_bf16x2(v[0], v[1]);
-            pk.y = pack_bf16x2(v[2], v[3]);
-            *reinterpret_cast<uint2*>(dst) = pk;
-          } else {
-            *reinterpret_cast<f32x4_t*>(dst) = v;
-          }
-        }
-#pragma unroll
-        for (int pss = 0; pss < PASSES; ++pss) {
-          const int q = pss * 64 + lane;
-          const int row = q / CPR, ch = q % CPR;
-          const u32x4_t piece = *reinterpret_cast<const u32x4_t*>(slice + row * RS + ch * 16);
-          const int64_t t = t0 + (wt * TT + j) * 16 + row;
-          const int64_t o = o0 + wo * OW + ch * (16 / ES);
-          if (t < a.T && o < a.O)
-            *reinterpret_cast<u32x4_t*>(reinterpret_cast<out_t*>(a.Y) + t * a.ldy + o) = piece;
-        }
-      }
-    };
-    if (a.out_bf16) transpose_store(bf16_t{});
-    else transpose_store(float{});
+    if (a.out_bf16)
+      write_wave_tile_pieces<OT, TT, 2>(smem + wave * wave_tile_slice_bytes<OT, 2>(), lane, get, a.Y, a.ldy, row0, col0, a.T, a.O);
+    else
+      write_wave_tile_pieces<OT, TT, 4>(smem + wave * wave_tile_slice_bytes<OT, 4>(), lane, get, a.Y, a.ldy, row0, col0, a.T, a.O);
   } else {
-#pragma unroll
-    for (int j = 0; j < TT; ++j) {
-      const int64_t t = t0 + (wt * TT + j) * 16 + r16;
-      if (t >= a.T) continue;
-#pragma unroll
-      for (int i = 0; i < OT; ++i) {
-        const int64_t o = o0 + (wo * OT + i) * 16 + kb * 4;
-        const f32x4_t v = acc[i][j];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (o + e >= a.O) break;
-          const float y = v[e];
-          if (a.out_bf16) reinterpret_cast<bf16_t*>(a.Y)[t * a.ldy + o + e] = (bf16_t)f32_to_bf16_rne(y);
-          else reinterpret_cast<float*>(a.Y)[t * a.ldy + o + e] = y;
-        }
-      }
-    }
+    write_wave_tile_elements<OT, TT>(lane, get, a.Y, a.ldy, row0, col0, a.T, a.O, a.out_bf16 != 0);
   }
 }
 
