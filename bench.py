@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_DENSE_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 PEAK_INT8_DENSE_TOPS = 5000.0    # MI355X dense int8 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
@@ -57,6 +58,15 @@ def algorithmic_bytes(L, out_bytes=2):
         w = L.O * L.K * 2                # dense operand form
     del b
     return 2.0 * L.T * L.K + w + out_bytes * L.T * L.O
+
+
+def ceiling_ms(L):
+    """Time below which one product cannot go on nominal peaks: the matrix-core roof (a level with N <= 2 runs
+    on the 2:4 sparse instruction at half the dense instruction count, the others on the dense one) or the HBM
+    roof of its algorithmic bytes, whichever is later."""
+    math = L.dense_flops * (0.5 if L.N <= 2 else 1.0) / (PEAK_BF16_DENSE_TFLOPS * 1e12)
+    hbm = algorithmic_bytes(L) / (PEAK_HBM_GBS * 1e9)
+    return max(math, hbm) * 1e3
 
 
 def measured_traffic():
@@ -339,10 +349,11 @@ def main():
             f"{int8['dense_equivalent_tops']:.0f} dense-equivalent)")
         log(f"nested levels: rank 48 matrices {rank_ms:.3f} ms ({nested['rank']['roofline']['achieved']:.0f} GB/s), "
             f"pack from ranks {pr_ms:.3f} ms ({nested['pack_ranked']['roofline']['achieved']:.0f} GB/s)")
-        log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}")
+        log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}{'% of ceiling':>14}")
         for L, ms in zip(layers, layer_ms):
             u = L.useful_flops / ms / 1e9
-            log(f"{L.name:<12}{L.N:>3}:{L.M:<3}{ms:>8.3f}{u:>13.1f}{L.dense_flops / ms / 1e9:>15.1f}{100 * u / PEAK_BF16_DENSE_TFLOPS:>12.1f}%")
+            log(f"{L.name:<12}{L.N:>3}:{L.M:<3}{ms:>8.3f}{u:>13.1f}{L.dense_flops / ms / 1e9:>15.1f}{100 * u / PEAK_BF16_DENSE_TFLOPS:>12.1f}%"
+                f"{100 * ceiling_ms(L) / ms:>13.1f}%")
         wbytes = sum(L.O * L.K * 2 for L in layers)
         obytes = sum(v.numel() * 2 + i.numel() * 4 for v, i in packed)
         sbytes = sum(nm.nm_spmm_workspace_bytes(L.O, L.K, L.N, L.M, L.T) for L in layers)
@@ -369,6 +380,8 @@ def main():
         "pct_of_bf16_dense_peak": 100.0 * useful / dt / 1e12 / PEAK_BF16_DENSE_TFLOPS,
         "dense_equivalent_tflops": dense / dt / 1e12,
         "pack_ms": pack_ms,
+        # the stack's time if every product ran at its own roof (nominal matrix-core or HBM peak), over the step
+        "fraction_of_ceiling": sum(ceiling_ms(L) for L in layers) / (dt * 1e3),
         "roofline": roofline,
         "nested_levels": nested,
         "training_products": training,
