@@ -70,13 +70,14 @@ struct TCfg {
 };
 
 // Transposing fragment read from a tile stored as [RS rows (reduction)][ROWB / 2 columns], the 16-byte pieces
-// of row r at slot (piece ^ 2 (r & 3)): the 16 lanes of a group touch four rows, and the swizzle puts their
-// 32-byte runs on different banks.  Lane (c16 = lane % 16, kb = lane / 16) receives the reduction indices
+// of row r at slot (piece ^ 2 (r & 3) ^ 8 ((r >> 3) & 1)): the 16 lanes of a group touch four rows, and the
+// first term puts their 32-byte runs on different banks; two groups are served together and their rows lie 8
+// apart, the second term sends them to different halves of the 64 banks.  Lane (c16 = lane % 16, kb = lane / 16) receives the reduction indices
 // 8 kb .. 8 kb + 7 of column 16 * block + c16.
 template <int ROWB>
 __device__ __forceinline__ u32x4_t read_transposed(const unsigned char* tile, int block, int c16, int kb) {
   const int sub = c16 >> 2;  // row inside the group of four; also (row & 3)
-  const int off = (8 * kb + sub) * ROWB + ((2 * (block ^ sub) + ((c16 & 3) >> 1)) << 4) + (c16 & 1) * 8;
+  const int off = (8 * kb + sub) * ROWB + (((2 * (block ^ sub) + ((c16 & 3) >> 1)) ^ (8 * (kb & 1))) << 4) + (c16 & 1) * 8;
   const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off));
   const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(tile + off + 4 * ROWB));
   typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
@@ -90,7 +91,7 @@ template <int ROWB>
 __device__ __forceinline__ void strided_load_place(int n, int lane, int* row, int* piece) {
   constexpr int PER_ROW = ROWB / 16, ROWS = 1024 / ROWB;
   *row = n * ROWS + lane / PER_ROW;
-  *piece = (lane % PER_ROW) ^ (2 * (*row & 3));
+  *piece = (lane % PER_ROW) ^ (2 * (*row & 3)) ^ (8 * ((*row >> 3) & 1));
 }
 
 template <bool Q_STRIDED>
@@ -173,24 +174,33 @@ nm_tgemm_kernel(const TGemmArgs a) {
   const bf16_t* q_base = Q_STRIDED ? a.Q + j0 : a.Q + j0 * a.ldq;
   const uint32_t ldp2 = (uint32_t)(a.ldp * 2), ldq2 = (uint32_t)(a.ldq * 2);
 
-  // the d-th load of the stage that starts at reduction index r into LDS buffer buf
-  auto issue_one = [&](auto d_tag, int64_t r, int buf) {
+  // A stage's sources: the (wave-uniform) operand addresses at its first reduction index and the rows it has
+  struct StageSrc { uniform_ptr_t p, q; int rows; };
+  auto stage_src = [&](int64_t r) {
+    StageSrc src;
+    src.p = make_uniform(p_base + r * a.ldp);
+    src.q = make_uniform(Q_STRIDED ? q_base + r * a.ldq : q_base + r);
+    src.rows = (int)((a.R - r) < C::RS ? (a.R - r) : C::RS);  // >= 1
+    return src;
+  };
+  // the d-th load of a stage into LDS buffer buf
+  auto issue_one = [&](auto d_tag, const StageSrc& src, int buf) {
     constexpr int d = decltype(d_tag)::value;
     const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
-    const int rows_left = (int)((a.R - r) < C::RS ? (a.R - r) : C::RS);  // >= 1
     if constexpr (d < C::P_PW) {
-      const int row = p_row[d] < rows_left ? p_row[d] : rows_left - 1;
-      dma16(make_uniform(p_base + r * a.ldp), (uint32_t)row * ldp2 + p_col[d], lds + p_dst[d]);
+      const int row = p_row[d] < src.rows ? p_row[d] : src.rows - 1;
+      dma16(src.p, (uint32_t)row * ldp2 + p_col[d], lds + p_dst[d]);
     } else if constexpr (Q_STRIDED) {
-      const int row = q_row[d - C::P_PW] < rows_left ? q_row[d - C::P_PW] : rows_left - 1;
-      dma16(make_uniform(q_base + r * a.ldq), (uint32_t)row * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+      const int row = q_row[d - C::P_PW] < src.rows ? q_row[d - C::P_PW] : src.rows - 1;
+      dma16(src.q, (uint32_t)row * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
     } else {
-      dma16(make_uniform(q_base + r), (uint32_t)q_row[d - C::P_PW] * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+      dma16(src.q, (uint32_t)q_row[d - C::P_PW] * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
     }
   };
   auto issue_stage = [&](int64_t r, int buf) {
+    const StageSrc src = stage_src(r);
     [&]<int... D>(std::integer_sequence<int, D...>) {
-      (issue_one(std::integral_constant<int, D>{}, r, buf), ...);
+      (issue_one(std::integral_constant<int, D>{}, src, buf), ...);
     }(std::make_integer_sequence<int, C::LPW>{});
   };
 
@@ -217,13 +227,14 @@ nm_tgemm_kernel(const TGemmArgs a) {
   };
   // 32 matrix instructions; the wave's loads of a later stage are issued between them
   auto multiply = [&](bool load, int64_t lr, int lbuf) {
+    const StageSrc src = stage_src(load ? lr : r_first);
     [&]<int... Q>(std::integer_sequence<int, Q...>) {
       ([&] {
         constexpr int j = Q / IT, i = Q % IT;
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pf[i]),
                                                             __builtin_bit_cast(bf16x8_t, qf[j]), acc[i][j], 0, 0, 0);
         if constexpr (Q % 4 == 3 && Q / 4 < C::LPW) {
-          if (load) issue_one(std::integral_constant<int, Q / 4>{}, lr, lbuf);
+          if (load) issue_one(std::integral_constant<int, Q / 4>{}, src, lbuf);
           __builtin_amdgcn_sched_barrier(0);
         }
       }(), ...);
