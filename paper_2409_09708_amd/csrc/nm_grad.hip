@@ -171,6 +171,12 @@ nm_tgemm_kernel(const TGemmArgs a) {
     q_dst[d] = (uint32_t)(C::P_BYTES + n * 1024);
   }
   const bf16_t* p_base = a.P + i0;
+  // lane byte offsets of the loads of a stage with all its rows (the common case; a ragged last stage clamps)
+  uint32_t p_voff[C::P_PW], q_voff[C::Q_PW];
+#pragma unroll
+  for (int d = 0; d < C::P_PW; ++d) p_voff[d] = (uint32_t)p_row[d] * (uint32_t)(a.ldp * 2) + p_col[d];
+#pragma unroll
+  for (int d = 0; d < C::Q_PW; ++d) q_voff[d] = (uint32_t)q_row[d] * (uint32_t)(a.ldq * 2) + q_col[d];
   const bf16_t* q_base = Q_STRIDED ? a.Q + j0 : a.Q + j0 * a.ldq;
   const uint32_t ldp2 = (uint32_t)(a.ldp * 2), ldq2 = (uint32_t)(a.ldq * 2);
 
@@ -187,14 +193,17 @@ nm_tgemm_kernel(const TGemmArgs a) {
   auto issue_one = [&](auto d_tag, const StageSrc& src, int buf) {
     constexpr int d = decltype(d_tag)::value;
     const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
+    const bool ragged = src.rows < C::RS;  // wave-uniform; only the last stage of the reduction
     if constexpr (d < C::P_PW) {
-      const int row = p_row[d] < src.rows ? p_row[d] : src.rows - 1;
-      dma16(src.p, (uint32_t)row * ldp2 + p_col[d], lds + p_dst[d]);
+      uint32_t voff = p_voff[d];
+      if (ragged && p_row[d] >= src.rows) voff = (uint32_t)(src.rows - 1) * ldp2 + p_col[d];
+      dma16(src.p, voff, lds + p_dst[d]);
     } else if constexpr (Q_STRIDED) {
-      const int row = q_row[d - C::P_PW] < src.rows ? q_row[d - C::P_PW] : src.rows - 1;
-      dma16(src.q, (uint32_t)row * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+      uint32_t voff = q_voff[d - C::P_PW];
+      if (ragged && q_row[d - C::P_PW] >= src.rows) voff = (uint32_t)(src.rows - 1) * ldq2 + q_col[d - C::P_PW];
+      dma16(src.q, voff, lds + q_dst[d - C::P_PW]);
     } else {
-      dma16(src.q, (uint32_t)q_row[d - C::P_PW] * ldq2 + q_col[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+      dma16(src.q, q_voff[d - C::P_PW], lds + q_dst[d - C::P_PW]);
     }
   };
   auto issue_stage = [&](int64_t r, int buf) {
