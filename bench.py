@@ -324,7 +324,8 @@ def main():
     q_x = [torch.randint(-127, 128, (layers[j].T, layers[j].K), device=dev, dtype=torch.int8, generator=gen)
            for j in train_layers]
     q_scale = [torch.full((layers[j].O,), 1e-4, dtype=torch.float32, device=dev) for j in train_layers]
-    q_ws = [nm.nm_i8_prepare(q_w[n], q_masks[n], layers[j].N, layers[j].M) for n, j in enumerate(train_layers)]
+    q_ws = [nm.nm_i8_prepare(q_w[n], q_masks[n], layers[j].N, layers[j].M, layers[j].T)
+            for n, j in enumerate(train_layers)]
 
     def int8_products():
         for n, j in enumerate(train_layers):

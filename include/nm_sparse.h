@@ -320,22 +320,23 @@ int32_t nm_prune_scored(const float* score, int64_t O, int64_t K, int64_t lds, i
  *   Xq       in   int8 [T, K], ld ldx
  *   x_scale, w_scale ([O], NULL = 1), bias ([O], NULL = 0)  fp32 rescaling, not used for NM_OUT_I32
  *   Y        out  [T, O], ld ldy: float, bfloat16 (round to nearest even) or int32
- *   workspace scratch of nm_i8_workspace_bytes(O, K, N, M) bytes, 256-byte aligned (NULL allowed when 0): the
+ *   workspace scratch of nm_i8_workspace_bytes(O, K, N, M, T) bytes, 256-byte aligned (NULL allowed when 0): the
  *             weight compressed to matrix-core operand order (values + 2-bit selectors at N <= 2, masked dense
- *             otherwise).
- * nm_linear_forward_i8 = nm_i8_prepare (weight only, once per weight) + nm_linear_forward_i8_prepared (the
- * product; the workspace is only read).  The matrix-core kernels need K % 128 == 0, 16-byte aligned Wq and Xq
+ *             otherwise), in the order of the kernel the token count T selects (large layers: the persistent
+ *             kernel's stream order, rows padded to whole 256-row tiles).
+ * nm_linear_forward_i8 = nm_i8_prepare (weight only, once per weight and token count) +
+ * nm_linear_forward_i8_prepared (the product; the workspace is only read).  The matrix-core kernels need K % 128 == 0, 16-byte aligned Wq and Xq
  * and ldw, ldx multiples of 16; other shapes run a general kernel on Wq and mask with the same results.
  * K * 127 * 128 must stay below 2^31 (K <= 132096) for the integer sum not to wrap.
  * Errors as for nm_linear_forward.
  */
-size_t nm_i8_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M);
+size_t nm_i8_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M, int64_t T);
 int32_t nm_linear_forward_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N,
                              int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
                              const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
                              void* workspace, size_t workspace_bytes, void* stream);
 int32_t nm_i8_prepare(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N,
-                      int32_t M, void* workspace, size_t workspace_bytes, void* stream);
+                      int32_t M, int64_t T, void* workspace, size_t workspace_bytes, void* stream);
 int32_t nm_linear_forward_i8_prepared(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask,
                                       int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
                                       const float* w_scale, const float* bias, void* Y, int64_t ldy,

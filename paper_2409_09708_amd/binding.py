@@ -138,7 +138,7 @@ def load_library() -> ctypes.CDLL:
     lib.nm_prune_scored.restype = c_int32
     lib.nm_prune_scored.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
     lib.nm_i8_workspace_bytes.restype = c_size_t
-    lib.nm_i8_workspace_bytes.argtypes = [c_int64, c_int64, c_int32, c_int32]
+    lib.nm_i8_workspace_bytes.argtypes = [c_int64, c_int64, c_int32, c_int32, c_int64]
     i8_args = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_void_p, c_int64, c_int64,
                ctypes.c_float, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
     lib.nm_linear_forward_i8.restype = c_int32
@@ -146,7 +146,7 @@ def load_library() -> ctypes.CDLL:
     lib.nm_linear_forward_i8_prepared.restype = c_int32
     lib.nm_linear_forward_i8_prepared.argtypes = i8_args
     lib.nm_i8_prepare.restype = c_int32
-    lib.nm_i8_prepare.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_void_p, c_size_t,
+    lib.nm_i8_prepare.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_int64, c_void_p, c_size_t,
                                   c_void_p]
     _LIB = lib
     return lib
@@ -623,8 +623,8 @@ def nm_linear_forward_prepared_batched(layers, stream=None):
     _check(load_library().nm_linear_forward_prepared_batched(descs, len(descs), _stream_handle(stream)))
 
 
-def nm_i8_workspace_bytes(O: int, K: int, N: int, M: int) -> int:
-    return int(load_library().nm_i8_workspace_bytes(O, K, N, M))
+def nm_i8_workspace_bytes(O: int, K: int, N: int, M: int, T: int) -> int:
+    return int(load_library().nm_i8_workspace_bytes(O, K, N, M, T))
 
 
 def _i8_weight(Wq, mask):
@@ -637,16 +637,17 @@ def _i8_weight(Wq, mask):
     return O, K, ldw
 
 
-def nm_i8_prepare(Wq, mask, N: int, M: int, workspace=None, stream=None):
-    """Compress the int8 weight into matrix-core operand order; returns the workspace (None if none is needed)."""
+def nm_i8_prepare(Wq, mask, N: int, M: int, T: int, workspace=None, stream=None):
+    """Compress the int8 weight into the operand order of the product at T tokens; returns the workspace (None if
+    none is needed)."""
     torch = _torch()
     O, K, ldw = _i8_weight(Wq, mask)
-    need = nm_i8_workspace_bytes(O, K, N, M)
+    need = nm_i8_workspace_bytes(O, K, N, M, T)
     if workspace is None and need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=Wq.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load_library().nm_i8_prepare(Wq.data_ptr(), O, K, ldw, mask.data_ptr(), N, M, ws_ptr, ws_bytes,
+    _check(load_library().nm_i8_prepare(Wq.data_ptr(), O, K, ldw, mask.data_ptr(), N, M, T, ws_ptr, ws_bytes,
                                         _stream_handle(stream)))
     return workspace
 
@@ -681,7 +682,7 @@ def nm_linear_forward_i8(Wq, mask, N: int, M: int, Xq, x_scale: float = 1.0, w_s
         if t.numel() != O or not t.is_contiguous():
             raise ValueError(f"{name} must be contiguous [O]")
         ptrs.append(t.data_ptr())
-    need = nm_i8_workspace_bytes(O, K, N, M)
+    need = nm_i8_workspace_bytes(O, K, N, M, T)
     if workspace is None and need:
         if _prepared:
             raise ValueError("a prepared call needs the workspace nm_i8_prepare filled")

@@ -309,9 +309,9 @@ int32_t nm_linear_backward_weight(const nm_bf16* dY, int64_t T, int64_t O, int64
   return device_status(e);
 }
 
-size_t nm_i8_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M) {
-  if (check_weight(O, K, N, M) != NM_OK) return 0;
-  return nm::i8_workspace_bytes(O, K, N, M);
+size_t nm_i8_workspace_bytes(int64_t O, int64_t K, int32_t N, int32_t M, int64_t T) {
+  if (check_weight(O, K, N, M) != NM_OK || T <= 0) return 0;
+  return nm::i8_workspace_bytes(O, K, N, M, T);
 }
 
 int32_t nm_linear_forward_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N,
@@ -323,8 +323,8 @@ int32_t nm_linear_forward_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw
 }
 
 int32_t nm_i8_prepare(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N, int32_t M,
-                      void* workspace, size_t workspace_bytes, void* stream) {
-  return i8_entry(Wq, O, K, ldw, mask, N, M, nullptr, 1, K, 1.f, nullptr, nullptr, nullptr, O, NM_OUT_F32, workspace,
+                      int64_t T, void* workspace, size_t workspace_bytes, void* stream) {
+  return i8_entry(Wq, O, K, ldw, mask, N, M, nullptr, T, K, 1.f, nullptr, nullptr, nullptr, O, NM_OUT_F32, workspace,
                   workspace_bytes, stream, nm::SPMM_PREPARE);
 }
 

@@ -104,4 +104,11 @@ __host__ __device__ __forceinline__ int64_t stream_selector_offset(int64_t row, 
   return (((row >> 8) * nk + step) << 11) + (r >> 5) * 256 + (r & 15) * 16 + chunk * 4 + ((r >> 4) & 1) * 2;
 }
 
+// int8 2:4 form: a lane's 16 compressed values take a whole selector word, so a row has 16 bytes of selectors
+// per K step (one word per lane group kb) and a (256-row tile, step) block is 4 KiB: [16-row block][row][kb]
+__host__ __device__ __forceinline__ int64_t stream_selector8_offset(int64_t row, int64_t step, int kb, int64_t nk) {
+  const int r = (int)(row & 255);
+  return (((row >> 8) * nk + step) << 12) + (r >> 4) * 256 + (r & 15) * 16 + kb * 4;
+}
+
 }  // namespace nm

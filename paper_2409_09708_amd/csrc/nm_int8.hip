@@ -29,9 +29,6 @@ namespace nm {
 
 namespace {
 
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
-typedef int i32x8_t __attribute__((ext_vector_type(8)));
-
 // ---------------------------------------------------------------------------------------------
 // Pre-pass: one lane per 32 consecutive weights of a row (one mask word).
 // Sparse form: run q (4 weights) owns slots 2q and 2q+1; its first kept weight goes to slot 2q with
@@ -87,6 +84,63 @@ mask_copy_i8_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* 
   uint4* dst = reinterpret_cast<uint4*>(dense + o * K + blk * 32);
   dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
   dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
+}
+
+// The same two forms in the persistent kernel's stream order (large layers): rows padded with zeros to whole
+// 256-row tiles; a K step is 128 wide in the 2:4 form (64 compressed bytes per row: the lane's 16 bytes are
+// piece blk % 4 of step blk / 4) and 64 wide in the dense form (the lane's 32 bytes are two pieces of step blk / 2).
+__global__ void __launch_bounds__(256)
+compress_i8_stream_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O,
+                          int64_t O_pad, int64_t K, unsigned char* __restrict__ vals_s, unsigned char* __restrict__ sel_s) {
+  const int64_t per_row = K / 32;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O_pad * per_row) return;
+  const int64_t o = id / per_row, blk = id % per_row;
+  uint32_t out[4] = {0, 0, 0, 0}, selw = 0;
+  if (o < O) {
+    const uint32_t mw = mask[o * per_row + blk];
+    const int8_t* w = Wq + o * ldw + blk * 32;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t bits = (mw >> (4 * q)) & 15u;
+      int slot = 0;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        if (((bits >> p) & 1u) && slot < 2) {
+          const int s = 2 * q + slot;
+          out[s >> 2] |= (uint32_t)(uint8_t)w[4 * q + p] << (8 * (s & 3));
+          selw |= (uint32_t)p << (2 * s);
+          ++slot;
+        }
+      }
+    }
+  }
+  const int64_t nk = K / 128, step = blk >> 2;
+  *reinterpret_cast<uint4*>(vals_s + stream_piece_offset(o, step, (int)(blk & 3), nk)) = make_uint4(out[0], out[1], out[2], out[3]);
+  *reinterpret_cast<uint32_t*>(sel_s + stream_selector8_offset(o, step, (int)(blk & 3), nk)) = selw;
+}
+
+__global__ void __launch_bounds__(256)
+mask_copy_i8_stream_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O,
+                           int64_t O_pad, int64_t K, unsigned char* __restrict__ dense_s) {
+  const int64_t per_row = K / 32;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O_pad * per_row) return;
+  const int64_t o = id / per_row, blk = id % per_row;
+  uint32_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (o < O) {
+    const uint32_t mw = mask[o * per_row + blk];
+    const int8_t* w = Wq + o * ldw + blk * 32;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        if ((mw >> (4 * i + b)) & 1u) out[i] |= (uint32_t)(uint8_t)w[4 * i + b] << (8 * b);
+  }
+  const int64_t nk = K / 64, step = blk >> 1;
+  const int c0 = (int)(blk & 1) * 2;
+  *reinterpret_cast<uint4*>(dense_s + stream_piece_offset(o, step, c0, nk)) = make_uint4(out[0], out[1], out[2], out[3]);
+  *reinterpret_cast<uint4*>(dense_s + stream_piece_offset(o, step, c0 + 1, nk)) = make_uint4(out[4], out[5], out[6], out[7]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -389,10 +443,11 @@ hipError_t dispatch_i8(const I8Args& g, hipStream_t s) {
 
 }  // namespace
 
-size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M) {
+size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   if (K % 128) return 0;  // the general kernel reads the weight and the mask itself
   const bool sparse_form = N <= 2 && N < M;
-  return sparse_form ? (size_t)(O * K / 2) + (size_t)(O * K / 8) : (size_t)(O * K);
+  const int64_t rows = stream_i8_takes(O, K, T, N, M) ? ((O + 255) / 256) * 256 : O;  // stream order: whole tiles
+  return sparse_form ? (size_t)(rows * K / 2) + (size_t)(rows * K / 8) : (size_t)(rows * K);
 }
 
 hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspace_short, int phases) {
@@ -408,13 +463,45 @@ hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspac
                        a.O, a.K, a.X, a.T, a.ldx, a.x_scale, a.w_scale, a.bias, a.Y, a.ldy, a.out_kind);
     return hipGetLastError();
   }
-  const size_t need = i8_workspace_bytes(a.O, a.K, a.N, a.M);
+  const size_t need = i8_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256)) {
     *workspace_short = true;
     return hipSuccess;
   }
   const bool sparse_form = a.N <= 2 && a.N < a.M;
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
+  if (stream_i8_takes(a.O, a.K, a.T, a.N, a.M)) {
+    // large layers: the persistent kernel, operands in its stream order.  It writes Y in 16-byte pieces and
+    // fetches scales and bias in 16-byte pieces; a call whose output or constants are not aligned for that runs
+    // the general kernel (it reads Wq and the mask itself).
+    const int64_t o_pad = ((a.O + 255) / 256) * 256;
+    unsigned char* sel_s = ws + (size_t)(o_pad * a.K / 2);
+    if (prepare) {
+      const int64_t n = o_pad * (a.K / 32);
+      const dim3 grid((unsigned)((n + 255) / 256));
+      if (sparse_form)
+        hipLaunchKernelGGL(compress_i8_stream_kernel, grid, dim3(256), 0, s, a.Wq, a.ldw, a.mask, a.O, o_pad, a.K, ws, sel_s);
+      else
+        hipLaunchKernelGGL(mask_copy_i8_stream_kernel, grid, dim3(256), 0, s, a.Wq, a.ldw, a.mask, a.O, o_pad, a.K, ws);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    if (!product) return hipSuccess;
+    const int per_piece = a.out_kind == 1 ? 8 : 4;
+    const bool vec = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) && a.ldy <= 0x7FFFFFFF &&
+                     aligned_to(a.w_scale, 16) && aligned_to(a.bias, 16) && (a.O % 4 == 0);
+    if (!vec) {
+      if (a.T * a.O > 0x7FFFFFFFll * 256) return hipErrorInvalidValue;
+      hipLaunchKernelGGL(i8_general_kernel, dim3((unsigned)((a.T * a.O + 255) / 256)), dim3(256), 0, s, a.Wq, a.ldw, a.mask,
+                         a.O, a.K, a.X, a.T, a.ldx, a.x_scale, a.w_scale, a.bias, a.Y, a.ldy, a.out_kind);
+      return hipGetLastError();
+    }
+    StreamI8Args g;
+    g.values = reinterpret_cast<const int8_t*>(ws); g.sel = sparse_form ? reinterpret_cast<const uint32_t*>(sel_s) : nullptr;
+    g.sparse_form = sparse_form; g.X = a.X; g.w_scale = a.w_scale; g.bias = a.bias; g.x_scale = a.x_scale;
+    g.Y = a.Y; g.O = a.O; g.K = a.K; g.T = a.T; g.ldx = a.ldx; g.ldy = a.ldy; g.out_kind = a.out_kind;
+    return launch_stream_i8(g, s);
+  }
   int8_t* vals = reinterpret_cast<int8_t*>(ws);
   uint32_t* sel = reinterpret_cast<uint32_t*>(ws + (size_t)(a.O * a.K / 2));
   if (prepare) {

@@ -100,6 +100,22 @@ hipError_t launch_backward_weight(const bf16_t* dY, int64_t T, int64_t O, int64_
                                   int64_t ldx, const uint32_t* mask, void* dW, int64_t lddw, int out_bf16, void* workspace,
                                   size_t workspace_bytes, hipStream_t s, bool* workspace_short);
 
+// nm_spmm.hip: the int8 layer on the persistent kernel (operands in stream order, O padded to 256 rows)
+struct StreamI8Args {
+  const int8_t* values;  // stream-order compressed values (2:4 form) or masked dense weight
+  const uint32_t* sel;   // stream-order selector words (2:4 form)
+  bool sparse_form;
+  const int8_t* X;
+  const float* w_scale;  // nullable; 16-byte aligned
+  const float* bias;     // nullable; 16-byte aligned
+  float x_scale;
+  void* Y;
+  int64_t O, K, T, ldx, ldy;
+  int out_kind;
+};
+bool stream_i8_takes(int64_t O, int64_t K, int64_t T, int N, int M);
+hipError_t launch_stream_i8(const StreamI8Args& a, hipStream_t s);
+
 // nm_int8.hip: the int8 layer.  Phases as for launch_spmm.
 struct I8LinearArgs {
   const int8_t* Wq;      // dense int8 weight [O, K], ld ldw
@@ -118,7 +134,7 @@ struct I8LinearArgs {
   void* workspace;
   size_t workspace_bytes;
 };
-size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M);
+size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);
 hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspace_short, int phases);
 
 }  // namespace nm

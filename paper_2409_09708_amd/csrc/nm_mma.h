@@ -11,6 +11,8 @@ typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(8))) uint32_t u32x8_t;
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
 
 // Asynchronous 16-byte (4-byte) per lane global -> LDS copy: lane i's piece lands at lds + 16*i (4*i).
 // `base` is wave-uniform (scalar registers), the lane adds an unsigned 32-bit byte offset; M0 carries

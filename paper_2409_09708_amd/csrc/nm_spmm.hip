@@ -482,7 +482,7 @@ nm_gemm_kernel(const GemmArgs a) {
 // neighbour but stores only its own) and the weight is zero-padded to whole tiles, so every tile is
 // full and lane offsets never change.
 // ---------------------------------------------------------------------------------------------
-template <bool SPARSE, int WO_, int WT_, int STAGES_>
+template <bool SPARSE, int WO_, int WT_, int STAGES_, bool I8 = false>
 struct StreamCfg {
   // Tiles are 256 out-features x (128 WT) tokens, a wave's share is 128 tokens wide.  The layout in use is
   // WO 4, WT 2: one block of 8 waves (64 x 128 outputs each) per CU, two waves per SIMD, three stages (four
@@ -493,22 +493,30 @@ struct StreamCfg {
   static constexpr int NW = WO * WT, NT = NW * 64, STAGES = STAGES_;
   static constexpr int PER_CU = (NW == 4 && STAGES == 2) ? 2 : 1;  // co-resident blocks
   static constexpr int OW = OT * 16;                     // out-features per wave
-  static constexpr int KSTEP = SPARSE ? 64 : 32;         // dense k per stage
-  static constexpr int X_ROWB = KSTEP * 2;               // bytes of one X row per stage
-  static constexpr int A_ROWB = 64;                      // 32 compressed values, or 32 dense weights
+  // The int8 forms (v_smfmac_i32_16x16x128_i8, v_mfma_i32_16x16x64_i8) have the same geometry in bytes with
+  // twice the K per step; only the selectors differ: a lane's 16 compressed values need a whole 32-bit word,
+  // so a row takes 16 bytes of selectors per step instead of 8 and no two rows share a word.
+  static constexpr int ES = I8 ? 1 : 2;                  // bytes per operand element
+  static constexpr int X_ROWB = SPARSE ? 128 : 64;       // bytes of one X row per stage
+  static constexpr int KSTEP = X_ROWB / ES;              // dense k per stage
+  static constexpr int A_ROWB = 64;                      // compressed values of the 2:4 form, or dense weights
   static constexpr int X_BYTES = BT * X_ROWB;
   static constexpr int A_BYTES = BO * A_ROWB;
-  static constexpr int S_BYTES = SPARSE ? BO * 8 : 0;
+  static constexpr int S_ROWB = I8 ? 16 : 8;
+  static constexpr int S_BYTES = SPARSE ? BO * S_ROWB : 0;
   static constexpr int STAGE = X_BYTES + A_BYTES + S_BYTES;
-  static constexpr int BIAS0 = STAGES * STAGE;           // one bias slice (BO floats) per stage buffer
-  static constexpr int LDS_BYTES = BIAS0 + STAGES * BO * 4;
+  // Per-out-feature constants of a tile travel through LDS: the bias (one slice of BO floats per stage buffer,
+  // read when the tile starts), or for int8 the weight scales and the bias (read when the tile ends, so the
+  // slices alternate with the tile's parity instead: two pairs)
+  static constexpr int BIAS0 = STAGES * STAGE;
+  static constexpr int LDS_BYTES = BIAS0 + (I8 ? 4 : STAGES) * BO * 4;
   static constexpr int X_PW = X_BYTES / 1024 / NW;
   static constexpr int A_PW = A_BYTES / 1024 / NW;
   static constexpr int S_PW = SPARSE ? S_BYTES / 256 / NW : 0;
   static constexpr int LPW = X_PW + A_PW + S_PW;
   static_assert(WO == 2 || WO == 4, "wave layouts");
   static_assert(BO * 4 == 1024, "the bias slice of a tile is one wave-load");
-  static_assert(LDS_BYTES * PER_CU <= 160 * 1024 && STAGES * (LPW + 1) < 64, "LDS budget and vmcnt range");
+  static_assert(LDS_BYTES * PER_CU <= 160 * 1024 && STAGES * (LPW + 2) < 64, "LDS budget and vmcnt range");
 };
 
 // One launch serves a list of layers of the same operand form: their tiles form one list (layer after layer),
@@ -520,25 +528,26 @@ struct StreamLayer {
   const uint32_t* sel;  // stream-order selectors (2:4 form)
   const bf16_t* X;
   const float* bias;    // nullable
+  const float* scale;   // int8: per-out-feature weight scales, nullable (= 1)
   void* Y;
-  int32_t O, T, nk, ldx, ldy;  // nk: K steps of the form (K / 64 or K / 32)
+  int32_t O, T, nk, ldx, ldy;  // nk: K steps of the form; ldx, ldy in elements
   int32_t n_o_tiles;
-  int32_t n_tiles;               // tiles of this layer
-  int32_t reserved0;
-  int32_t out_bf16;
+  int32_t n_tiles;      // tiles of this layer
+  float x_scale;        // int8: activation scale
+  int32_t out_kind;     // NM_OUT_F32 / NM_OUT_BF16 / NM_OUT_I32 (int8 only)
   int32_t reserved;
 };
-constexpr int kStreamLayersMax = 48;
+constexpr int kStreamLayersMax = 44;
 struct StreamGroup {
   int32_t count, n_tiles;
   StreamLayer layer[kStreamLayersMax];
 };
 static_assert(sizeof(StreamGroup) <= 4096, "the table must fit the kernel argument segment");
 
-template <bool SPARSE, int WO_, int WT_, int STAGES_>
+template <bool SPARSE, int WO_, int WT_, int STAGES_, bool I8 = false>
 __global__ void __launch_bounds__(WO_ * WT_ * 64, (WO_ * WT_ == 4 && STAGES_ == 2) ? 2 : (WO_ * WT_) / 4)
 nm_stream_kernel(const StreamGroup g) {
-  using C = StreamCfg<SPARSE, WO_, WT_, STAGES_>;
+  using C = StreamCfg<SPARSE, WO_, WT_, STAGES_, I8>;
   constexpr int OT = C::OT, TT = C::TT, STAGES = C::STAGES;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -585,7 +594,7 @@ nm_stream_kernel(const StreamGroup g) {
       int row, c;
       if (SPARSE) { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (row & 7); }
       else { row = 16 * j + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
-      x_voff[i] = (uint32_t)(((int64_t)row * ldx + c * 8) * 2);
+      x_voff[i] = (uint32_t)((int64_t)row * ldx * C::ES + c * 16);
     }
 #pragma unroll
     for (int i = 0; i < C::A_PW; ++i)
@@ -622,6 +631,7 @@ nm_stream_kernel(const StreamGroup g) {
   ListPos ld_at{0, 0};
   uint32_t ld_bias_voff = 0;
   const float* ld_bias = nullptr;
+  const float* ld_scale = nullptr;
   const unsigned char* ld_x = nullptr;
   const unsigned char* ld_w = nullptr;
   const unsigned char* ld_s = nullptr;
@@ -636,20 +646,21 @@ nm_stream_kernel(const StreamGroup g) {
       layer_offsets(L.ldx, ld_nk);
       ld_offsets_of = ld_layer;
     }
-    ld_x = reinterpret_cast<const unsigned char*>(L.X + t0 * L.ldx);
+    ld_x = reinterpret_cast<const unsigned char*>(L.X) + t0 * L.ldx * C::ES;
     ld_w = reinterpret_cast<const unsigned char*>(L.A) + (((int64_t)o_tile * 16 * ld_nk) << 10);
-    ld_s = SPARSE ? reinterpret_cast<const unsigned char*>(L.sel) + (((int64_t)o_tile * ld_nk) << 11) : nullptr;
+    ld_s = SPARSE ? reinterpret_cast<const unsigned char*>(L.sel) + (int64_t)o_tile * ld_nk * C::S_BYTES : nullptr;
     // bias[o0 + 4 lane ..]: past the last out-feature re-read the last four (never stored)
     const int64_t ob = (int64_t)o_tile * C::BO + lane * 4;
     ld_bias = L.bias;
+    ld_scale = L.scale;
     ld_bias_voff = (uint32_t)((ob + 4 <= L.O ? ob : L.O - 4) * 4);
     ld_n = n;
     ld_ks = 0;
   };
   auto cursor_advance = [&]() {
-    ld_x += C::KSTEP * 2;
+    ld_x += C::X_ROWB;
     ld_w += 1024;
-    if (SPARSE) ld_s += 2048;
+    if (SPARSE) ld_s += C::S_BYTES;
     // past the block's last stage the cursor walks the last tile again: the step below then needs no
     // conditions (the surplus stages land in buffers nobody reads any more)
     if (++ld_ks == ld_nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
@@ -661,9 +672,16 @@ nm_stream_kernel(const StreamGroup g) {
     if constexpr (d == 0) {
       // a tile's first stage brings the tile's bias slice along (older than the stage's own loads, so
       // every wait that covers the stage covers it); slice s belongs to stage buffer s
-      if (wave == 0 && ld_bias != nullptr && ld_ks == 0)  // wave 0 also fetches the tiles' bias slices
-        dma16(make_uniform(ld_bias), ld_bias_voff,
-              __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)C::BIAS0 + stage_off / (uint32_t)C::STAGE * (C::BO * 4)));
+      if (wave == 0 && ld_ks == 0) {  // wave 0 also fetches the tiles' per-out-feature constants
+        if constexpr (I8) {
+          const uint32_t pair = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)C::BIAS0 + (uint32_t)(ld_n & 1) * (2 * C::BO * 4));
+          if (ld_scale != nullptr) dma16(make_uniform(ld_scale), ld_bias_voff, pair);
+          if (ld_bias != nullptr) dma16(make_uniform(ld_bias), ld_bias_voff, pair + C::BO * 4);
+        } else if (ld_bias != nullptr) {
+          dma16(make_uniform(ld_bias), ld_bias_voff,
+                __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)C::BIAS0 + stage_off / (uint32_t)C::STAGE * (C::BO * 4)));
+        }
+      }
     }
     if constexpr (d < C::X_PW) {
       dma16_at(make_uniform(ld_x), x_voff[d], lds, __builtin_amdgcn_readfirstlane(x_dst[d]));
@@ -690,18 +708,21 @@ nm_stream_kernel(const StreamGroup g) {
   struct FragAddr { uint32_t a, s, xlo, xhi; };  // byte offsets into the dynamic LDS
   FragAddr at0;
   at0.a = (uint32_t)(C::X_BYTES + (wo * C::OW + r16) * C::A_ROWB + ((kb ^ ((r16 >> 2) & 3)) * 16));
-  at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (wo * C::OW / 32) * 256 + r16 * 16 + kb * 4);
+  at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (I8 ? wo * OT : wo * C::OW / 32) * 256 + r16 * 16 + kb * 4);
   at0.xlo = (uint32_t)((wt * 128 + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16)));
   at0.xhi = (uint32_t)((wt * 128 + r16) * C::X_ROWB + ((4 + kb) ^ (r16 & 7)) * 16);
   auto frag_addr = [&](uint32_t stage_off) {
     return FragAddr{at0.a + stage_off, at0.s + stage_off, at0.xlo + stage_off, at0.xhi + stage_off};
   };
-  // W fragments come in pairs of 16-row blocks: one selector word serves both (low / high half)
-  auto read_a2 = [&](const FragAddr& at, int ip, u32x4_t& av0, u32x4_t& av1, int& sv) {
+  // W fragments come in pairs of 16-row blocks: for bfloat16 one selector word serves both (low / high half),
+  // for int8 each block has its own word (sv holds the pair)
+  constexpr int SV = I8 ? 2 : 1;  // selector registers per pair of blocks
+  auto read_a2 = [&](const FragAddr& at, int ip, u32x4_t& av0, u32x4_t& av1, int* sv) {
     av0 = *reinterpret_cast<const u32x4_t*>(smem + at.a + (2 * ip) * 16 * C::A_ROWB);
     av1 = *reinterpret_cast<const u32x4_t*>(smem + at.a + (2 * ip + 1) * 16 * C::A_ROWB);
-    if (SPARSE) sv = (int)*reinterpret_cast<const uint32_t*>(smem + at.s + ip * 256);
-    else sv = 0;
+#pragma unroll
+    for (int q = 0; q < SV; ++q)
+      sv[q] = SPARSE ? (int)*reinterpret_cast<const uint32_t*>(smem + at.s + (ip * SV + q) * 256) : 0;
   };
   auto read_b = [&](const FragAddr& at, int j, bfrag_t& bv) {
     if constexpr (SPARSE) {
@@ -726,17 +747,18 @@ nm_stream_kernel(const StreamGroup g) {
   __builtin_amdgcn_s_barrier();
 
   u32x4_t afr[2][OT];  // W fragments of the current step and of the next one; the roles alternate
-  int sfr[2][OT / 2];
+  int sfr[2][OT / 2 * SV];
   FragAddr at[2];      // likewise the fragment addresses in the current and in the next buffer
   bfrag_t bq[4];
   at[0] = at0;
 #pragma unroll
-  for (int ip = 0; ip < OT / 2; ++ip) read_a2(at[0], ip, afr[0][2 * ip], afr[0][2 * ip + 1], sfr[0][ip]);
+  for (int ip = 0; ip < OT / 2; ++ip) read_a2(at[0], ip, afr[0][2 * ip], afr[0][2 * ip + 1], &sfr[0][ip * SV]);
 #pragma unroll
   for (int j = 0; j < 3; ++j) read_b(at[0], j, bq[j]);
 
   uint32_t cur_off = 0;  // LDS offset of the buffer that holds the current stage
-  f32x4_t acc[OT][TT];
+  using acc_t = std::conditional_t<I8, i32x4_t, f32x4_t>;
+  acc_t acc[OT][TT];
 
   // One K step, free of conditions: a wave issues one instruction at a time, in order, so every other
   // instruction of the step is time its matrix instructions do not get.  PP names the fragment and address
@@ -763,12 +785,19 @@ nm_stream_kernel(const StreamGroup g) {
           constexpr int part = j - (TT - AG);
 #pragma unroll
           for (int ip = part * (OT / 2) / AG; ip < (part + 1) * (OT / 2) / AG; ++ip)
-            read_a2(at[PP ^ 1], ip, afr[PP ^ 1][2 * ip], afr[PP ^ 1][2 * ip + 1], sfr[PP ^ 1][ip]);
+            read_a2(at[PP ^ 1], ip, afr[PP ^ 1][2 * ip], afr[PP ^ 1][2 * ip + 1], &sfr[PP ^ 1][ip * SV]);
         }
         [&]<int... I>(std::integer_sequence<int, I...>) {
           ([&] {
             constexpr int i = I;
-            if constexpr (SPARSE)
+            if constexpr (SPARSE && I8)
+              acc[i][j] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(i32x4_t, afr[PP][i]),
+                                                                   __builtin_bit_cast(i32x8_t, bq[j & 3]), acc[i][j],
+                                                                   sfr[PP][i], 0, 0);
+            else if constexpr (I8)
+              acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, afr[PP][i]),
+                                                                __builtin_bit_cast(i32x4_t, bq[j & 3]), acc[i][j], 0, 0, 0);
+            else if constexpr (SPARSE)
               acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, afr[PP][i]),
                                                                     __builtin_bit_cast(bf16x16_t, bq[j & 3]),
                                                                     acc[i][j], sfr[PP][i / 2], 0, i & 1);
@@ -803,13 +832,18 @@ nm_stream_kernel(const StreamGroup g) {
     const int64_t o0 = (int64_t)o_tile * C::BO;
 #pragma unroll
     for (int i = 0; i < OT; ++i) {
-      // the accumulators start from the bias, which came with the tile's first stage
-      f32x4_t b = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      if (L.bias != nullptr)
-        b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + cur_off / (uint32_t)C::STAGE * (C::BO * 4) +
-                                              (wo * C::OW + i * 16 + kb * 4) * 4);
+      if constexpr (I8) {
 #pragma unroll
-      for (int j = 0; j < TT; ++j) acc[i][j] = b;
+        for (int j = 0; j < TT; ++j) acc[i][j] = i32x4_t{0, 0, 0, 0};
+      } else {
+        // the accumulators start from the bias, which came with the tile's first stage
+        f32x4_t b = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (L.bias != nullptr)
+          b = *reinterpret_cast<const f32x4_t*>(smem + C::BIAS0 + cur_off / (uint32_t)C::STAGE * (C::BO * 4) +
+                                                (wo * C::OW + i * 16 + kb * 4) * 4);
+#pragma unroll
+        for (int j = 0; j < TT; ++j) acc[i][j] = b;
+      }
     }
 
     // steps in pairs, so that every tile starts with fragment set 0; an odd count ends with a copy
@@ -821,7 +855,9 @@ nm_stream_kernel(const StreamGroup g) {
       step(std::integral_constant<int, 0>{});
       at[0] = at[1];
 #pragma unroll
-      for (int i = 0; i < OT; ++i) { afr[0][i] = afr[1][i]; sfr[0][i / 2] = sfr[1][i / 2]; }
+      for (int i = 0; i < OT; ++i) afr[0][i] = afr[1][i];
+#pragma unroll
+      for (int i = 0; i < OT / 2 * SV; ++i) sfr[0][i] = sfr[1][i];
     }
     if (n + 1 == my_tiles) wait_loads_outstanding<0>();  // the surplus stages: nothing in flight when the block ends
 
@@ -831,11 +867,35 @@ nm_stream_kernel(const StreamGroup g) {
     // permutation then puts the four pieces of a row's 64-byte segment into four consecutive lanes: a store
     // instruction is merged only across consecutive lanes, and 16 requests of 64 bytes go through where 64 of
     // 16 bytes did (2 % of the whole stack).
+    // int8: the sums are rescaled first, y = fma(float(acc), x_scale * w_scale[o], bias[o]); the tile's scales
+    // and bias came with its first stage (pair n mod 2, so the next tile's do not overwrite them)
+    f32x4_t sc[I8 ? OT : 1], bi[I8 ? OT : 1];
+    if constexpr (I8) {
+      const unsigned char* pair = smem + C::BIAS0 + (n & 1) * (2 * C::BO * 4);
+#pragma unroll
+      for (int i = 0; i < OT; ++i) {
+        const int off = (wo * C::OW + i * 16 + kb * 4) * 4;
+        sc[i] = f32x4_t{L.x_scale, L.x_scale, L.x_scale, L.x_scale};
+        bi[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (L.scale != nullptr) sc[i] *= *reinterpret_cast<const f32x4_t*>(pair + off);
+        if (L.bias != nullptr) bi[i] = *reinterpret_cast<const f32x4_t*>(pair + C::BO * 4 + off);
+      }
+    }
+    auto value = [&](int i, int j) -> f32x4_t {
+      if constexpr (I8) {
+        f32x4_t y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = fmaf((float)acc[i][j][e], sc[i][e], bi[i][e]);
+        return y;
+      } else {
+        return acc[i][j];
+      }
+    };
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
       const int64_t t = t0 + wt * 128 + j * 16 + r16;
       const bool row_ok = t >= t_lo;
-      if (L.out_bf16) {
+      if (L.out_kind == 1) {
         // lane 4m + q takes the piece of lane (token row m, kb = 0, 2, 1, 3 for q = 0 .. 3)
         const int q4 = lane & 3;
         const int src_lane = (lane >> 2) + 16 * (((q4 & 1) << 1) | (q4 >> 1));
@@ -843,9 +903,11 @@ nm_stream_kernel(const StreamGroup g) {
         const bool row_ok2 = t2 >= t_lo;
 #pragma unroll
         for (int ip = 0; ip < OT / 2; ++ip) {
-          const f32x4_t v0 = acc[2 * ip][j], v1 = acc[2 * ip + 1][j];
+          const f32x4_t v0 = value(2 * ip, j), v1 = value(2 * ip + 1, j);
           const uint32_t a0 = pack_bf16x2(v0[0], v0[1]), a1 = pack_bf16x2(v0[2], v0[3]);
           const uint32_t b0 = pack_bf16x2(v1[0], v1[1]), b1 = pack_bf16x2(v1[2], v1[3]);
+          // even lane rows keep their first operand and receive the odd partner's; odd rows receive the
+          // even partner's second operand and keep theirs
           const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
           const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
           u32x4_t piece = u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
@@ -859,8 +921,11 @@ nm_stream_kernel(const StreamGroup g) {
 #pragma unroll
         for (int i = 0; i < OT; ++i) {
           const int64_t o = o0 + wo * C::OW + i * 16 + kb * 4;
+          u32x4_t piece;
+          if (I8 && L.out_kind == 2) piece = __builtin_bit_cast(u32x4_t, acc[i][j]);  // the integer sums themselves
+          else piece = __builtin_bit_cast(u32x4_t, value(i, j));
           if (row_ok && o < L.O)
-            *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(L.Y) + t * L.ldy + o) = acc[i][j];
+            *reinterpret_cast<u32x4_t*>(reinterpret_cast<uint32_t*>(L.Y) + t * L.ldy + o) = piece;
         }
       }
     }
@@ -962,10 +1027,10 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <bool SPARSE>
+template <bool SPARSE, bool I8 = false>
 static hipError_t launch_stream_group(const StreamGroup& grp, hipStream_t s) {
-  using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4>;  // dense stages are half the size: four fit
-  auto kern = nm_stream_kernel<SPARSE, 4, 2, SPARSE ? 3 : 4>;
+  using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;  // dense stages are half the size: four fit
+  auto kern = nm_stream_kernel<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;
   static int n_cu = 0;  // filled once; a race only repeats the query
   if (!n_cu) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -991,12 +1056,12 @@ static bool group_append(StreamGroup& grp, const GemmArgs& g) {
   const int64_t end = (int64_t)grp.n_tiles + n_o * n_t;
   if (grp.count >= kStreamLayersMax || end > 0x7FFFFFF0) return false;
   StreamLayer& L = grp.layer[grp.count++];
-  L.A = g.A; L.sel = g.sel; L.X = g.X; L.bias = g.bias; L.Y = g.Y;
+  L.A = g.A; L.sel = g.sel; L.X = g.X; L.bias = g.bias; L.scale = nullptr; L.Y = g.Y;
   L.O = (int32_t)g.O; L.T = (int32_t)g.T; L.nk = (int32_t)(g.K / C::KSTEP);
   L.ldx = (int32_t)g.ldx; L.ldy = (int32_t)g.ldy;
   L.n_o_tiles = (int32_t)n_o;
-  L.n_tiles = (int32_t)(n_o * n_t); L.reserved0 = 0;
-  L.out_bf16 = g.out_bf16; L.reserved = 0;
+  L.n_tiles = (int32_t)(n_o * n_t);
+  L.x_scale = 1.f; L.out_kind = g.out_bf16 ? 1 : 0; L.reserved = 0;
   grp.n_tiles = (int32_t)end;
   return true;
 }
@@ -1007,6 +1072,31 @@ static hipError_t launch_stream(const GemmArgs& g, hipStream_t s) {
   grp.count = 0; grp.n_tiles = 0;
   if (!group_append<SPARSE>(grp, g)) return hipErrorInvalidValue;
   return launch_stream_group<SPARSE>(grp, s);
+}
+
+// The int8 layer on the persistent kernel.  The operands are in stream order (see nm_int8.hip's pre-pass).
+bool stream_i8_takes(int64_t O, int64_t K, int64_t T, int N, int M) {
+  const bool sparse_form = N <= 2 && N < M;
+  const int64_t kstep = sparse_form ? 128 : 64;
+  // the per-tile constants alternate between two LDS slices, which needs tiles of at least three steps
+  return pick_tile(O, T) == 0 && K % kstep == 0 && K / kstep >= 3 && O <= (1 << 24) && T < (1ll << 31) && K <= (1 << 22);
+}
+
+hipError_t launch_stream_i8(const StreamI8Args& a, hipStream_t s) {
+  StreamGroup grp;
+  grp.count = 1;
+  StreamLayer& L = grp.layer[0];
+  const int64_t kstep = a.sparse_form ? 128 : 64;
+  const int64_t n_o = (a.O + 255) / 256, n_t = (a.T + 255) / 256;
+  if (n_o * n_t > 0x7FFFFFF0) return hipErrorInvalidValue;
+  L.A = reinterpret_cast<const bf16_t*>(a.values); L.sel = a.sel; L.X = reinterpret_cast<const bf16_t*>(a.X);
+  L.bias = a.bias; L.scale = a.w_scale; L.Y = a.Y;
+  L.O = (int32_t)a.O; L.T = (int32_t)a.T; L.nk = (int32_t)(a.K / kstep);
+  L.ldx = (int32_t)a.ldx; L.ldy = (int32_t)a.ldy;
+  L.n_o_tiles = (int32_t)n_o; L.n_tiles = (int32_t)(n_o * n_t);
+  L.x_scale = a.x_scale; L.out_kind = a.out_kind; L.reserved = 0;
+  grp.n_tiles = L.n_tiles;
+  return a.sparse_form ? launch_stream_group<true, true>(grp, s) : launch_stream_group<false, true>(grp, s);
 }
 
 template <bool SPARSE>

@@ -103,12 +103,50 @@ def test_large_tile_paths_and_prepared_calls(N, M, edge):
     Wd, Xd = dev_i8(wq), dev_i8(xq)
     whole = nm.nm_linear_forward_i8(Wd, words, N, M, Xd, out_dtype=torch.int32)
     assert np.array_equal(whole.cpu().numpy().astype(np.int64), q.nm_accumulate_i8(xq, wq, mask))
-    ws = nm.nm_i8_prepare(Wd, words, N, M)
-    assert ws.numel() == nm.nm_i8_workspace_bytes(O, K, N, M)
+    ws = nm.nm_i8_prepare(Wd, words, N, M, T)
+    assert ws.numel() == nm.nm_i8_workspace_bytes(O, K, N, M, T)
     snapshot = ws.clone()
     for _ in range(2):
         assert torch.equal(nm.nm_linear_forward_i8_prepared(Wd, words, N, M, Xd, ws, out_dtype=torch.int32), whole)
     assert torch.equal(ws, snapshot)
+
+
+@pytest.mark.parametrize("N,M,K", [(2, 4, 640), (2, 16, 640), (4, 8, 640), (8, 8, 640), (1, 8, 384), (4, 8, 384)])
+def test_persistent_kernel_all_outputs(N, M, K):
+    # enough 256 x 256 tiles and at least three K steps: the persistent kernel, operands in stream order.  Ragged
+    # tiles in both directions, an odd and an even number of K steps, scales and bias through LDS, every output
+    # type, a prepared workspace serving repeated calls
+    rng = np.random.default_rng(7700 + N * 17 + M + K)
+    T, O = 16 * 256 + 37, 16 * 256 + 36
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = random_mask(rng, O, K, N, M)
+    words = dev_words(orc.mask_to_words(mask))
+    Wd, Xd = dev_i8(wq), dev_i8(xq)
+    acc = q.nm_accumulate_i8(xq, wq, mask)
+    ws = nm.nm_i8_prepare(Wd, words, N, M, T)
+    o_pad = 17 * 256
+    assert ws.numel() == (o_pad * K // 2 + o_pad * K // 8 if N <= 2 else o_pad * K)
+    snapshot = ws.clone()
+    got = nm.nm_linear_forward_i8_prepared(Wd, words, N, M, Xd, ws, out_dtype=torch.int32)
+    assert np.array_equal(got.cpu().numpy().astype(np.int64), acc)
+    x_scale = 0.0173
+    x_scale32 = float(np.float32(x_scale))
+    w_scale = (0.001 + 0.002 * rng.random(O)).astype(np.float32)
+    bias = rng.standard_normal(O).astype(np.float32)
+    Yref = q.nm_linear_i8(xq, wq, mask, x_scale32, w_scale, bias)
+    ws_d, b_d = torch.from_numpy(w_scale).cuda(), torch.from_numpy(bias).cuda()
+    for dt in (torch.float32, torch.bfloat16):
+        Y = nm.nm_linear_forward_i8_prepared(Wd, words, N, M, Xd, ws, x_scale=x_scale, w_scale=ws_d, bias=b_d, out_dtype=dt)
+        check_scaled(host_output(Y), Yref, acc, x_scale32 * w_scale.astype(np.float64), bias, dt == torch.bfloat16, (N, M, K, dt))
+    # scales without bias, bias without scales
+    Y = nm.nm_linear_forward_i8_prepared(Wd, words, N, M, Xd, ws, x_scale=x_scale, w_scale=ws_d)
+    check_scaled(host_output(Y), q.nm_linear_i8(xq, wq, mask, x_scale32, w_scale), acc, x_scale32 * w_scale.astype(np.float64),
+                 None, False, "scale only")
+    Y = nm.nm_linear_forward_i8_prepared(Wd, words, N, M, Xd, ws, bias=b_d)
+    check_scaled(host_output(Y), q.nm_linear_i8(xq, wq, mask, 1.0, np.ones(O), bias), acc, np.ones(O), bias, False, "bias only")
+    assert torch.equal(ws, snapshot)
+    whole = nm.nm_linear_forward_i8(Wd, words, N, M, Xd, out_dtype=torch.int32)
+    assert torch.equal(whole, got)
 
 
 def test_pruned_positions_are_ignored_whatever_they_hold():

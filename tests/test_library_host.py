@@ -272,11 +272,15 @@ def test_backward_weight_workspace_sizes(lib):
 
 def test_int8_argument_errors_and_sizes(lib):
     f = lib.nm_i8_workspace_bytes
-    assert f(768, 768, 2, 4) == 768 * 768 // 2 + 768 * 768 // 8   # values + 2-bit selectors
-    assert f(768, 768, 1, 16) == 768 * 768 // 2 + 768 * 768 // 8  # every level with N <= 2 takes the 2:4 form
-    assert f(768, 768, 4, 8) == 768 * 768 and f(768, 768, 8, 8) == 768 * 768  # masked dense copy
-    assert f(64, 48, 1, 8) == 0                                   # general kernel
-    assert f(64, 64, 3, 2) == 0 and f(0, 64, 2, 4) == 0
+    assert f(768, 768, 2, 4, 197) == 768 * 768 // 2 + 768 * 768 // 8   # values + 2-bit selectors
+    assert f(768, 768, 1, 16, 197) == 768 * 768 // 2 + 768 * 768 // 8  # every level with N <= 2 takes the 2:4 form
+    assert f(768, 768, 4, 8, 197) == 768 * 768 and f(768, 768, 8, 8, 197) == 768 * 768  # masked dense copy
+    assert f(64, 48, 1, 8, 197) == 0                                   # general kernel
+    assert f(64, 64, 3, 2, 197) == 0 and f(0, 64, 2, 4, 197) == 0 and f(64, 128, 2, 4, 0) == 0
+    # large layers: the persistent kernel's stream order, rows padded to whole 256-row tiles (700 -> 768)
+    assert f(700, 768, 2, 4, 50432) == 768 * 768 // 2 + 768 * 768 // 8
+    assert f(700, 768, 4, 8, 50432) == 768 * 768
+    assert f(700, 256, 2, 4, 50432) == 700 * 256 // 2 + 700 * 256 // 8  # fewer than three K steps: tiled kernel
 
     def call(**kw):
         a = dict(Wq=FAKE, O=64, K=128, ldw=128, mask=FAKE, N=2, M=4, Xq=FAKE, T=16, ldx=128, Y=FAKE, ldy=64, dt=2,
@@ -290,11 +294,12 @@ def test_int8_argument_errors_and_sizes(lib):
     assert call(K=130) == 2 and call(T=0) == 2 and call(ldw=64) == 2 and call(ldx=64) == 2 and call(ldy=8) == 2
     assert call(dt=3) == 5
     assert call(mask=FAKE + 2) == 4 and call(Y=FAKE + 2) == 4 and call(Y=FAKE + 2, dt=1) != 4
-    need = lib.nm_i8_workspace_bytes(64, 128, 2, 4)
+    need = lib.nm_i8_workspace_bytes(64, 128, 2, 4, 16)
     assert call(ws=None, wsb=0) == 6 and call(wsb=need - 1) == 6 and call(ws=FAKE + 16) == 6
-    assert lib.nm_i8_prepare(None, 64, 128, 128, FAKE, 2, 4, FAKE, need, None) == 1
-    assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, None, 0, None) == 6
-    assert lib.nm_i8_prepare(FAKE, 64, 48, 48, FAKE, 1, 8, None, 0, None) == 0  # nothing to prepare
+    assert lib.nm_i8_prepare(None, 64, 128, 128, FAKE, 2, 4, 16, FAKE, need, None) == 1
+    assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, 16, None, 0, None) == 6
+    assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, 0, FAKE, need, None) == 2
+    assert lib.nm_i8_prepare(FAKE, 64, 48, 48, FAKE, 1, 8, 16, None, 0, None) == 0  # nothing to prepare
 
 
 def test_prune_scored_argument_errors(lib):
