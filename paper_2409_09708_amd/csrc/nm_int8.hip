@@ -13,9 +13,11 @@
 //     k = 32 kb .. 32 kb + 31 and their 16 selectors in one register; the X operand lane (col, kb) holds
 //     k = 16 kb + e (e < 16) and 64 + 16 kb + (e - 16) (e >= 16).  Half of the dense multiply-accumulates.
 //   * N > 2: the masked dense weight through v_mfma_i32_16x16x64_i8 (lane (row, kb): k = 16 kb .. 16 kb + 15).
-// A K step is 128 wide, so the LDS geometry in bytes is that of the bfloat16 kernel at K = 64: 128-byte X rows,
+// A K step is 128 wide, so the LDS geometry in bytes is that of the bfloat16 kernels at K = 64: 128-byte X rows,
 // 64-byte compressed (128-byte dense) W rows, 16-byte pieces XOR-swizzled, asynchronous global -> LDS copies
-// three stages deep, one barrier per step.  Shapes the tiles cannot take run a one-lane-per-output kernel.
+// three stages deep, one barrier per step.  Large layers run the persistent kernel of the bfloat16 path
+// (nm_spmm.hip, templated on these instructions; the pre-pass here writes its stream order), smaller ones the
+// tiled kernel below, shapes the tiles cannot take a one-lane-per-output kernel.
 #include "nm_device.h"
 #include "nm_launch.h"
 #include "nm_mma.h"
