@@ -477,6 +477,8 @@ nm_gemm_kernel(const GemmArgs a) {
 // TT-3 of stage g) every wave has issued all its reads of stage g: it drains them, makes sure its
 // share of stage g+1 has landed, meets the others at the step's only barrier and then refills the
 // buffer of stage g with stage g+3, two full steps ahead of its use.
+// The tiles that share X rows (same tokens, other out-features) run on one XCD at the same time; each
+// walks K from its own starting step and wraps around, so that they do not miss on the same lines together.
 // The weight arrives in stream order (see the pre-pass above): every W load is one contiguous
 // kilobyte.  A ragged last token tile is shifted back inside X (it recomputes a few rows of its
 // neighbour but stores only its own) and the weight is zero-padded to whole tiles, so every tile is
@@ -627,7 +629,7 @@ nm_stream_kernel(const StreamGroup g) {
 
   // ---- load cursor = the stage to be issued next (tile number in this block, k step) as running pointers: X
   // rows of the tile at the step's k, W and selector blocks of the step
-  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_offsets_of = -1;
+  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_wrap = 1, ld_offsets_of = -1;
   ListPos ld_at{0, 0};
   uint32_t ld_bias_voff = 0;
   const float* ld_bias = nullptr;
@@ -654,6 +656,14 @@ nm_stream_kernel(const StreamGroup g) {
     ld_bias = L.bias;
     ld_scale = L.scale;
     ld_bias_voff = (uint32_t)((ob + 4 <= L.O ? ob : L.O - 4) * 4);
+    // The tiles that share the tile's X rows (same tokens, other out-features) run on the same XCD at the
+    // same time; each starts at its own K step and wraps around, so they ask for different slices of those rows
+    // at any moment and find the others' slices in L2 instead of missing on them together.
+    ld_wrap = ld_nk - (int)((unsigned)o_tile % (unsigned)ld_nk);  // steps until the walk wraps to K step 0
+    const int64_t k0 = ld_nk - ld_wrap;
+    ld_x += k0 * C::X_ROWB;
+    ld_w += k0 * 1024;
+    if (SPARSE) ld_s += k0 * C::S_BYTES;
     ld_n = n;
     ld_ks = 0;
   };
@@ -663,7 +673,12 @@ nm_stream_kernel(const StreamGroup g) {
     if (SPARSE) ld_s += C::S_BYTES;
     // past the block's last stage the cursor walks the last tile again: the step below then needs no
     // conditions (the surplus stages land in buffers nobody reads any more)
-    if (++ld_ks == ld_nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
+    if (++ld_ks == ld_wrap) {
+      ld_x -= (int64_t)ld_nk * C::X_ROWB;
+      ld_w -= (int64_t)ld_nk * 1024;
+      if (SPARSE) ld_s -= (int64_t)ld_nk * C::S_BYTES;
+    }
+    if (ld_ks == ld_nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
   };
   // the d-th of this wave's LPW loads of the cursor's stage into the stage buffer at LDS offset stage_off
   auto issue_one = [&](auto d_tag, uint32_t stage_off) {
