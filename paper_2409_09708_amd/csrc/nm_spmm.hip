@@ -657,9 +657,10 @@ nm_stream_kernel(const StreamGroup g) {
     ld_scale = L.scale;
     ld_bias_voff = (uint32_t)((ob + 4 <= L.O ? ob : L.O - 4) * 4);
     // The tiles that share the tile's X rows (same tokens, other out-features) run on the same XCD at the
-    // same time; each starts at its own K step and wraps around, so they ask for different slices of those rows
-    // at any moment and find the others' slices in L2 instead of missing on them together.
-    ld_wrap = ld_nk - (int)((unsigned)o_tile % (unsigned)ld_nk);  // steps until the walk wraps to K step 0
+    // same time, and so do a few that share its W rows (same out-features, other tokens); each starts at its
+    // own K step and wraps around, so they ask for different slices of those rows at any moment and find the
+    // others' slices in L2 instead of missing on them together.
+    ld_wrap = ld_nk - (int)((unsigned)(o_tile + (int)(t_lo / C::BT)) % (unsigned)ld_nk);  // steps until the walk wraps to K step 0
     const int64_t k0 = ld_nk - ld_wrap;
     ld_x += k0 * C::X_ROWB;
     ld_w += k0 * 1024;
