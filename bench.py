@@ -69,9 +69,9 @@ def ceiling_ms(L):
     return max(math, hbm) * 1e3
 
 
-def measured_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None
-    when the kernel source has changed since the counters were taken."""
+def measured_traffic(schedule):
+    """HBM bytes per launch of the dominant kernel, in the given launch schedule, from the committed rocprofv3
+    counter summary, or None when the kernel source has changed since the counters were taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_deit_b256.txt")
     src = os.path.join(ROOT, "paper_2409_09708_amd", "csrc", "nm_spmm.hip")
@@ -82,8 +82,9 @@ def measured_traffic():
         return None
     if f"nm_spmm.hip {now}" not in text:
         return None
+    key = "sparse_gemm_hbm_bytes_per_launch_" + ("batched" if schedule == "batched" else "single")
     for line in text.splitlines():
-        if line.startswith("sparse_gemm_hbm_bytes_per_launch"):
+        if line.startswith(key + " "):
             return int(line.split()[1])
     return None
 
@@ -208,37 +209,68 @@ def main():
     useful = sum(L.useful_flops for L in layers)
     dense = sum(L.dense_flops for L in layers)
 
-    # ---- per-kernel durations with HIP events on the launch stream: a second pass over the same step with
-    # events around the batched pack and around every product launch
+    # ---- kernel durations with HIP events on the launch stream: a second pass over the same step with events
+    # around the batched pack and around every product launch.  In the batched schedule the library launches the
+    # persistent kernel once per operand form; the pass hands it the two groups one after the other, so each event
+    # pair brackets exactly one kernel.  Otherwise (and for the per-layer report) every layer is its own launch.
     reps = max(3, min(args.steps, 10))
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
-          for _ in range(reps)]
+    sp = [j for j, L in enumerate(layers) if L.N <= 2]
+    dn = [j for j, L in enumerate(layers) if L.N > 2]
+    sp_useful = sum(layers[j].useful_flops for j in sp)
     pk = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for r in range(reps):
-        pk[r][0].record(stream)
-        nm.nm_pack_prepare_batched(pack_args, stream=stream, out=packed, workspaces=workspaces)
-        pk[r][1].record(stream)
-        for j, (L, (v, i), X, Y, ws) in enumerate(zip(layers, packed, Xs, Ys, workspaces)):
-            ev[r][j][0].record(stream)
-            nm.nm_linear_forward_prepared(v, i, L.K, L.N, L.M, X, ws, out=Y, stream=stream)
-            ev[r][j][1].record(stream)
-    torch.cuda.synchronize()
-    layer_ms = [float(np.median([ev[r][j][0].elapsed_time(ev[r][j][1]) for r in range(reps)])) for j in range(len(layers))]
+    layer_ms = None
+    if args.schedule == "batched":
+        entries = [(v, i, L.K, L.N, L.M, X, ws, None, Y) for L, (v, i), X, Y, ws in zip(layers, packed, Xs, Ys, workspaces)]
+        descs_sp = nm.forward_descs([entries[j] for j in sp])
+        descs_dn = nm.forward_descs([entries[j] for j in dn])
+        gv = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+        for r in range(reps):
+            pk[r][0].record(stream)
+            nm.nm_pack_prepare_batched(pack_args, stream=stream, out=packed, workspaces=workspaces)
+            pk[r][1].record(stream)
+            gv[r][0].record(stream)
+            nm.nm_linear_forward_prepared_batched(descs_sp, stream=stream)
+            gv[r][1].record(stream)
+            nm.nm_linear_forward_prepared_batched(descs_dn, stream=stream)
+            gv[r][2].record(stream)
+        torch.cuda.synchronize()
+        sp_ms = float(np.median([g[0].elapsed_time(g[1]) for g in gv]))
+        dn_ms = float(np.median([g[1].elapsed_time(g[2]) for g in gv]))
+        sp_launches = 1
+    if args.schedule != "batched" or args.report:
+        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+              for _ in range(reps)]
+        for r in range(reps):
+            if args.schedule != "batched":
+                pk[r][0].record(stream)
+            nm.nm_pack_prepare_batched(pack_args, stream=stream, out=packed, workspaces=workspaces)
+            if args.schedule != "batched":
+                pk[r][1].record(stream)
+            for j, (L, (v, i), X, Y, ws) in enumerate(zip(layers, packed, Xs, Ys, workspaces)):
+                ev[r][j][0].record(stream)
+                nm.nm_linear_forward_prepared(v, i, L.K, L.N, L.M, X, ws, out=Y, stream=stream)
+                ev[r][j][1].record(stream)
+        torch.cuda.synchronize()
+        layer_ms = [float(np.median([ev[r][j][0].elapsed_time(ev[r][j][1]) for r in range(reps)]))
+                    for j in range(len(layers))]
+        if args.schedule != "batched":
+            sp_ms = sum(layer_ms[j] for j in sp)
+            dn_ms = sum(layer_ms[j] for j in dn)
+            sp_launches = len(sp)
     pack_ms = float(np.median([a.elapsed_time(b) for a, b in pk]))
 
-    # dominant kernel: the sparse matrix-core product (levels with N <= 2): 36 of the 48 launches per step
-    sp = [j for j, L in enumerate(layers) if L.N <= 2]
-    sp_useful = sum(layers[j].useful_flops for j in sp)
-    sp_ms = sum(layer_ms[j] for j in sp)
+    # dominant kernel: the sparse matrix-core product (the 36 layers with N <= 2): one launch for all of them in
+    # the batched schedule, one per layer otherwise
     achieved = sp_useful / (sp_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_DENSE_TFLOPS, "traffic": measured_traffic(),
-                "kernel": "nm_stream_kernel<sparse> (v_smfmac_f32_16x16x64_bf16); useful FLOPs 2*T*O*K*N/M per launch, "
-                          "averaged over the 36 launches per step with N <= 2",
-                "launches_per_step": len(sp), "avg_launch_ms": sp_ms / len(sp),
-                "useful_flops_per_launch": sp_useful / len(sp),
+                "frac": achieved / PEAK_BF16_DENSE_TFLOPS, "traffic": measured_traffic(args.schedule),
+                "kernel": "nm_stream_kernel<sparse> (v_smfmac_f32_16x16x64_bf16); useful FLOPs 2*T*O*K*N/M summed over the "
+                          f"{len(sp)} layers with N <= 2, {sp_launches} launch(es) per step",
+                "launches_per_step": sp_launches, "avg_launch_ms": sp_ms / sp_launches,
+                "useful_flops_per_launch": sp_useful / sp_launches,
                 "dense_equivalent_tflops": sum(layers[j].dense_flops for j in sp) / (sp_ms * 1e-3) / 1e12,
-                "algorithmic_hbm_bytes_per_launch": sum(algorithmic_bytes(layers[j]) for j in sp) / len(sp)}
+                "algorithmic_hbm_bytes_per_launch": sum(algorithmic_bytes(layers[j]) for j in sp) / sp_launches,
+                "dense_form_kernel_ms_per_step": dn_ms}
 
     # ---- nested levels (ranks inside groups): rank the 48 weights once for their M, then take each layer's
     # level from the ranks.  Streaming kernels: algorithmic bytes = 2 read + 1/2 written per weight for the
@@ -351,7 +383,7 @@ def main():
         log(f"nested levels: rank 48 matrices {rank_ms:.3f} ms ({nested['rank']['roofline']['achieved']:.0f} GB/s), "
             f"pack from ranks {pr_ms:.3f} ms ({nested['pack_ranked']['roofline']['achieved']:.0f} GB/s)")
         log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}{'% of ceiling':>14}")
-        for L, ms in zip(layers, layer_ms):
+        for L, ms in zip(layers, layer_ms or []):
             u = L.useful_flops / ms / 1e9
             log(f"{L.name:<12}{L.N:>3}:{L.M:<3}{ms:>8.3f}{u:>13.1f}{L.dense_flops / ms / 1e9:>15.1f}{100 * u / PEAK_BF16_DENSE_TFLOPS:>12.1f}%"
                 f"{100 * ceiling_ms(L) / ms:>13.1f}%")
