@@ -191,7 +191,8 @@ int32_t nm_pack_ranked(const nm_bf16* W, const uint8_t* rank, int64_t O, int64_t
  *                    aligned; may be NULL when that size is 0.  Its contents are undefined
  *                    after the call; concurrent calls need distinct workspaces.
  * The matrix-core kernels need K % 64 == 0, 16-byte aligned X, values and Y and ldx, ldy
- * multiples of 8; other shapes run a slower general kernel with the same results.
+ * multiples of 8; other shapes run a slower general kernel with the same results.  Rows of X and Y
+ * that start on 128-byte boundaries (ldx, ldy multiples of 64) are fastest.
  */
 int32_t nm_spmm(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K,
                 int32_t N, int32_t M, const nm_bf16* X, int64_t T, int64_t ldx,
