@@ -276,17 +276,15 @@ def main():
     # level from the ranks.  Streaming kernels: algorithmic bytes = 2 read + 1/2 written per weight for the
     # ranking; 2.5 read + packed bytes written for the ranked pack.
     ranks = [torch.empty((L.O, L.K // 2), dtype=torch.uint8, device=dev) for L in layers]
-    lib = nm.load_library()
-    sh = int(stream.cuda_stream)
-
     rank_args = [(W, L.M) for W, L in zip(Ws, layers)]
 
     def rank_all():
         nm.nm_rank_batched(rank_args, stream=stream, out=ranks)
 
+    ranked_args = [(W, r, L.N, L.M) for W, r, L in zip(Ws, ranks, layers)]
+
     def pack_ranked_all():
-        for W, L, r, (v, i) in zip(Ws, layers, ranks, packed):
-            lib.nm_pack_ranked(W.data_ptr(), r.data_ptr(), L.O, L.K, L.K, L.N, L.M, v.data_ptr(), i.data_ptr(), sh)
+        nm.nm_pack_ranked_batched(ranked_args, stream=stream, out=packed)
 
     def timed(fn):
         fn()
@@ -301,7 +299,7 @@ def main():
     n_weights = sum(L.O * L.K for L in layers)
     packed_bytes = sum(v.numel() * 2 + i.numel() * 4 for v, i in packed)
     rank_ms, pr_ms = timed(rank_all), timed(pack_ranked_all)
-    nested = {"workload": "48 DeiT-B weight matrices: ranking in one launch, ranked packing one launch per matrix",
+    nested = {"workload": "48 DeiT-B weight matrices: ranking in one launch, packing from the ranks in one launch",
               "rank": {"ms": rank_ms, "algorithmic_bytes": 2.5 * n_weights,
                        "roofline": {"bound": "hbm", "achieved": 2.5 * n_weights / rank_ms / 1e6, "peak": 8000.0,
                                     "unit": "GB/s", "frac": 2.5 * n_weights / rank_ms / 1e6 / 8000.0}},
@@ -375,11 +373,34 @@ def main():
                          "frac": q_tops / PEAK_INT8_DENSE_TOPS}}
     del q_masks, q_w, q_x, q_scale, q_ws
 
+    # ---- context, not part of the path: the vendor library's dense bf16 product (torch.matmul) on the same four
+    # shapes with unpruned weights, i.e. what the block costs without any sparsity
+    try:
+        def dense_library():
+            for j in train_layers:
+                torch.matmul(Xs[j], Ws[j].t(), out=Ys[j])
+
+        lib_ms = timed(dense_library)
+        sparse_block_ms = None
+        if layer_ms:
+            sparse_block_ms = sum(layer_ms[j] for j in train_layers)
+        dense_library_reference = {
+            "workload": "torch.matmul (vendor dense bf16 GEMM) on the four products of one DeiT-B block at batch 256, "
+                        "unpruned weights, bf16 out",
+            "ms": lib_ms, "tflops": block_flops / lib_ms / 1e9}
+        if sparse_block_ms:
+            dense_library_reference["this_library_block_ms_at_seed0_levels"] = sparse_block_ms
+    except Exception as e:  # the comparison is optional
+        dense_library_reference = {"error": str(e)[:200]}
+
     if args.report:
         log(f"training products of one block: dX {dx_ms:.3f} ms ({training['input_gradient']['roofline']['achieved']:.0f} "
             f"TFLOP/s), dW {dw_ms:.3f} ms ({training['weight_gradient']['roofline']['achieved']:.0f} TFLOP/s)")
         log(f"int8 products of one block: {q_ms:.3f} ms ({q_tops:.0f} useful TOP/s, "
             f"{int8['dense_equivalent_tops']:.0f} dense-equivalent)")
+        if "ms" in dense_library_reference:
+            log(f"for scale, the vendor library's dense bf16 product on the block's four shapes: "
+                f"{dense_library_reference['ms']:.3f} ms ({dense_library_reference['tflops']:.0f} TFLOP/s)")
         log(f"nested levels: rank 48 matrices {rank_ms:.3f} ms ({nested['rank']['roofline']['achieved']:.0f} GB/s), "
             f"pack from ranks {pr_ms:.3f} ms ({nested['pack_ranked']['roofline']['achieved']:.0f} GB/s)")
         log(f"{'layer':<12}{'N:M':>6}{'ms':>9}{'useful TF/s':>13}{'dense-eq TF/s':>15}{'% bf16 peak':>13}{'% of ceiling':>14}")
@@ -419,6 +440,7 @@ def main():
         "nested_levels": nested,
         "training_products": training,
         "int8_products": int8,
+        "dense_library_reference": dense_library_reference,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -178,6 +178,18 @@ int32_t nm_rank_mask(const uint8_t* rank, int64_t O, int64_t K, int32_t N, int32
                      void* stream);
 int32_t nm_pack_ranked(const nm_bf16* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int32_t N,
                        int32_t M, nm_bf16* values, uint32_t* indices, void* stream);
+/* One nm_pack_ranked per descriptor (W contiguous, ldw = K), in a single launch where the shapes and levels
+ * allow: after the ranks of a supernet's layers are written, a sampled configuration (one level per layer,
+ * Section 3.1) is packed from them in one go.  descs is a HOST array, read before the call returns. */
+typedef struct nm_pack_ranked_desc {
+  const nm_bf16* W;    /* device, [O, K] contiguous */
+  const uint8_t* rank; /* device, nm_rank_bytes(O, K) bytes written by nm_rank(W, M) */
+  nm_bf16* values;     /* device, out */
+  uint32_t* indices;   /* device, out */
+  int64_t O, K;
+  int32_t N, M;
+} nm_pack_ranked_desc;
+int32_t nm_pack_ranked_batched(const nm_pack_ranked_desc* descs, int32_t count, void* stream);
 
 /*
  * nm_spmm -- Y = X * W_s^T from the packed weight (Fig. 2, lower part):

@@ -21,7 +21,7 @@ EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
-    "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_prepare_batched",
+    "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_ranked_batched", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
     "nm_backward_input_workspace_bytes", "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
     "nm_linear_forward_prepared_batched", "nm_prune_scored", "nm_i8_workspace_bytes", "nm_linear_forward_i8", "nm_i8_prepare", "nm_linear_forward_i8_prepared",
@@ -36,6 +36,11 @@ class NmError(RuntimeError):
 
 class PackDesc(ctypes.Structure):
     _fields_ = [("W", c_void_p), ("values", c_void_p), ("indices", c_void_p),
+                ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32)]
+
+
+class PackRankedDesc(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("rank", c_void_p), ("values", c_void_p), ("indices", c_void_p),
                 ("O", c_int64), ("K", c_int64), ("N", c_int32), ("M", c_int32)]
 
 
@@ -123,6 +128,8 @@ def load_library() -> ctypes.CDLL:
     lib.nm_pack_ranked.restype = c_int32
     lib.nm_pack_ranked.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p,
                                    c_void_p]
+    lib.nm_pack_ranked_batched.restype = c_int32
+    lib.nm_pack_ranked_batched.argtypes = [ctypes.POINTER(PackRankedDesc), c_int32, c_void_p]
     lib.nm_backward_weight_workspace_bytes.restype = c_size_t
     lib.nm_backward_weight_workspace_bytes.argtypes = [c_int64, c_int64, c_int64]
     lib.nm_linear_backward_input.restype = c_int32
@@ -331,6 +338,24 @@ def nm_pack_ranked(W, rank, N: int, M: int, stream=None):
     _check(load_library().nm_pack_ranked(W.data_ptr(), rank.data_ptr(), O, K, ldw, N, M, values.data_ptr(),
                                          indices.data_ptr(), _stream_handle(stream)))
     return values, indices
+
+
+def nm_pack_ranked_batched(layers: Sequence[Tuple[object, object, int, int]], stream=None, out=None):
+    """One launch for many (W, rank, N, M); returns [(values, indices), ...]."""
+    torch = _torch()
+    descs = (PackRankedDesc * len(layers))()
+    outs: List[Tuple[object, object]] = []
+    for i, (W, rank, N, M) in enumerate(layers):
+        _need(W, torch.bfloat16, "W")
+        if not W.is_contiguous():
+            raise ValueError("nm_pack_ranked_batched needs contiguous weights")
+        O, K = int(W.shape[0]), int(W.shape[1])
+        _need_rank(rank, O, K)
+        values, indices = out[i] if out is not None else _empty_packed(O, K, N, M, W.device)
+        outs.append((values, indices))
+        descs[i] = PackRankedDesc(W.data_ptr(), rank.data_ptr(), values.data_ptr(), indices.data_ptr(), O, K, N, M)
+    _check(load_library().nm_pack_ranked_batched(descs, len(layers), _stream_handle(stream)))
+    return outs
 
 
 def nm_pack(W, N: int, M: int, mask=None, stream=None):

@@ -168,6 +168,20 @@ int32_t nm_pack_ranked(const nm_bf16* W, const uint8_t* rank, int64_t O, int64_t
   return device_status(nm::launch_pack_ranked(W, rank, O, K, ldw, N, M, values, indices, (hipStream_t)stream));
 }
 
+int32_t nm_pack_ranked_batched(const nm_pack_ranked_desc* descs, int32_t count, void* stream) {
+  if (!descs) return NM_ERR_NULL;
+  if (count <= 0) return NM_ERR_SHAPE;
+  static_assert(sizeof(nm_pack_ranked_desc) == sizeof(nm::PackRankedDesc), "descriptor layouts must match");
+  for (int32_t i = 0; i < count; ++i) {
+    const nm_pack_ranked_desc& d = descs[i];
+    if (!d.W || !d.rank || !d.values || !d.indices) return NM_ERR_NULL;
+    if (int32_t s = check_weight(d.O, d.K, d.N, d.M)) return s;
+    if (!aligned(d.W, 2) || !aligned(d.values, 2) || !aligned(d.indices, 4)) return NM_ERR_ALIGN;
+  }
+  return device_status(nm::launch_pack_ranked_batched(reinterpret_cast<const nm::PackRankedDesc*>(descs), count,
+                                                      (hipStream_t)stream));
+}
+
 int32_t nm_mask_check(const uint32_t* mask, int64_t O, int64_t K, int32_t N, int32_t M, uint32_t* bad_groups,
                       void* stream) {
   if (!mask || !bad_groups) return NM_ERR_NULL;

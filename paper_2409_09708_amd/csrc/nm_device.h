@@ -90,14 +90,14 @@ __device__ __forceinline__ uint32_t legalize_mask(uint32_t bits, int N, int M, u
 // K step) as one contiguous kilobyte.
 //   values (2:4 form, a step = 32 compressed values = 64 dense k) or dense weights (a step = 32 weights):
 //     block (row/16, step) at ((row/16) * nk + step) * 1024; inside it the 16-byte piece `chunk` (0..3) of
-//     row r = row % 16 at (4 r + (chunk ^ (r/4 % 4))) * 16  (the XOR is the LDS swizzle)
+//     row r = row % 16 at (4 r + (chunk ^ (r/2 % 4))) * 16  (the XOR is the LDS swizzle)
 //   selectors of the 2:4 form: block (row/256, step) of 2 KiB; rows r and r+16 of a 32-row pair share the
 //     32-bit word of (r % 16, chunk): low half = the first row's 16 selector bits of that chunk, high half
 //     = the second row's, which is what the matrix instruction's ABID modifier selects
 // ---------------------------------------------------------------------------------------------
 __host__ __device__ __forceinline__ int64_t stream_piece_offset(int64_t row, int64_t step, int chunk, int64_t nk) {
   const int r = (int)(row & 15);
-  return (((row >> 4) * nk + step) << 10) + ((r * 4 + (chunk ^ ((r >> 2) & 3))) << 4);
+  return (((row >> 4) * nk + step) << 10) + ((r * 4 + (chunk ^ ((r >> 1) & 3))) << 4);
 }
 __host__ __device__ __forceinline__ int64_t stream_selector_offset(int64_t row, int64_t step, int chunk, int64_t nk) {
   const int r = (int)(row & 255);

@@ -161,9 +161,9 @@ nm_tgemm_kernel(const TGemmArgs a) {
       q_col[d] = (uint32_t)(piece * 16);
     } else {
       // [BJ rows j][32 reduction indices]: 64 bytes per row, load n covers rows 16n .. 16n+15, lane ->
-      // (row 16n + lane / 4, slot lane % 4), the slot holds piece slot ^ ((row >> 2) & 3)
+      // (row 16n + lane / 4, slot lane % 4), the slot holds piece slot ^ ((row >> 1) & 3)
       int64_t row = 16 * n + (lane >> 2);
-      const int piece = (lane & 3) ^ (int)((row >> 2) & 3);
+      const int piece = (lane & 3) ^ (int)((row >> 1) & 3);
       if (row > q_last_row) row = q_last_row;
       q_row[d] = (int)row;
       q_col[d] = (uint32_t)(piece * 16);
@@ -230,7 +230,7 @@ nm_tgemm_kernel(const TGemmArgs a) {
         qf[j] = read_transposed<C::Q_ROWB>(base + C::P_BYTES, wj * JT + j, c16, kb);
       } else {
         const int row = (wj * JT + j) * 16 + c16;
-        qf[j] = *reinterpret_cast<const u32x4_t*>(base + C::P_BYTES + row * 64 + ((kb ^ ((c16 >> 2) & 3)) << 4));
+        qf[j] = *reinterpret_cast<const u32x4_t*>(base + C::P_BYTES + row * 64 + ((kb ^ ((c16 >> 1) & 3)) << 4));
       }
     }
   };

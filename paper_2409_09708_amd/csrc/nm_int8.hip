@@ -231,7 +231,7 @@ nm_i8_gemm_kernel(const I8Args a) {
     const int j = (wave + i * C::NW) % C::A_LOADS;
     int64_t row;
     int c;
-    if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 2) & 3); }
+    if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 1) & 3); }
     else { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (int)(row & 7); }
     if (row > o_last) row = o_last;
     a_voff[i] = (uint32_t)(row * a_ld + c * 16);
@@ -278,7 +278,7 @@ nm_i8_gemm_kernel(const I8Args a) {
   const int x_sw = r16 & 7;
   const int x_row = (wt * TT * 16 + r16) * 128;
   const int a_row = C::X_BYTES + (wo * OT * 16 + r16) * C::A_ROWB;
-  const int a_sw = SPARSE ? ((r16 >> 2) & 3) : (r16 & 7);
+  const int a_sw = SPARSE ? ((r16 >> 1) & 3) : (r16 & 7);
   const int s_row = C::X_BYTES + C::A_BYTES + (wo * OT * 16 + r16) * 16 + kb * 4;
 
   constexpr int H = C::H;

@@ -15,6 +15,14 @@ struct PackDesc {
   int64_t O, K;
   int32_t N, M;
 };
+struct PackRankedDesc {
+  const bf16_t* W;
+  const uint8_t* rank;
+  bf16_t* values;
+  uint32_t* indices;
+  int64_t O, K;
+  int32_t N, M;
+};
 
 // nm_pack.hip
 hipError_t launch_prune(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N, int M, uint32_t* mask,
@@ -36,6 +44,7 @@ struct LayerDesc {
 hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStream_t s, bool* workspace_short);
 hipError_t launch_unpack(const bf16_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M,
                          bf16_t* Wd, int64_t ldw, hipStream_t s);
+hipError_t launch_pack_ranked_batched(const PackRankedDesc* descs, int count, hipStream_t s);
 hipError_t launch_pack_ranked(const bf16_t* W, const uint8_t* rank, int64_t O, int64_t K, int64_t ldw, int N, int M,
                               bf16_t* values, uint32_t* indices, hipStream_t s);
 hipError_t launch_mask_check(const uint32_t* mask, int64_t O, int64_t K, int N, int M, uint32_t* bad, hipStream_t s);

@@ -231,11 +231,13 @@ struct BatchEntry {
   bf16_t* values;
   uint32_t* indices;
   unsigned char* stream_ws;  // NULL, or where the product kernel's operand order is written as well
+  const uint32_t* rank;      // stored ranks the selection is read from (the ranked launch), else unused
   int64_t n_chunks;
   int64_t K;
   uint32_t block_end;  // exclusive prefix end, in blocks
   uint16_t N, M;
 };
+static_assert(sizeof(BatchEntry) == 64, "descriptor size");
 constexpr int kBatchMax = 56;  // 56 * 64 bytes of descriptors ride in the kernel arguments
 struct BatchArgs {
   BatchEntry e[kBatchMax];
@@ -252,6 +254,7 @@ struct BatchArgs {
 // levels go through per-matrix launches.
 #define NM_FOR_EACH_BATCH_LEVEL(X) X(1, 4) X(2, 4) X(1, 8) X(2, 8) X(4, 8) X(1, 16) X(2, 16) X(4, 16)
 
+template <int SRC>  // 0: selection by magnitude, 2: from stored ranks
 __global__ void __launch_bounds__(kPackThreads) pack_batched_kernel(const BatchArgs args) {
   __shared__ uint32_t sbits[kSbitsWords];
   int m = 0;
@@ -263,8 +266,8 @@ __global__ void __launch_bounds__(kPackThreads) pack_batched_kernel(const BatchA
   switch (level) {
 #define X(n, mm)                                                                                      \
   case n * 32 + mm:                                                                                   \
-    code_block<n, mm, false>(d.W, d.n_chunks, chunk0, nullptr, d.values, d.indices, nullptr, nullptr, \
-                             sbits, d.stream_ws, d.K);                                                \
+    code_block<n, mm, SRC>(d.W, d.n_chunks, chunk0, SRC ? d.rank : nullptr, d.values, d.indices, nullptr, \
+                           nullptr, sbits, d.stream_ws, d.K);                                         \
     break;
     NM_FOR_EACH_BATCH_LEVEL(X)
 #undef X
@@ -515,7 +518,7 @@ hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s) 
   uint64_t blocks = 0;
   auto flush = [&]() {
     if (args.count) {
-      hipLaunchKernelGGL(pack_batched_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, s, args);
+      hipLaunchKernelGGL(pack_batched_kernel<0>, dim3((unsigned)blocks), dim3(kPackThreads), 0, s, args);
       args.count = 0;
       blocks = 0;
     }
@@ -533,7 +536,40 @@ hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s) 
     if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
     BatchEntry& e = args.e[args.count++];
     e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
-    e.stream_ws = nullptr; e.K = d.K;
+    e.stream_ws = nullptr; e.rank = nullptr; e.K = d.K;
+    blocks += nb;
+    e.block_end = (uint32_t)blocks;
+    e.N = (uint16_t)d.N; e.M = (uint16_t)d.M;
+  }
+  flush();
+  return hipGetLastError();
+}
+
+// nm_pack_ranked for many matrices: one launch for those the fast kernel takes, own launches for the rest
+hipError_t launch_pack_ranked_batched(const PackRankedDesc* descs, int count, hipStream_t s) {
+  BatchArgs args;
+  args.count = 0;
+  uint64_t blocks = 0;
+  auto flush = [&]() {
+    if (args.count) {
+      hipLaunchKernelGGL(pack_batched_kernel<2>, dim3((unsigned)blocks), dim3(kPackThreads), 0, s, args);
+      args.count = 0;
+      blocks = 0;
+    }
+  };
+  for (int i = 0; i < count; ++i) {
+    const PackRankedDesc& d = descs[i];
+    if (!(batch_level(d.N, d.M) && flat_ok(d.O, d.K, d.K, d.N, d.M, d.W, d.rank, d.values, d.indices, nullptr))) {
+      hipError_t e = launch_pack_ranked(d.W, d.rank, d.O, d.K, d.K, d.N, d.M, d.values, d.indices, s);
+      if (e != hipSuccess) return e;
+      continue;
+    }
+    const int64_t n_chunks = d.O * d.K / kChunk;
+    const uint64_t nb = blocks_for(n_chunks, kPackThreads);
+    if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
+    BatchEntry& e = args.e[args.count++];
+    e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
+    e.stream_ws = nullptr; e.rank = reinterpret_cast<const uint32_t*>(d.rank); e.K = d.K;
     blocks += nb;
     e.block_end = (uint32_t)blocks;
     e.N = (uint16_t)d.N; e.M = (uint16_t)d.M;
@@ -560,7 +596,7 @@ hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStr
   uint64_t blocks = 0;
   auto flush = [&]() {
     if (args.count) {
-      hipLaunchKernelGGL(pack_batched_kernel, dim3((unsigned)blocks), dim3(kPackThreads), 0, s, args);
+      hipLaunchKernelGGL(pack_batched_kernel<0>, dim3((unsigned)blocks), dim3(kPackThreads), 0, s, args);
       args.count = 0;
       blocks = 0;
     }
@@ -577,6 +613,7 @@ hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStr
       BatchEntry& e = args.e[args.count++];
       e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
       e.stream_ws = fused ? reinterpret_cast<unsigned char*>(d.workspace) : nullptr;
+      e.rank = nullptr;
       e.K = d.K;
       blocks += nb;
       e.block_end = (uint32_t)blocks;

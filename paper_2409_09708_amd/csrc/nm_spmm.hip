@@ -302,7 +302,7 @@ nm_gemm_kernel(const GemmArgs a) {
     const int j = (wave + i * C::NW) % C::A_LOADS;
     int64_t row;
     int c;
-    if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 2) & 3); }
+    if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 1) & 3); }
     else { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (int)(row & 7); }
     if (row > o_last) row = o_last;
     a_voff[i] = (uint32_t)((row * a_ld + c * 8) * 2);
@@ -352,7 +352,7 @@ nm_gemm_kernel(const GemmArgs a) {
   const int x_sw = r16 & 7;
   const int x_row = (wt * TT * 16 + r16) * 128;
   const int a_row = C::X_BYTES + (wo * OT * 16 + r16) * C::A_ROWB;
-  const int a_sw = SPARSE ? ((r16 >> 2) & 3) : (r16 & 7);
+  const int a_sw = SPARSE ? ((r16 >> 1) & 3) : (r16 & 7);
   const int s_row = C::X_BYTES + C::A_BYTES + (wo * OT * 16 + r16) * 8 + (kb >> 1) * 4;
 
   // One sub-step = 32 matrix instructions per wave.  SPARSE: a stage is one sub-step (K = 64 through
@@ -595,7 +595,7 @@ nm_stream_kernel(const StreamGroup g) {
       const int j = wave + i * C::NW;
       int row, c;
       if (SPARSE) { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (row & 7); }
-      else { row = 16 * j + (lane >> 2); c = (lane & 3) ^ ((row >> 2) & 3); }
+      else { row = 16 * j + (lane >> 2); c = (lane & 3) ^ ((row >> 1) & 3); }
       x_voff[i] = (uint32_t)((int64_t)row * ldx * C::ES + c * 16);
     }
 #pragma unroll
@@ -723,9 +723,9 @@ nm_stream_kernel(const StreamGroup g) {
   using bfrag_t = std::conditional_t<SPARSE, u32x8_t, u32x4_t>;
   struct FragAddr { uint32_t a, s, xlo, xhi; };  // byte offsets into the dynamic LDS
   FragAddr at0;
-  at0.a = (uint32_t)(C::X_BYTES + (wo * C::OW + r16) * C::A_ROWB + ((kb ^ ((r16 >> 2) & 3)) * 16));
+  at0.a = (uint32_t)(C::X_BYTES + (wo * C::OW + r16) * C::A_ROWB + ((kb ^ ((r16 >> 1) & 3)) * 16));
   at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (I8 ? wo * OT : wo * C::OW / 32) * 256 + r16 * 16 + kb * 4);
-  at0.xlo = (uint32_t)((wt * 128 + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 2) & 3)) * 16)));
+  at0.xlo = (uint32_t)((wt * 128 + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 1) & 3)) * 16)));
   at0.xhi = (uint32_t)((wt * 128 + r16) * C::X_ROWB + ((4 + kb) ^ (r16 & 7)) * 16);
   auto frag_addr = [&](uint32_t stage_off) {
     return FragAddr{at0.a + stage_off, at0.s + stage_off, at0.xlo + stage_off, at0.xhi + stage_off};

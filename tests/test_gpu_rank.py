@@ -95,6 +95,27 @@ def test_rank_batched_equals_single_calls():
         assert np.array_equal(host_bytes(r), orc.rank_nibbles(orc.nm_rank(host_bits(w), M))), (O, K, M)
 
 
+def test_pack_ranked_batched_equals_the_oracle_and_single_calls():
+    # a sampled configuration packed from stored ranks in one call: fast-kernel shapes at the sampler's levels,
+    # a level outside the batched kernel's set (3:8), a shape the fast kernel does not take (own launches),
+    # and more matrices than one launch's table holds
+    rng = np.random.default_rng(4400)
+    specs = [(768, 768, 2, 4), (2304, 768, 1, 8), (301, 384, 4, 16), (23, 40, 2, 8), (3072, 768, 1, 16),
+             (64, 128, 3, 8), (768, 3072, 4, 8), (128, 64, 1, 4), (96, 256, 2, 16)]
+    specs += [(32 + 16 * (i % 3), 64, (1, 2)[i % 2], (4, 8, 16)[i % 3]) for i in range(60)]
+    Wn = [wl.tie_heavy_weights(rng, O, K) if i % 2 else wl.draw_weights(rng, O, K)
+          for i, (O, K, _, _) in enumerate(specs)]
+    Ws = [dev_bf16(w) for w in Wn]
+    ranks = nm.nm_rank_batched([(w, M) for w, (_, _, _, M) in zip(Ws, specs)])
+    outs = nm.nm_pack_ranked_batched([(w, r, N, M) for w, r, (_, _, N, M) in zip(Ws, ranks, specs)])
+    for n, (w, wd, r, (O, K, N, M), (v, i)) in enumerate(zip(Wn, Ws, ranks, specs, outs)):
+        v1, i1 = nm.nm_pack_ranked(wd, r, N, M)
+        assert torch.equal(v.view(torch.int16), v1.view(torch.int16)) and torch.equal(i, i1), (O, K, N, M)
+        if n < 12:
+            vals, idx = orc.nm_pack(w, orc.nm_mask(w, N, M), N, M)
+            assert np.array_equal(host_bits(v), vals) and np.array_equal(host_words(i), idx), (O, K, N, M)
+
+
 @pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (3, 8), (4, 8), (4, 16), (16, 16)])
 def test_mask_from_a_supplied_saliency(N, M):
     # Section 3.1: any saliency may rank the weights.  Random scores with many ties, signed zeros, infinities and

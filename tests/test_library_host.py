@@ -151,6 +151,24 @@ def test_pack_batched_argument_errors(lib):
     assert lib.nm_pack_batched(d, 2, None) == 2
 
 
+def test_pack_ranked_batched_argument_errors(lib):
+    assert lib.nm_pack_ranked_batched(None, 1, None) == 1
+    d = (binding.PackRankedDesc * 2)()
+    d[0] = binding.PackRankedDesc(FAKE, FAKE, FAKE, FAKE, 4, 16, 2, 4)
+    d[1] = binding.PackRankedDesc(FAKE, FAKE, FAKE, FAKE, 4, 16, 2, 4)
+    assert lib.nm_pack_ranked_batched(d, 0, None) == 2
+    d[1] = binding.PackRankedDesc(FAKE, None, FAKE, FAKE, 4, 16, 2, 4)
+    assert lib.nm_pack_ranked_batched(d, 2, None) == 1
+    d[1] = binding.PackRankedDesc(FAKE, FAKE, FAKE, None, 4, 16, 2, 4)
+    assert lib.nm_pack_ranked_batched(d, 2, None) == 1
+    d[1] = binding.PackRankedDesc(FAKE, FAKE, FAKE, FAKE, 4, 16, 0, 4)
+    assert lib.nm_pack_ranked_batched(d, 2, None) == 3
+    d[1] = binding.PackRankedDesc(FAKE, FAKE, FAKE, FAKE, 4, 24, 1, 16)
+    assert lib.nm_pack_ranked_batched(d, 2, None) == 2
+    d[1] = binding.PackRankedDesc(FAKE, FAKE, FAKE, FAKE + 2, 4, 16, 2, 4)
+    assert lib.nm_pack_ranked_batched(d, 2, None) == 4
+
+
 def test_spmm_argument_errors(lib):
     ok = dict(values=FAKE, indices=FAKE, O=64, K=64, N=2, M=4, X=FAKE, T=16, ldx=64, Y=FAKE, ldy=64, dt=0,
               ws=None, wsb=0)
