@@ -44,7 +44,9 @@
  *   last HIP error code.  `stream` is a hipStream_t passed as void* (NULL = the null
  *   stream).  Calls validate their arguments on the host, enqueue their kernels on
  *   `stream` and return without synchronising.  Argument errors are reported before
- *   anything is launched, so they can be exercised without a GPU.
+ *   anything is launched, so they can be exercised without a GPU.  A call enqueues
+ *   kernels only (no copies, fills or allocations), so it may be issued on a stream that
+ *   is being captured into a graph; host descriptor arrays are read before it returns.
  *   No function throws, aborts or prints.
  */
 #ifndef NM_SPARSE_H
