@@ -751,15 +751,27 @@ nm_stream_kernel(const StreamGroup g) {
   };
 
   // ---- prologue: three stages in flight, the first one landed, its first fragments in registers
+  // A stage's loads leave in two parts: HEAD of them right after the barrier that frees the buffer (one after
+  // each of the step's last three groups), the others after the first groups of the next step.  The requests
+  // of the eight waves then reach the CU's one load path spread over the step instead of in one burst, behind
+  // which every wave's matrix instructions would queue (a wave issues in order).
+  constexpr int HEAD = 3, TAIL = C::LPW - HEAD;
+  static_assert(HEAD >= 1 && HEAD <= 3 && TAIL >= 0 && TAIL <= C::TT - 3, "the tail must be out before the next step's wait");
   cursor_tile(0);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s) {
-    [&]<int... D>(std::integer_sequence<int, D...>) {
-      (issue_one(std::integral_constant<int, D>{}, (uint32_t)(s * C::STAGE)), ...);
-    }(std::make_integer_sequence<int, C::LPW>{});
-    cursor_advance();
+    if (s + 1 < STAGES) {
+      [&]<int... D>(std::integer_sequence<int, D...>) {
+        (issue_one(std::integral_constant<int, D>{}, (uint32_t)(s * C::STAGE)), ...);
+      }(std::make_integer_sequence<int, C::LPW>{});
+      cursor_advance();
+    } else {  // the last one's tail leaves in the first step
+      [&]<int... D>(std::integer_sequence<int, D...>) {
+        (issue_one(std::integral_constant<int, D>{}, (uint32_t)(s * C::STAGE)), ...);
+      }(std::make_integer_sequence<int, HEAD>{});
+    }
   }
-  wait_loads_outstanding<(STAGES - 1) * C::LPW>();
+  wait_loads_outstanding<(STAGES - 2) * C::LPW + HEAD>();
   __builtin_amdgcn_s_barrier();
 
   u32x4_t afr[2][OT];  // W fragments of the current step and of the next one; the roles alternate
@@ -786,6 +798,7 @@ nm_stream_kernel(const StreamGroup g) {
     uint32_t nxt_off = cur_off + C::STAGE;
     if (nxt_off == (uint32_t)(STAGES * C::STAGE)) nxt_off = 0;
     at[PP ^ 1] = frag_addr(nxt_off);
+    const uint32_t prev_off = cur_off == 0 ? (uint32_t)((STAGES - 1) * C::STAGE) : cur_off - (uint32_t)C::STAGE;
     [&]<int... J>(std::integer_sequence<int, J...>) {
       ([&] {
         constexpr int j = J;
@@ -823,14 +836,13 @@ nm_stream_kernel(const StreamGroup g) {
                                                                   0, 0, 0);
           }(), ...);
         }(std::make_integer_sequence<int, OT>{});
-        if constexpr (j >= TT - 3) {
-          // this wave's loads of the stage three ahead, a third after each of the last three groups
-          constexpr int part = j - (TT - 3);
-          constexpr int lo = part * C::LPW / 3, hi = (part + 1) * C::LPW / 3;
-          [&]<int... D>(std::integer_sequence<int, D...>) {
-            (issue_one(std::integral_constant<int, lo + D>{}, cur_off), ...);
-          }(std::make_integer_sequence<int, hi - lo>{});
-          if constexpr (part == 2) cursor_advance();
+        if constexpr (j >= TT - HEAD) {
+          // the buffer this step has consumed is free: the head of this wave's loads of the stage that goes there
+          issue_one(std::integral_constant<int, j - (TT - HEAD)>{}, cur_off);
+        } else if constexpr (j < TAIL) {
+          // the tail of the stage begun in the previous step, into the buffer consumed there
+          issue_one(std::integral_constant<int, HEAD + j>{}, prev_off);
+          if constexpr (j == TAIL - 1) cursor_advance();
         }
         __builtin_amdgcn_sched_barrier(0);
       }(), ...);
