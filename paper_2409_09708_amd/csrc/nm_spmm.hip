@@ -751,12 +751,14 @@ nm_stream_kernel(const StreamGroup g) {
   };
 
   // ---- prologue: three stages in flight, the first one landed, its first fragments in registers
-  // A stage's loads leave in two parts: HEAD of them right after the barrier that frees the buffer (one after
-  // each of the step's last three groups), the others after the first groups of the next step.  The requests
-  // of the eight waves then reach the CU's one load path spread over the step instead of in one burst, behind
-  // which every wave's matrix instructions would queue (a wave issues in order).
-  constexpr int HEAD = 3, TAIL = C::LPW - HEAD;
-  static_assert(HEAD >= 1 && HEAD <= 3 && TAIL >= 0 && TAIL <= C::TT - 3, "the tail must be out before the next step's wait");
+  // A stage's loads leave one at a time, SPREAD groups apart, from the barrier that frees the buffer (after group
+  // TT-3) round to the groups before the next step's barrier: load d after group (TT - 3 + d SPREAD) mod TT.
+  // HEAD of them fall into the step that freed the buffer, the others into the next one.  The requests of the
+  // eight waves then reach the CU's one load path spread over the step instead of in one burst, behind which
+  // every wave's matrix instructions would queue (a wave issues in order).
+  constexpr int SPREAD = C::LPW <= 4 ? 2 : 1;
+  constexpr int HEAD = (3 + SPREAD - 1) / SPREAD;
+  static_assert(HEAD <= C::LPW && (C::LPW - 1) * SPREAD < C::TT, "the last load must be out before the next step's wait");
   cursor_tile(0);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s) {
@@ -836,13 +838,14 @@ nm_stream_kernel(const StreamGroup g) {
                                                                   0, 0, 0);
           }(), ...);
         }(std::make_integer_sequence<int, OT>{});
-        if constexpr (j >= TT - HEAD) {
-          // the buffer this step has consumed is free: the head of this wave's loads of the stage that goes there
-          issue_one(std::integral_constant<int, j - (TT - HEAD)>{}, cur_off);
-        } else if constexpr (j < TAIL) {
-          // the tail of the stage begun in the previous step, into the buffer consumed there
-          issue_one(std::integral_constant<int, HEAD + j>{}, prev_off);
-          if constexpr (j == TAIL - 1) cursor_advance();
+        {
+          // the load that leaves after this group, if any: into the buffer this step has consumed (free since the
+          // barrier), or the rest of the stage begun in the previous step into the buffer consumed there
+          constexpr int since = (j - (TT - 3) + TT) % TT;  // groups since the barrier
+          if constexpr (since % SPREAD == 0 && since / SPREAD < C::LPW) {
+            issue_one(std::integral_constant<int, since / SPREAD>{}, j >= TT - 3 ? cur_off : prev_off);
+            if constexpr (since / SPREAD == C::LPW - 1) cursor_advance();
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }(), ...);
