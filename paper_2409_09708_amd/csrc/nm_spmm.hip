@@ -1319,6 +1319,14 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
   hipError_t e = hipSuccess;
   auto flush = [&](StreamGroup& grp, bool sparse) {
     if (grp.count == 0) return hipSuccess;
+    // Deepest layers first (insertion sort, stable): the blocks take the list in order, so the launch then ends
+    // with the cheapest tiles and its last, partly filled round is as short as the list allows.
+    for (int i = 1; i < grp.count; ++i) {
+      const StreamLayer L = grp.layer[i];
+      int j = i;
+      for (; j > 0 && grp.layer[j - 1].nk < L.nk; --j) grp.layer[j] = grp.layer[j - 1];
+      grp.layer[j] = L;
+    }
     const hipError_t r = sparse ? launch_stream_group<true>(grp, s) : launch_stream_group<false>(grp, s);
     grp.count = 0; grp.n_tiles = 0;
     return r;
