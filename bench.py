@@ -132,7 +132,7 @@ def main():
                     help="also run one plain 256 MiB device copy (a known HBM traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        print("bench.py measures one GPU only: the library has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
 
     import torch

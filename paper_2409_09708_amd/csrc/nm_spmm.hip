@@ -257,18 +257,18 @@ __device__ __forceinline__ f32x4_t bias_init(const float* bias, int64_t o, int64
   return v;
 }
 
+// One tile of one layer; `block` is the block's number among the layer's blocks (a multiple of 8 of them, so
+// that block mod 8 is the XCD the block runs on).
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
-__global__ void __launch_bounds__(WO * WT * 64)
-nm_gemm_kernel(const GemmArgs a) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, unsigned char* smem) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   // XCD-aware tile order: consecutive block ids land on different XCDs (8 of them, each with its
   // own L2); give every XCD a contiguous range of tiles so that the blocks sharing an L2 share X rows.
   const int n_tiles = a.n_o_tiles * a.n_t_tiles;
   const int per_xcd = (n_tiles + 7) >> 3;
-  const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  const int tile = (int)(block & 7) * per_xcd + (int)(block >> 3);
   if (tile >= n_tiles) return;
   const int o_tile = tile % a.n_o_tiles;
   const int t_tile = tile / a.n_o_tiles;
@@ -459,6 +459,38 @@ nm_gemm_kernel(const GemmArgs a) {
   } else {
     write_wave_tile_elements<OT, TT>(lane, get, a.Y, a.ldy, row0, col0, a.T, a.O, a.out_bf16 != 0);
   }
+}
+
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
+__global__ void __launch_bounds__(WO * WT * 64)
+nm_gemm_kernel(const GemmArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  gemm_tile<SPARSE, WO, WT, OT, TT, STAGES>(a, blockIdx.x, smem);
+}
+
+// The tiles of many small layers of one operand form in one launch: products of a few tokens are a handful of
+// tiles each, far fewer than the chip has compute units, and independent ones fill it together.  A block finds
+// its layer in the running block counts (whole multiples of 8 per layer) by bisection.
+constexpr int kTileLayersMax = 36;
+struct GemmGroup {
+  int32_t count;
+  uint32_t block_end[kTileLayersMax];  // exclusive prefix ends, in blocks
+  GemmArgs layer[kTileLayersMax];
+};
+static_assert(sizeof(GemmGroup) <= 4096, "the table must fit the kernel argument segment");
+
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
+__global__ void __launch_bounds__(WO * WT * 64)
+nm_gemm_group_kernel(const GemmGroup g) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  int lo = 0, hi = g.count - 1;  // the first layer whose end lies beyond this block
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (blockIdx.x >= g.block_end[mid]) lo = mid + 1;
+    else hi = mid;
+  }
+  const unsigned first = lo ? g.block_end[lo - 1] : 0u;
+  gemm_tile<SPARSE, WO, WT, OT, TT, STAGES>(g.layer[lo], blockIdx.x - first, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1058,6 +1090,50 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Tiled kernel, many layers in one launch.  tile_group_append fills the table (false: full, launch it and retry;
+// a layer with more blocks than a grid holds never fits and is launched alone).
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
+static bool tile_group_append(GemmGroup& grp, GemmArgs g) {
+  using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+  g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
+  g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
+  const int64_t blocks = (((int64_t)g.n_o_tiles * g.n_t_tiles + 7) / 8) * 8;
+  const int64_t first = grp.count ? grp.block_end[grp.count - 1] : 0;
+  if (grp.count >= kTileLayersMax || first + blocks > 0x7FFFFFF0) return false;
+  grp.block_end[grp.count] = (uint32_t)(first + blocks);
+  grp.layer[grp.count++] = g;
+  return true;
+}
+
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
+static hipError_t launch_gemm_group(GemmGroup& grp, hipStream_t s) {
+  using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+  if (grp.count == 0) return hipSuccess;
+  auto kern = nm_gemm_group_kernel<SPARSE, WO, WT, OT, TT, STAGES>;
+  static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  // deepest layers first, so that the launch ends with the shortest tiles; the block counts move with them
+  for (int i = 1; i < grp.count; ++i) {
+    const GemmArgs L = grp.layer[i];
+    int j = i;
+    for (; j > 0 && grp.layer[j - 1].K < L.K; --j) grp.layer[j] = grp.layer[j - 1];
+    grp.layer[j] = L;
+  }
+  uint32_t end = 0;
+  for (int i = 0; i < grp.count; ++i) {
+    end += (uint32_t)((((int64_t)grp.layer[i].n_o_tiles * grp.layer[i].n_t_tiles + 7) / 8) * 8);
+    grp.block_end[i] = end;
+  }
+  hipLaunchKernelGGL(kern, dim3(end), dim3(C::NT), C::LDS_BYTES, s, grp);
+  grp.count = 0;
+  return hipGetLastError();
+}
+
 template <bool SPARSE, bool I8 = false>
 static hipError_t launch_stream_group(const StreamGroup& grp, hipStream_t s) {
   using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;  // dense stages are half the size: four fit
@@ -1284,6 +1360,35 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
   return product ? dispatch_gemm<false>(g, pick, s) : hipSuccess;
 }
 
+// The product of a prepared layer on the tiled kernel, as a table entry (the operands launch_spmm would hand the
+// kernel): false when the layer takes another path.
+static bool tiled_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form, int* pick) {
+  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
+  *pick = pick_tile(a.O, a.T);
+  if (*pick == 0) return false;
+  *sparse_form = a.N <= 2 && a.N < a.M;
+  g->X = a.X; g->bias = a.bias; g->Y = a.Y;
+  g->O = a.O; g->K = a.K; g->T = a.T; g->ldx = a.ldx; g->ldy = a.ldy;
+  g->out_bf16 = a.out_bf16;
+  g->n_o_tiles = g->n_t_tiles = 0;
+  g->sel = nullptr;
+  const int per_piece = a.out_bf16 ? 8 : 4;
+  g->vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
+                 (a.bias == nullptr || aligned_to(a.bias, 16));
+  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
+  if (*sparse_form) {
+    if (a.N == 2 && a.M == 4) {
+      g->A = a.values; g->sel = a.indices;
+    } else {
+      g->A = reinterpret_cast<const bf16_t*>(ws);
+      g->sel = reinterpret_cast<const uint32_t*>(ws + (size_t)(a.O * a.K));
+    }
+  } else {
+    g->A = a.N == a.M ? a.values : reinterpret_cast<const bf16_t*>(ws);
+  }
+  return true;
+}
+
 // The product of a prepared layer on the persistent kernel, as a table entry: false when this layer takes
 // another path (too few tiles, a shape or alignment the kernel does not handle).
 static bool stream_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form) {
@@ -1331,6 +1436,37 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
     grp.count = 0; grp.n_tiles = 0;
     return r;
   };
+  GemmGroup tile_grp[4];  // 2:4 form with 128 x 128 and 64 x 64 tiles, dense form likewise
+  for (GemmGroup& t : tile_grp) t.count = 0;
+  auto tile_append = [&](int which, const GemmArgs& g) {
+    switch (which) {
+      case 0: return tile_group_append<true, 2, 2, 4, 4, 3>(tile_grp[0], g);
+      case 1: return tile_group_append<true, 2, 2, 2, 2, 3>(tile_grp[1], g);
+      case 2: return tile_group_append<false, 2, 2, 4, 4, 3>(tile_grp[2], g);
+      default: return tile_group_append<false, 2, 2, 2, 2, 3>(tile_grp[3], g);
+    }
+  };
+  auto tile_flush = [&](int which) {
+    switch (which) {
+      case 0: return launch_gemm_group<true, 2, 2, 4, 4, 3>(tile_grp[0], s);
+      case 1: return launch_gemm_group<true, 2, 2, 2, 2, 3>(tile_grp[1], s);
+      case 2: return launch_gemm_group<false, 2, 2, 4, 4, 3>(tile_grp[2], s);
+      default: return launch_gemm_group<false, 2, 2, 2, 2, 3>(tile_grp[3], s);
+    }
+  };
+  // A layer alone takes 64 x 64 tiles when 128 x 128 ones would leave most compute units idle; the layers of a
+  // call fill the chip together, so they take the larger tiles (half the operand traffic into the compute
+  // units per output) as soon as the call holds enough of them.  A sum is accumulated in the same order under
+  // either tile size, so the outputs are the same bytes.
+  int64_t mid_tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    GemmArgs g;
+    bool sparse_form = false;
+    int pick = 0;
+    if (tiled_entry(layers[i], &g, &sparse_form, &pick))
+      mid_tiles += ((layers[i].O + 127) / 128) * ((layers[i].T + 127) / 128);
+  }
+  const bool promote = mid_tiles >= 256;
   for (int i = 0; i < count; ++i) {
     GemmArgs g;
     bool sparse_form = false;
@@ -1342,13 +1478,26 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
         ok = sparse_form ? group_append<true>(grp, g) : group_append<false>(grp, g);
         if (!ok) return hipErrorInvalidValue;
       }
+    } else if (int pick = 0; tiled_entry(layers[i], &g, &sparse_form, &pick)) {
+      // small layers: the tiled kernel, all layers of one operand form and tile size in one launch
+      const int which = (sparse_form ? 0 : 2) + ((pick == 2 || promote) ? 0 : 1);
+      if (!tile_append(which, g)) {
+        if ((e = tile_flush(which)) != hipSuccess) return e;
+        if (!tile_append(which, g)) {  // more blocks than a grid holds: alone
+          bool short_ws = false;
+          if ((e = launch_spmm(layers[i], s, &short_ws, SPMM_PRODUCT)) != hipSuccess) return e;
+        }
+      }
     } else {
       bool short_ws = false;
       if ((e = launch_spmm(layers[i], s, &short_ws, SPMM_PRODUCT)) != hipSuccess) return e;
     }
   }
   if ((e = flush(sparse_grp, true)) != hipSuccess) return e;
-  return flush(dense_grp, false);
+  if ((e = flush(dense_grp, false)) != hipSuccess) return e;
+  for (int which = 0; which < 4; ++which)
+    if ((e = tile_flush(which)) != hipSuccess) return e;
+  return hipSuccess;
 }
 
 }  // namespace nm

@@ -300,3 +300,59 @@ def test_prepare_then_prepared_equals_the_single_call(N, M):
         assert torch.equal(whole, part)
     if ws is not None:
         assert torch.equal(ws, snapshot)
+
+
+def test_batched_call_groups_small_products_into_shared_launches():
+    # Products too small for the persistent kernel: the batched call runs all layers of one operand form and tile
+    # size in one launch of the tiled kernel.  Both forms and both tile sizes, levels with and without a workspace,
+    # bias, both output types, ragged shapes, an unaligned output view (element-wise write-out), more layers than
+    # one launch's table holds (40 of one class), and a layer the gather kernel takes.  Every output must hold the
+    # bytes of the single call, and one layer of each class is checked against the oracle.
+    rng = np.random.default_rng(5151)
+    specs = []  # (T, K, O, N, M, out dtype, bias)
+    for n in range(40):  # 2:4 form, 64 x 64 tiles
+        specs.append((197 if n % 2 else 50 + n, 64 * (1 + n % 5), 64 + 24 * (n % 7), (1, 2)[n % 2], (4, 8, 16)[n % 3],
+                      torch.bfloat16 if n % 3 else torch.float32, n % 4 == 0))
+    specs += [(197, 768, 3072, 2, 4, torch.bfloat16, False), (197, 3072, 768, 1, 8, torch.float32, True),   # batch-1 block
+              (197, 768, 768, 4, 8, torch.bfloat16, True), (130, 704, 72, 3, 4, torch.float32, False),      # dense form, 64 x 64
+              (197, 256, 200, 8, 8, torch.bfloat16, False),
+              (2048, 128, 2048, 2, 8, torch.bfloat16, False), (2048, 192, 2048, 2, 4, torch.float32, True),  # 128 x 128 tiles
+              (2048, 128, 2048, 4, 16, torch.bfloat16, True),
+              (64, 48, 40, 1, 8, torch.float32, False)]                                                       # gather kernel
+    entries, singles, keep = [], [], {}
+    for n, (T, K, O, N, M, dt, with_bias) in enumerate(specs):
+        Xh, Wh = wl.draw_activations(rng, T, K), wl.draw_weights(rng, O, K)
+        X = dev_bf16(Xh)
+        v, i = nm.nm_pack(dev_bf16(Wh), N, M)
+        ws = nm.nm_spmm_prepare(v, i, K, N, M, T)
+        bh = rng.standard_normal(O).astype(np.float32) if with_bias else None
+        bias = torch.from_numpy(bh).cuda() if with_bias else None
+        singles.append(nm.nm_linear_forward_prepared(v, i, K, N, M, X, ws, bias=bias, out_dtype=dt))
+        entries.append((v, i, K, N, M, X, ws, bias, torch.zeros((T, O), dtype=dt, device="cuda")))
+        if n in (1, 40, 41, 42, 45, 47):
+            keep[n] = (Xh, Wh, bh)
+    # an output view whose rows are not whole 16-byte pieces
+    T, K, O, N, M = 100, 128, 70, 2, 4
+    X = dev_bf16(wl.draw_activations(rng, T, K))
+    v, i = nm.nm_pack(dev_bf16(wl.draw_weights(rng, O, K)), N, M)
+    singles.append(nm.nm_linear_forward_prepared(v, i, K, N, M, X, None))
+    wide = torch.zeros((T, O + 3), dtype=torch.float32, device="cuda")
+    entries.append((v, i, K, N, M, X, None, None, wide[:, 1:O + 1]))
+    nm.nm_linear_forward_prepared_batched(entries)
+    torch.cuda.synchronize()
+    for n, (e, ref) in enumerate(zip(entries, singles)):
+        assert torch.equal(e[-1], ref), (n, specs[n] if n < len(specs) else "view")
+    assert int(wide[:, 0].count_nonzero()) == 0 and int(wide[:, O + 1:].count_nonzero()) == 0
+    # a call with few small layers keeps their own (smaller) tiles: same bytes again
+    few = entries[:6] + entries[40:43]
+    for e in few:
+        e[-1].zero_()
+    nm.nm_linear_forward_prepared_batched(few)
+    for e, ref in zip(few, singles[:6] + singles[40:43]):
+        assert torch.equal(e[-1], ref)
+    for n, (Xh, Wh, bh) in keep.items():
+        T, K, O, N, M, dt, _ = specs[n]
+        Yref, B = orc.nm_linear_from_bits(Xh, Wh, N, M, bias=bh)
+        if bh is not None:
+            B = B + np.abs(bh)[None, :]  # the bias is one more term of the sum (it dominates these short sums)
+        check_output(host_output(entries[n][-1]), Yref, B, K // M * N + 1, dt == torch.float32, specs[n])
