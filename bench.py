@@ -373,6 +373,29 @@ def main():
                          "frac": q_tops / PEAK_INT8_DENSE_TOPS}}
     del q_masks, q_w, q_x, q_scale, q_ws
 
+    # ---- the same stack at batch 1 (197 tokens): products of a few tiles each, bound by streaming the weights; all
+    # 48 go to the library in one call, which runs the layers of one operand form in one launch of the tiled kernel
+    Ts = 197
+    small_layers = [(W, L.N, L.M, Ts) for W, L in zip(Ws, layers)]
+    small_packed, small_ws = nm.nm_pack_prepare_batched(small_layers, stream=stream)
+    small_Y = [torch.empty((Ts, L.O), dtype=torch.bfloat16, device=dev) for L in layers]
+    small_descs = nm.forward_descs([(v, i, L.K, L.N, L.M, X[:Ts], ws, None, Y) for (v, i), ws, X, Y, L in
+                                    zip(small_packed, small_ws, Xs, small_Y, layers)])
+
+    def small_products():
+        nm.nm_linear_forward_prepared_batched(small_descs, stream=stream)
+
+    small_ms = timed(small_products)
+    small_bytes = sum((ws.numel() if ws is not None else v.numel() * 2 + i.numel() * 4) + 2 * Ts * (L.K + L.O)
+                      for (v, i), ws, L in zip(small_packed, small_ws, layers))
+    small_batch = {"workload": "the 48 linears at batch 1 (T=197), bf16 out, one batched call; bytes = operand-form weights "
+                               "+ X + Y of every layer",
+                   "ms": small_ms, "algorithmic_bytes": small_bytes,
+                   "useful_tflops": sum(2.0 * Ts * L.O * L.K * L.N / L.M for L in layers) / small_ms / 1e9,
+                   "roofline": {"bound": "hbm", "achieved": small_bytes / small_ms / 1e6, "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "frac": small_bytes / small_ms / 1e6 / PEAK_HBM_GBS}}
+    del small_packed, small_ws, small_Y, small_descs
+
     # ---- context, not part of the path: the vendor library's dense bf16 product (torch.matmul) on the same four
     # shapes with unpruned weights, i.e. what the block costs without any sparsity
     try:
@@ -398,6 +421,8 @@ def main():
             f"TFLOP/s), dW {dw_ms:.3f} ms ({training['weight_gradient']['roofline']['achieved']:.0f} TFLOP/s)")
         log(f"int8 products of one block: {q_ms:.3f} ms ({q_tops:.0f} useful TOP/s, "
             f"{int8['dense_equivalent_tops']:.0f} dense-equivalent)")
+        log(f"batch 1 (T=197), 48 products in one call: {small_ms * 1e3:.1f} us "
+            f"({small_batch['roofline']['achieved']:.0f} GB/s of weights + activations)")
         if "ms" in dense_library_reference:
             log(f"for scale, the vendor library's dense bf16 product on the block's four shapes: "
                 f"{dense_library_reference['ms']:.3f} ms ({dense_library_reference['tflops']:.0f} TFLOP/s)")
@@ -440,6 +465,7 @@ def main():
         "nested_levels": nested,
         "training_products": training,
         "int8_products": int8,
+        "small_batch_products": small_batch,
         "dense_library_reference": dense_library_reference,
     }
     if not args.no_cpu_baseline:

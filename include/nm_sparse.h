@@ -250,7 +250,8 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
  * the shapes allow: large layers of the same operand form (N <= 2, or N > 2) share one launch of the persistent
  * product kernel, whose blocks walk the tiles of all of them as one list.  For the independent products of a
  * stack of layers (each with its own input; Section 3: one level per layer) this removes the partial last round
- * of tiles every single launch ends with.  Results are bit-identical to the single calls.
+ * of tiles every single launch ends with.  Small layers (a few tokens: batch-1 inference) likewise share launches
+ * of the tiled kernel, which no one of them could fill.  Results are bit-identical to the single calls.
  *   descs  HOST array of `count` descriptors, read before the call returns.  Fields as the arguments of
  *          nm_linear_forward_prepared; the outputs must not overlap each other or any input.
  * Errors as for nm_linear_forward_prepared (the first offending descriptor decides); nothing is launched on an
