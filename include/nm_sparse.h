@@ -47,6 +47,8 @@
  *   anything is launched, so they can be exercised without a GPU.  A call enqueues
  *   kernels only (no copies, fills or allocations), so it may be issued on a stream that
  *   is being captured into a graph; host descriptor arrays are read before it returns.
+ *   The first launch of a kernel in a process also raises that kernel's dynamic-LDS limit
+ *   (hipFuncSetAttribute): issue a call once eagerly before recording it.
  *   No function throws, aborts or prints.
  */
 #ifndef NM_SPARSE_H
