@@ -954,42 +954,70 @@ nm_stream_kernel(const StreamGroup g) {
         return acc[i][j];
       }
     };
+    // The layer's output geometry goes into registers first: read through the table entry, every store would
+    // wait for a scalar load of its own (and for everything else the wave has in flight with it).
+    int32_t ldy_s = L.ldy, o_s = L.O, kind_s = L.out_kind;
+    uint64_t y_s = reinterpret_cast<uint64_t>(L.Y);
+    asm volatile("" : "+s"(ldy_s), "+s"(o_s), "+s"(kind_s), "+s"(y_s));
+    // global address space, so that the stores are not counted with the LDS operations
+    using gbyte_t = __attribute__((address_space(1))) unsigned char;
+    using gpiece_t = __attribute__((address_space(1))) u32x4_t;
+    const int first_row = (int)(t_lo - t0);  // rows of a shifted last tile below this one belong to its neighbour
+    if (kind_s == 1) {
+      // lane 4m + q takes the piece of lane (token row m, kb = 0, 2, 1, 3 for q = 0 .. 3)
+      const int q4 = lane & 3;
+      const int src_lane = (lane >> 2) + 16 * (((q4 & 1) << 1) | (q4 >> 1));
+      // item n = (token block j, out-feature pair ip): convert, exchange, permute; the permuted piece of one item
+      // is stored while the permutation of the next one is under way
+      auto permuted = [&](int j, int ip) {
+        const f32x4_t v0 = value(2 * ip, j), v1 = value(2 * ip + 1, j);
+        const uint32_t a0 = pack_bf16x2(v0[0], v0[1]), a1 = pack_bf16x2(v0[2], v0[3]);
+        const uint32_t b0 = pack_bf16x2(v1[0], v1[1]), b1 = pack_bf16x2(v1[2], v1[3]);
+        // even lane rows keep their first operand and receive the odd partner's; odd rows receive the
+        // even partner's second operand and keep theirs
+        const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
+        const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
+        u32x4_t piece = u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
 #pragma unroll
-    for (int j = 0; j < TT; ++j) {
-      const int64_t t = t0 + wt * 128 + j * 16 + r16;
-      const bool row_ok = t >= t_lo;
-      if (L.out_kind == 1) {
-        // lane 4m + q takes the piece of lane (token row m, kb = 0, 2, 1, 3 for q = 0 .. 3)
-        const int q4 = lane & 3;
-        const int src_lane = (lane >> 2) + 16 * (((q4 & 1) << 1) | (q4 >> 1));
-        const int64_t t2 = t0 + wt * 128 + j * 16 + (lane >> 2);
-        const bool row_ok2 = t2 >= t_lo;
+        for (int e = 0; e < 4; ++e) piece[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane * 4, (int)piece[e]);
+        return piece;
+      };
+      const int row = wt * 128 + (lane >> 2);                            // this lane's row of the tile in block j = 0
+      const int64_t col = o0 + wo * C::OW + q4 * 8;                      // its out-feature for ip = 0
+      gbyte_t* dst = (gbyte_t*)y_s + ((t0 + row) * (int64_t)ldy_s + col) * 2;
+      const int64_t block_bytes = (int64_t)ldy_s * 32;                   // 16 token rows further
+      bool col_ok[OT / 2];
 #pragma unroll
-        for (int ip = 0; ip < OT / 2; ++ip) {
-          const f32x4_t v0 = value(2 * ip, j), v1 = value(2 * ip + 1, j);
-          const uint32_t a0 = pack_bf16x2(v0[0], v0[1]), a1 = pack_bf16x2(v0[2], v0[3]);
-          const uint32_t b0 = pack_bf16x2(v1[0], v1[1]), b1 = pack_bf16x2(v1[2], v1[3]);
-          // even lane rows keep their first operand and receive the odd partner's; odd rows receive the
-          // even partner's second operand and keep theirs
-          const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
-          const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
-          u32x4_t piece = u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
+      for (int ip = 0; ip < OT / 2; ++ip) col_ok[ip] = col + 2 * ip * 16 < o_s;
+      constexpr int ITEMS = TT * (OT / 2);
+      u32x4_t cur = permuted(0, 0);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) piece[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane * 4, (int)piece[e]);
-          const int64_t o = o0 + wo * C::OW + 2 * ip * 16 + q4 * 8;
-          if (row_ok2 && o < L.O)
-            *reinterpret_cast<u32x4_t*>(reinterpret_cast<bf16_t*>(L.Y) + t2 * L.ldy + o) = piece;
-        }
-      } else {
+      for (int n = 0; n < ITEMS; ++n) {
+        const int j = n / (OT / 2), ip = n % (OT / 2);
+        u32x4_t nxt = cur;
+        if (n + 1 < ITEMS) nxt = permuted((n + 1) / (OT / 2), (n + 1) % (OT / 2));
+        if (row + j * 16 >= first_row && col_ok[ip]) *(gpiece_t*)(dst + ip * 64) = cur;
+        if (ip == OT / 2 - 1) dst += block_bytes;
+        cur = nxt;
+      }
+    } else {
+      const int row = wt * 128 + r16;
+      const int64_t col = o0 + wo * C::OW + kb * 4;
+      gbyte_t* dst = (gbyte_t*)y_s + ((t0 + row) * (int64_t)ldy_s + col) * 4;
+      const int64_t block_bytes = (int64_t)ldy_s * 64;
+      bool col_ok[OT];
+#pragma unroll
+      for (int i = 0; i < OT; ++i) col_ok[i] = col + i * 16 < o_s;
+#pragma unroll
+      for (int j = 0; j < TT; ++j) {
 #pragma unroll
         for (int i = 0; i < OT; ++i) {
-          const int64_t o = o0 + wo * C::OW + i * 16 + kb * 4;
           u32x4_t piece;
-          if (I8 && L.out_kind == 2) piece = __builtin_bit_cast(u32x4_t, acc[i][j]);  // the integer sums themselves
+          if (I8 && kind_s == 2) piece = __builtin_bit_cast(u32x4_t, acc[i][j]);  // the integer sums themselves
           else piece = __builtin_bit_cast(u32x4_t, value(i, j));
-          if (row_ok && o < L.O)
-            *reinterpret_cast<u32x4_t*>(reinterpret_cast<uint32_t*>(L.Y) + t * L.ldy + o) = piece;
+          if (row + j * 16 >= first_row && col_ok[i]) *(gpiece_t*)(dst + i * 64) = piece;
         }
+        dst += block_bytes;
       }
     }
   }
