@@ -263,7 +263,47 @@ nm_tgemm_kernel(const TGemmArgs a) {
   // STAGES - 1 stages ahead.
   {
     int buf = 0;
-    for (int64_t ks = 0; ks < nk; ++ks) {
+    int64_t ks = 0;
+    // Steady state, free of conditions: while the stage to be fetched exists and has all its rows (then so has
+    // the one being multiplied), the waits are fixed, no row is clamped or cleared, and the operand addresses
+    // advance by additions.  A wave issues in order, so every scalar and vector instruction saved here is issue
+    // time its matrix instructions get.  The last STAGES - 1 steps (and a ragged last stage of the reduction)
+    // take the general form below.
+    int64_t n_fast = nk - (STAGES - 1);
+    if (n_fast > 0 && a.R - (r_first + (nk - 1) * C::RS) < C::RS) --n_fast;
+    if (n_fast > 0) {
+      const int64_t r_load = r_first + (int64_t)(STAGES - 1) * C::RS;
+      const unsigned char* fp = reinterpret_cast<const unsigned char*>(p_base + r_load * a.ldp);
+      const unsigned char* fq = reinterpret_cast<const unsigned char*>(Q_STRIDED ? q_base + r_load * a.ldq : q_base + r_load);
+      const int64_t p_step = (int64_t)C::RS * a.ldp * 2, q_step = Q_STRIDED ? (int64_t)C::RS * a.ldq * 2 : (int64_t)C::RS * 2;
+      uint32_t lds_load = lds0 + (uint32_t)((STAGES - 1) * C::STAGE);  // LDS address of the buffer to be refilled
+      for (; ks < n_fast; ++ks) {
+        wait_loads_outstanding<(STAGES - 2) * C::LPW>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(buf);
+        const uniform_ptr_t up = make_uniform(fp), uq = make_uniform(fq);
+        const uint32_t lds = __builtin_amdgcn_readfirstlane(lds_load);
+        [&]<int... Q>(std::integer_sequence<int, Q...>) {
+          ([&] {
+            constexpr int j = Q / IT, i = Q % IT;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pf[i]),
+                                                                __builtin_bit_cast(bf16x8_t, qf[j]), acc[i][j], 0, 0, 0);
+            if constexpr (Q % 4 == 3 && Q / 4 < C::LPW) {
+              constexpr int d = Q / 4;
+              if constexpr (d < C::P_PW) dma16(up, p_voff[d], lds + p_dst[d]);
+              else dma16(uq, q_voff[d - C::P_PW], lds + q_dst[d - C::P_PW]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }(), ...);
+        }(std::make_integer_sequence<int, C::MMA>{});
+        fp += p_step;
+        fq += q_step;
+        lds_load += (uint32_t)C::STAGE;
+        if (lds_load == lds0 + (uint32_t)(STAGES * C::STAGE)) lds_load = lds0;
+        if (++buf == STAGES) buf = 0;
+      }
+    }
+    for (; ks < nk; ++ks) {
       const int64_t ahead = nk - 1 - ks;  // stages after this one; the loads of at most STAGES - 2 of them are out
       wait_stage(ahead < STAGES - 2 ? (int)ahead : STAGES - 2);
       const int64_t r = r_first + ks * C::RS;
