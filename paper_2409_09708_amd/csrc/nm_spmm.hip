@@ -664,6 +664,7 @@ nm_stream_kernel(const StreamGroup g) {
   int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_wrap = 1, ld_offsets_of = -1;
   ListPos ld_at{0, 0};
   uint32_t ld_bias_voff = 0;
+  int ld_consts = 0;  // nonzero while the cursor's tile still has per-out-feature constants for this wave to fetch
   const float* ld_bias = nullptr;
   const float* ld_scale = nullptr;
   const unsigned char* ld_x = nullptr;
@@ -688,6 +689,7 @@ nm_stream_kernel(const StreamGroup g) {
     ld_bias = L.bias;
     ld_scale = L.scale;
     ld_bias_voff = (uint32_t)((ob + 4 <= L.O ? ob : L.O - 4) * 4);
+    ld_consts = (wave == 0 && (ld_bias != nullptr || (I8 && ld_scale != nullptr))) ? 1 : 0;
     // The tiles that share the tile's X rows (same tokens, other out-features) run on the same XCD at the
     // same time, and so do a few that share its W rows (same out-features, other tokens); each starts at its
     // own K step and wraps around, so they ask for different slices of those rows at any moment and find the
@@ -720,7 +722,8 @@ nm_stream_kernel(const StreamGroup g) {
     if constexpr (d == 0) {
       // a tile's first stage brings the tile's bias slice along (older than the stage's own loads, so
       // every wait that covers the stage covers it); slice s belongs to stage buffer s
-      if (wave == 0 && ld_ks == 0) {  // wave 0 also fetches the tiles' per-out-feature constants
+      if (ld_consts) {  // wave 0 also fetches the tile's per-out-feature constants, once (one test per step)
+        ld_consts = 0;
         if constexpr (I8) {
           const uint32_t pair = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)C::BIAS0 + (uint32_t)(ld_n & 1) * (2 * C::BO * 4));
           if (ld_scale != nullptr) dma16(make_uniform(ld_scale), ld_bias_voff, pair);
