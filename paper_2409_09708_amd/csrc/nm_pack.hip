@@ -257,8 +257,12 @@ struct BatchArgs {
 template <int SRC>  // 0: selection by magnitude, 2: from stored ranks
 __global__ void __launch_bounds__(kPackThreads) pack_batched_kernel(const BatchArgs args) {
   __shared__ uint32_t sbits[kSbitsWords];
-  int m = 0;
-  while (m < args.count - 1 && blockIdx.x >= args.e[m].block_end) ++m;
+  int m = 0, hi = args.count - 1;  // the first matrix whose blocks end beyond this one, by bisection
+  while (m < hi) {
+    const int mid = (m + hi) >> 1;
+    if (blockIdx.x >= args.e[mid].block_end) m = mid + 1;
+    else hi = mid;
+  }
   const BatchEntry& d = args.e[m];
   const uint32_t first = m ? args.e[m - 1].block_end : 0u;
   const int64_t chunk0 = (int64_t)(blockIdx.x - first) * kPackThreads;

@@ -80,8 +80,12 @@ struct RankBatchArgs {
 };
 
 __global__ void __launch_bounds__(256) rank_batched_kernel(const RankBatchArgs args) {
-  int m = 0;
-  while (m < args.count - 1 && blockIdx.x >= args.e[m].block_end) ++m;
+  int m = 0, hi = args.count - 1;  // the first matrix whose blocks end beyond this one, by bisection
+  while (m < hi) {
+    const int mid = (m + hi) >> 1;
+    if (blockIdx.x >= args.e[mid].block_end) m = mid + 1;
+    else hi = mid;
+  }
   const RankEntry& d = args.e[m];
   const uint32_t first = m ? args.e[m - 1].block_end : 0u;
   const int64_t c = (int64_t)(blockIdx.x - first) * 256 + threadIdx.x;
