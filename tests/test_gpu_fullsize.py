@@ -192,3 +192,25 @@ def test_batched_products_equal_the_single_calls():
     nm.nm_linear_forward_prepared_batched(descs)
     for e, ref in zip(entries, singles):
         assert torch.equal(e[-1], ref)
+
+
+def test_batched_call_with_more_layers_than_one_launch_holds():
+    # 50 layers of the 2:4 form that all take the persistent kernel (256 tiles each): the table of a launch holds
+    # fewer, so the call flushes it and starts another; shallow K (three steps), one shared input
+    rng = np.random.default_rng(777)
+    T, K, O = 65536, 192, 256
+    X = dev_bf16(wl.draw_activations(rng, T, K))
+    entries, singles = [], []
+    for n in range(50):
+        N, M = ((2, 4), (1, 4), (2, 8), (1, 16))[n % 4]
+        v, i = nm.nm_pack(dev_bf16(wl.draw_weights(rng, O, K)), N, M)
+        ws = nm.nm_spmm_prepare(v, i, K, N, M, T)
+        entries.append((v, i, K, N, M, X, ws, None, torch.zeros((T, O), dtype=torch.bfloat16, device="cuda")))
+        if n % 7 == 0:
+            singles.append((n, nm.nm_linear_forward_prepared(v, i, K, N, M, X, ws, out_dtype=torch.bfloat16)))
+    nm.nm_linear_forward_prepared_batched(entries)
+    torch.cuda.synchronize()
+    for n, ref in singles:
+        assert torch.equal(entries[n][-1], ref), n
+    for e in entries:  # every output was written (no layer fell between two launches)
+        assert int(e[-1][::4099].count_nonzero()) > 0
