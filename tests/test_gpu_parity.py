@@ -177,6 +177,24 @@ def test_spmm_parity_large_tile_path(N, M):
     check_output(Y, Yref, B, K // M * N, True, (N, M))
 
 
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 8), (4, 8)])
+def test_spmm_parity_large_tile_path_bf16_output(N, M):
+    # the same path writing bfloat16: ragged in both directions (the last token tile is shifted back and stores
+    # only its own rows; the last out-feature tile stores only its own columns), three K steps, with a bias
+    rng = np.random.default_rng(3600 + N * 17 + M)
+    T, K, O = 16 * 256 + 37, 192, 16 * 256 + 40
+    X = wl.draw_activations(rng, T, K)
+    W = wl.draw_weights(rng, O, K)
+    bias = rng.standard_normal(O).astype(np.float32)
+    Yref, B = orc.nm_linear_from_bits(X, W, N, M, bias=bias)
+    v, i = nm.nm_pack(dev_bf16(W), N, M)
+    out = torch.full((T + 2, O + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+    nm.nm_linear_forward(v, i, K, N, M, dev_bf16(X), bias=torch.from_numpy(bias).cuda(), out=out[1:T + 1, :O])
+    check_output(host_output(out[1:T + 1, :O]), Yref, B + np.abs(bias)[None, :], K // M * N + 1, False, (N, M))
+    guard = out.float()
+    assert bool((guard[0] == 7).all()) and bool((guard[T + 1] == 7).all()) and bool((guard[:, O:] == 7).all())
+
+
 @pytest.mark.parametrize("N,M", [(2, 4), (1, 8), (4, 8), (2, 16)])
 def test_spmm_with_bias_and_strided_views(N, M):
     rng = np.random.default_rng(3700 + N + M)
