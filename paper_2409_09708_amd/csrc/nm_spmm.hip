@@ -661,7 +661,8 @@ nm_stream_kernel(const StreamGroup g) {
 
   // ---- load cursor = the stage to be issued next (tile number in this block, k step) as running pointers: X
   // rows of the tile at the step's k, W and selector blocks of the step
-  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_wrap = 1;
+  int ld_n = 0, ld_ks = 0, ld_nk = 1, ld_wrap = 1, ld_offsets_of = -1;
+  ListPos ld_at{0, 0};
   uint32_t ld_bias_voff = 0;
   int ld_consts = 0;  // nonzero while the cursor's tile still has per-out-feature constants for this wave to fetch
   const float* ld_bias = nullptr;
@@ -669,80 +670,32 @@ nm_stream_kernel(const StreamGroup g) {
   const unsigned char* ld_x = nullptr;
   const unsigned char* ld_w = nullptr;
   const unsigned char* ld_s = nullptr;
-  // The cursor's place in the list.  A layer's constants stay in scalar registers from tile to tile: only a
-  // change of layer reads the table in the kernel arguments and divides (all eight waves would otherwise wait
-  // for three dependent scalar loads and two divisions in the middle of a K step, once per tile).  Inside a
-  // layer the block's next tile lies `slots` list entries further: out-feature tile and token tile advance by
-  // slots mod n_o and slots / n_o, and the starting K step (o + t) mod nk by a fixed amount likewise.
-  int cw_layer = 0, cw_begin = 0, cw_end = 0;  // layer, its first list entry on this XCD, one past its last
-  int cw_no = 1, cw_q = 0, cw_r = 0, cw_o = 0, cw_t = 0, cw_T = 0, cw_O = 0, cw_ldx = 0;
-  int cw_phase = 0, cw_d1 = 0, cw_d2 = 0;
-  uint64_t cw_X = 0, cw_A = 0, cw_S = 0;
-  auto cursor_layer = [&](int entry) {
-    int share = xcd_share(cw_layer);
-    while (entry >= cw_begin + share) {
-      cw_begin += share;
-      share = xcd_share(++cw_layer);
-    }
-    cw_end = cw_begin + share;
-    const StreamLayer& L = g.layer[cw_layer];
-    const int local = xcd * ((L.n_tiles + 7) >> 3) + (entry - cw_begin);
-    cw_no = L.n_o_tiles;
-    cw_o = local % cw_no;
-    cw_t = local / cw_no;
-    cw_q = slots / cw_no;
-    cw_r = slots % cw_no;
+  auto cursor_tile = [&](int n) {
+    int o_tile;
+    int64_t t_lo, t0;
+    tile_place(n, ld_at, o_tile, t_lo, t0);
+    const int ld_layer = ld_at.layer;
+    const StreamLayer& L = g.layer[ld_layer];
     ld_nk = L.nk;
-    cw_phase = (int)((unsigned)(cw_o + cw_t) % (unsigned)ld_nk);
-    cw_d1 = (int)((unsigned)(cw_q + cw_r) % (unsigned)ld_nk);  // o += r, t += q
-    int d2 = (cw_q + cw_r + 1 - cw_no) % ld_nk;                // o += r - n_o, t += q + 1
-    cw_d2 = d2 < 0 ? d2 + ld_nk : d2;
-    cw_T = L.T; cw_O = L.O; cw_ldx = L.ldx;
-    cw_X = reinterpret_cast<uint64_t>(L.X);
-    cw_A = reinterpret_cast<uint64_t>(L.A);
-    cw_S = reinterpret_cast<uint64_t>(L.sel);
-    ld_bias = L.bias;
-    ld_scale = L.scale;
-    layer_offsets(cw_ldx, ld_nk);
-    asm volatile("" : "+s"(cw_end), "+s"(cw_no), "+s"(cw_q), "+s"(cw_r), "+s"(cw_d1), "+s"(cw_d2), "+s"(cw_T), "+s"(cw_O));
-    asm volatile("" : "+s"(cw_ldx), "+s"(ld_nk), "+s"(cw_X), "+s"(cw_A), "+s"(cw_S));
-  };
-  auto cursor_tile = [&](int n, bool first_tile) {
-    if (first_tile) {
-      cursor_layer(first);
-    } else if (n != ld_n) {  // (n == ld_n: past the block's last stage, the last tile again)
-      const int entry = first + n * slots;
-      if (entry >= cw_end) {
-        cursor_layer(entry);
-      } else {
-        cw_o += cw_r;
-        cw_t += cw_q;
-        if (cw_o >= cw_no) {
-          cw_o -= cw_no;
-          ++cw_t;
-          cw_phase += cw_d2;
-        } else {
-          cw_phase += cw_d1;
-        }
-        if (cw_phase >= ld_nk) cw_phase -= ld_nk;
-      }
+    if (ld_offsets_of != ld_layer) {
+      layer_offsets(L.ldx, ld_nk);
+      ld_offsets_of = ld_layer;
     }
-    const int o_tile = cw_o;
-    const int64_t t_lo = (int64_t)cw_t * C::BT;
-    const int64_t t0 = t_lo + C::BT <= cw_T ? t_lo : (int64_t)cw_T - C::BT;
-    ld_x = reinterpret_cast<const unsigned char*>(cw_X) + t0 * cw_ldx * C::ES;
-    ld_w = reinterpret_cast<const unsigned char*>(cw_A) + (((int64_t)o_tile * 16 * ld_nk) << 10);
-    ld_s = SPARSE ? reinterpret_cast<const unsigned char*>(cw_S) + (int64_t)o_tile * ld_nk * C::S_BYTES : nullptr;
+    ld_x = reinterpret_cast<const unsigned char*>(L.X) + t0 * L.ldx * C::ES;
+    ld_w = reinterpret_cast<const unsigned char*>(L.A) + (((int64_t)o_tile * 16 * ld_nk) << 10);
+    ld_s = SPARSE ? reinterpret_cast<const unsigned char*>(L.sel) + (int64_t)o_tile * ld_nk * C::S_BYTES : nullptr;
     // bias[o0 + 4 lane ..]: past the last out-feature re-read the last four (never stored)
     const int64_t ob = (int64_t)o_tile * C::BO + lane * 4;
-    ld_bias_voff = (uint32_t)((ob + 4 <= cw_O ? ob : cw_O - 4) * 4);
+    ld_bias = L.bias;
+    ld_scale = L.scale;
+    ld_bias_voff = (uint32_t)((ob + 4 <= L.O ? ob : L.O - 4) * 4);
     ld_consts = (wave == 0 && (ld_bias != nullptr || (I8 && ld_scale != nullptr))) ? 1 : 0;
     // The tiles that share the tile's X rows (same tokens, other out-features) run on the same XCD at the
     // same time, and so do a few that share its W rows (same out-features, other tokens); each starts at its
-    // own K step, (o + t) mod nk, and wraps around, so they ask for different slices of those rows at any
-    // moment and find the others' slices in L2 instead of missing on them together.
-    ld_wrap = ld_nk - cw_phase;  // steps until the walk wraps to K step 0
-    const int64_t k0 = cw_phase;
+    // own K step and wraps around, so they ask for different slices of those rows at any moment and find the
+    // others' slices in L2 instead of missing on them together.
+    ld_wrap = ld_nk - (int)((unsigned)(o_tile + (int)(t_lo / C::BT)) % (unsigned)ld_nk);  // steps until the walk wraps to K step 0
+    const int64_t k0 = ld_nk - ld_wrap;
     ld_x += k0 * C::X_ROWB;
     ld_w += k0 * 1024;
     if (SPARSE) ld_s += k0 * C::S_BYTES;
@@ -760,7 +713,7 @@ nm_stream_kernel(const StreamGroup g) {
       ld_w -= (int64_t)ld_nk * 1024;
       if (SPARSE) ld_s -= (int64_t)ld_nk * C::S_BYTES;
     }
-    if (ld_ks == ld_nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n, false);
+    if (ld_ks == ld_nk) cursor_tile(ld_n + 1 < my_tiles ? ld_n + 1 : ld_n);
   };
   // the d-th of this wave's LPW loads of the cursor's stage into the stage buffer at LDS offset stage_off
   auto issue_one = [&](auto d_tag, uint32_t stage_off) {
@@ -841,7 +794,7 @@ nm_stream_kernel(const StreamGroup g) {
   constexpr int SPREAD = C::LPW <= 4 ? 2 : 1;
   constexpr int HEAD = (3 + SPREAD - 1) / SPREAD;
   static_assert(HEAD <= C::LPW && (C::LPW - 1) * SPREAD < C::TT, "the last load must be out before the next step's wait");
-  cursor_tile(0, true);
+  cursor_tile(0);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s) {
     if (s + 1 < STAGES) {
