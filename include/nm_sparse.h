@@ -40,8 +40,11 @@
  *
  * Ownership and execution
  *   Every data pointer is a DEVICE pointer owned by the caller unless it is marked
- *   "host".  The library allocates no device memory and keeps no state besides the
- *   last HIP error code.  `stream` is a hipStream_t passed as void* (NULL = the null
+ *   "host".  The library allocates no device memory.  Its only state: the last HIP
+ *   error code of the calling thread, and per device (a process may use several, the
+ *   current one at call time is used) a few marks of one-time setup: the dynamic-LDS limit
+ *   raised per kernel, the compute-unit count.  No
+ *   environment variable is read.  `stream` is a hipStream_t passed as void* (NULL = the null
  *   stream).  Calls validate their arguments on the host, enqueue their kernels on
  *   `stream` and return without synchronising.  Argument errors are reported before
  *   anything is launched, so they can be exercised without a GPU.  A call enqueues
@@ -67,7 +70,8 @@ typedef uint16_t nm_bf16; /* bfloat16 bit pattern */
 enum {
   NM_OK = 0,
   NM_ERR_NULL = 1,      /* a required pointer is NULL */
-  NM_ERR_SHAPE = 2,     /* O, K or T <= 0; K % M != 0; a leading dimension smaller than the row; count <= 0 */
+  NM_ERR_SHAPE = 2,     /* O, K or T <= 0; K % M != 0; a leading dimension smaller than the row; count <= 0;
+                           O, K or T above 2^31 or O * K above 2^40 */
   NM_ERR_LEVEL = 3,     /* M not in {4, 8, 16} or N outside [1, M] */
   NM_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
   NM_ERR_DTYPE = 5,     /* out_dtype is not one the call offers */
@@ -383,6 +387,25 @@ typedef struct nm_layer_desc {
 } nm_layer_desc;
 
 int32_t nm_pack_prepare_batched(const nm_layer_desc* descs, int32_t count, void* stream);
+
+/*
+ * Measurement aids -- no part of the layer and of no passage of the paper: the two rates the kernels above are
+ * priced against, measured on the device at hand rather than taken from a data sheet.
+ *   nm_probe_matrix_rate  a loop of nothing but matrix instructions on register operands, every compute unit
+ *                         busy with two waves per SIMD.  kind 0: the 2:4 sparse bfloat16 instruction
+ *                         (v_smfmac_f32_16x16x64_bf16), kind 1: the dense one (v_mfma_f32_16x16x32_bf16); each
+ *                         wave issues iters * 32 of them.
+ *       sink  device, out: nm_probe_sink_bytes() bytes, 4-byte aligned (keeps the sums alive; contents arbitrary)
+ *       ops   HOST, out: dense-equivalent operations the launch performs (2 * 16 * 16 * K per instruction);
+ *             divide by the launch's measured duration.
+ *   nm_probe_copy         dst[0 .. bytes) = src[0 .. bytes): a plain streaming copy, 16 bytes per lane; bytes a
+ *                         multiple of 16, both pointers 16-byte aligned, no overlap.  Reads and writes `bytes`
+ *                         once each, which also calibrates a profiler's byte counters.
+ * Errors: NM_ERR_NULL, NM_ERR_DTYPE (kind), NM_ERR_SHAPE (iters <= 0, bytes), NM_ERR_ALIGN, NM_ERR_DEVICE.
+ */
+size_t nm_probe_sink_bytes(void);
+int32_t nm_probe_matrix_rate(int32_t kind, int32_t iters, void* sink, int64_t* ops, void* stream);
+int32_t nm_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /*
  * Host-only helpers of the configuration search (no GPU work, HOST pointers throughout).

@@ -21,6 +21,7 @@ EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
+    "nm_probe_sink_bytes", "nm_probe_matrix_rate", "nm_probe_copy",
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_ranked_batched", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
     "nm_backward_input_workspace_bytes", "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
@@ -108,6 +109,12 @@ def load_library() -> ctypes.CDLL:
                                     c_void_p]
     lib.nm_linear_forward_prepared.restype = c_int32
     lib.nm_linear_forward_prepared.argtypes = lib.nm_linear_forward.argtypes
+    lib.nm_probe_sink_bytes.restype = c_size_t
+    lib.nm_probe_sink_bytes.argtypes = []
+    lib.nm_probe_matrix_rate.restype = c_int32
+    lib.nm_probe_matrix_rate.argtypes = [c_int32, c_int32, c_void_p, ctypes.POINTER(c_int64), c_void_p]
+    lib.nm_probe_copy.restype = c_int32
+    lib.nm_probe_copy.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     lib.nm_pack_prepare_batched.restype = c_int32
     lib.nm_pack_prepare_batched.argtypes = [ctypes.POINTER(LayerDesc), c_int32, c_void_p]
     lib.nm_rank_bytes.restype = c_size_t
@@ -454,12 +461,19 @@ def bf16_bits(t):
 _WORKSPACES = {}
 
 
-def _workspace(nbytes: int, device):
-    """A cached scratch tensor per device, grown on demand (allocated by torch, not by the library)."""
+def _workspace(nbytes: int, device, stream=None):
+    """A cached scratch tensor per (device, stream), grown on demand (allocated by torch, not by the library).
+    Calls on different streams may overlap, and concurrent calls need distinct workspaces, hence one per
+    stream.  A tensor that is replaced may still be read by kernels on its stream: it is marked as in use on
+    that stream so that the allocator does not hand its memory out before they finish."""
     torch = _torch()
-    key = (device.type, device.index)
+    index = device.index if device.index is not None else torch.cuda.current_device()
+    handle = _stream_handle(stream)
+    key = (device.type, index, handle)
     ws = _WORKSPACES.get(key)
     if ws is None or ws.numel() < nbytes:
+        if ws is not None and handle:
+            ws.record_stream(torch.cuda.ExternalStream(handle, device=index))
         ws = torch.empty((max(nbytes, 1 << 20),), dtype=torch.uint8, device=device)
         _WORKSPACES[key] = ws
     return ws
@@ -514,7 +528,7 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
     if workspace is None and need:
         if _prepared:
             raise ValueError("a prepared call needs the workspace nm_spmm_prepare filled")
-        workspace = _workspace(need, X.device)
+        workspace = _workspace(need, X.device, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     bias_ptr = None
@@ -537,6 +551,26 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
                                    out.data_ptr(), ldy, code, ws_ptr, ws_bytes, _stream_handle(stream))
     _check(st)
     return out
+
+
+def nm_probe_matrix_rate(kind: int, iters: int, sink=None, stream=None):
+    """Launch the matrix-instruction loop (kind 0: 2:4 sparse bf16, 1: dense bf16); returns (sink, operations)."""
+    torch = _torch()
+    lib = load_library()
+    if sink is None:
+        sink = torch.empty((lib.nm_probe_sink_bytes(),), dtype=torch.uint8, device="cuda")
+    ops = c_int64(0)
+    _check(lib.nm_probe_matrix_rate(kind, iters, sink.data_ptr(), ctypes.byref(ops), _stream_handle(stream)))
+    return sink, int(ops.value)
+
+
+def nm_probe_copy(src, dst, stream=None):
+    """dst = src with the library's plain streaming copy kernel (equal-sized contiguous device tensors)."""
+    nbytes = src.numel() * src.element_size()
+    if not (src.is_contiguous() and dst.is_contiguous()) or dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must be contiguous and of equal size")
+    _check(load_library().nm_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream)))
+    return dst
 
 
 def _out_matrix(out, out_dtype, rows: int, cols: int, device, name: str):
@@ -570,7 +604,7 @@ def nm_linear_backward_input(Ws, dY, out_dtype=None, out=None, workspace=None, s
     out, ldx, code = _out_matrix(out, out_dtype, T, K, dY.device, "dX")
     need = nm_backward_input_workspace_bytes(O, K, T)
     if workspace is None and need:
-        workspace = _workspace(need, dY.device)
+        workspace = _workspace(need, dY.device, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load_library().nm_linear_backward_input(Ws.data_ptr(), O, K, ldw, dY.data_ptr(), T, ldy, out.data_ptr(), ldx,
@@ -600,7 +634,7 @@ def nm_linear_backward_weight(dY, X, mask=None, out_dtype=None, out=None, worksp
     out, lddw, code = _out_matrix(out, out_dtype, O, K, dY.device, "dW")
     need = nm_backward_weight_workspace_bytes(O, K, T)
     if workspace is None and need:
-        workspace = _workspace(need, dY.device)
+        workspace = _workspace(need, dY.device, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load_library().nm_linear_backward_weight(dY.data_ptr(), T, O, ldy, X.data_ptr(), K, ldx, mask_ptr,
@@ -711,7 +745,7 @@ def nm_linear_forward_i8(Wq, mask, N: int, M: int, Xq, x_scale: float = 1.0, w_s
     if workspace is None and need:
         if _prepared:
             raise ValueError("a prepared call needs the workspace nm_i8_prepare filled")
-        workspace = _workspace(need, Xq.device)
+        workspace = _workspace(need, Xq.device, stream)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     lib = load_library()

@@ -9,6 +9,7 @@ namespace {
 
 thread_local int32_t g_last_hip_error = 0;
 
+
 inline int32_t device_status(hipError_t e) {
   if (e == hipSuccess) return NM_OK;
   g_last_hip_error = (int32_t)e;
@@ -24,6 +25,7 @@ inline int32_t check_weight(int64_t O, int64_t K, int32_t N, int32_t M) {
   if (!level_ok(N, M)) return NM_ERR_LEVEL;
   if (O <= 0 || K <= 0 || (K % M) != 0) return NM_ERR_SHAPE;
   if (O > (int64_t)1 << 31 || K > (int64_t)1 << 31) return NM_ERR_SHAPE;
+  if (O * K > (int64_t)1 << 40) return NM_ERR_SHAPE;  // every launcher's grid (at most one block per 1024 weights) fits 2^31 - 1
   return NM_OK;
 }
 
@@ -357,6 +359,23 @@ int32_t nm_prune_scored(const float* score, int64_t O, int64_t K, int64_t lds, i
   if (lds < K) return NM_ERR_SHAPE;
   if (!aligned(score, 4) || !aligned(mask, 4)) return NM_ERR_ALIGN;
   return device_status(nm::launch_score_mask(score, O, K, lds, N, M, mask, (hipStream_t)stream));
+}
+
+size_t nm_probe_sink_bytes(void) { return nm::probe_sink_bytes(); }
+
+int32_t nm_probe_matrix_rate(int32_t kind, int32_t iters, void* sink, int64_t* ops, void* stream) {
+  if (!sink || !ops) return NM_ERR_NULL;
+  if (kind != 0 && kind != 1) return NM_ERR_DTYPE;
+  if (iters <= 0) return NM_ERR_SHAPE;
+  if (!aligned(sink, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_probe_matrix(kind, iters, static_cast<float*>(sink), ops, (hipStream_t)stream));
+}
+
+int32_t nm_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst) return NM_ERR_NULL;
+  if (bytes == 0 || (bytes % 16) != 0) return NM_ERR_SHAPE;
+  if (!aligned(src, 16) || !aligned(dst, 16)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_probe_copy(src, dst, bytes, (hipStream_t)stream));
 }
 
 int32_t nm_linear_forward_prepared_batched(const nm_forward_desc* descs, int32_t count, void* stream) {

@@ -437,13 +437,8 @@ template <bool Q_STRIDED>
 hipError_t launch_tgemm(TGemmArgs g, hipStream_t s) {
   using C = TCfg;
   auto kern = nm_tgemm_kernel<Q_STRIDED>;
-  static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static PerDeviceOnce lds_limit;
+  if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
   const int64_t n_tiles = (int64_t)g.n_i_tiles * g.n_j_tiles;
   const int64_t grid = ((n_tiles * g.splits + 7) / 8) * 8;
   if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;

@@ -22,8 +22,6 @@
 #include "nm_launch.h"
 #include "nm_mma.h"
 
-#include <stdlib.h>
-
 #include <type_traits>
 #include <utility>
 
@@ -416,13 +414,8 @@ template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
 hipError_t launch_i8_gemm(I8Args g, hipStream_t s) {
   using C = I8Cfg<SPARSE, WO, WT, OT, TT, STAGES>;
   auto kern = nm_i8_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES>;
-  static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static PerDeviceOnce lds_limit;
+  if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
   g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
   g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
   const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
@@ -434,10 +427,9 @@ hipError_t launch_i8_gemm(I8Args g, hipStream_t s) {
 
 template <bool SPARSE>
 hipError_t dispatch_i8(const I8Args& g, hipStream_t s) {
-  static const int forced = getenv("NM_I8_TILE") ? atoi(getenv("NM_I8_TILE")) : 0;  // tuning aid
   const int64_t tiles_big = ((g.O + 255) / 256) * ((g.T + 255) / 256);
   const int64_t tiles_mid = ((g.O + 127) / 128) * ((g.T + 127) / 128);
-  int pick = forced ? forced : (tiles_big >= 256 ? 3 : (tiles_mid >= 256 ? 2 : 1));
+  const int pick = tiles_big >= 256 ? 3 : (tiles_mid >= 256 ? 2 : 1);
   if (pick == 3) return launch_i8_gemm<SPARSE, 4, 2, 4, 8, SPARSE ? 3 : 2>(g, s);
   if (pick == 2) return launch_i8_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
   return launch_i8_gemm<SPARSE, 2, 2, 2, 2, 3>(g, s);

@@ -8,6 +8,44 @@ namespace nm {
 
 typedef uint16_t bf16_t;
 
+// One-time setup of a kernel on the current device.  Function attributes and the compute-unit count belong to a
+// device, and a process may drive several (one current at a time), so the "done" marks are kept per device.
+// A race between threads only repeats an idempotent call.
+constexpr int kMaxDevices = 64;
+struct PerDeviceOnce {
+  bool done[kMaxDevices] = {};
+};
+inline hipError_t current_device_slot(int* dev) {
+  hipError_t e = hipGetDevice(dev);
+  if (e != hipSuccess) return e;
+  return (*dev >= 0 && *dev < kMaxDevices) ? hipSuccess : hipErrorInvalidDevice;
+}
+template <typename Kernel>
+inline hipError_t raise_dynamic_lds_limit(Kernel kern, int bytes, PerDeviceOnce& once) {
+  int dev = 0;
+  hipError_t e = current_device_slot(&dev);
+  if (e != hipSuccess) return e;
+  if (once.done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  once.done[dev] = true;
+  return hipSuccess;
+}
+// Compute units of the current device (cached per device).
+inline hipError_t compute_units(int* n) {
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = current_device_slot(&dev);
+  if (e != hipSuccess) return e;
+  if (!cached[dev]) {
+    int cus = 0;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    cached[dev] = cus > 0 ? cus : 1;
+  }
+  *n = cached[dev];
+  return hipSuccess;
+}
+
 struct PackDesc {
   const bf16_t* W;
   bf16_t* values;
@@ -124,6 +162,12 @@ struct StreamI8Args {
 };
 bool stream_i8_takes(int64_t O, int64_t K, int64_t T, int N, int M);
 hipError_t launch_stream_i8(const StreamI8Args& a, hipStream_t s);
+
+// nm_probe.hip: measurement aids (matrix-instruction rate, streaming copy rate)
+constexpr int kMaxProbeBlocks = 2048;
+size_t probe_sink_bytes();
+hipError_t launch_probe_matrix(int kind, int iters, float* sink, int64_t* ops, hipStream_t s);
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 // nm_int8.hip: the int8 layer.  Phases as for launch_spmm.
 struct I8LinearArgs {

@@ -21,8 +21,6 @@
 #include "nm_launch.h"
 #include "nm_mma.h"
 
-#include <stdlib.h>
-
 #include <type_traits>
 #include <utility>
 
@@ -1071,11 +1069,9 @@ static bool tiles_ok(int64_t K, const void* X, int64_t ldx, const void* values, 
 // Which product kernel a layer of O out-features runs at T tokens: 0 = the persistent 256 x 256 kernel
 // (needs the weight in stream order), 1.. = the tiled kernel with smaller tiles (row-major operand form).
 static int pick_tile(int64_t O, int64_t T) {
-  static const int forced = getenv("NM_GEMM_TILE") ? atoi(getenv("NM_GEMM_TILE")) : -1;  // tuning aid
   const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
   const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
-  int pick = forced >= 0 ? forced : (tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3));
-  if (pick != 0 && pick != 2) pick = 3;
+  int pick = tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3);
   if (pick == 0 && T < 256) pick = 2;
   return pick;
 }
@@ -1105,13 +1101,8 @@ template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
 static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
   auto kern = nm_gemm_kernel<SPARSE, WO, WT, OT, TT, STAGES>;
-  static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static PerDeviceOnce lds_limit;
+  if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
   g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
   g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
   const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
@@ -1141,13 +1132,8 @@ static hipError_t launch_gemm_group(GemmGroup& grp, hipStream_t s) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
   if (grp.count == 0) return hipSuccess;
   auto kern = nm_gemm_group_kernel<SPARSE, WO, WT, OT, TT, STAGES>;
-  static bool attr_done = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static PerDeviceOnce lds_limit;
+  if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
   // deepest layers first, so that the launch ends with the shortest tiles; the block counts move with them
   for (int i = 1; i < grp.count; ++i) {
     const GemmArgs L = grp.layer[i];
@@ -1169,16 +1155,11 @@ template <bool SPARSE, bool I8 = false>
 static hipError_t launch_stream_group(const StreamGroup& grp, hipStream_t s) {
   using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;  // dense stages are half the size: four fit
   auto kern = nm_stream_kernel<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;
-  static int n_cu = 0;  // filled once; a race only repeats the query
-  if (!n_cu) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    int dev = 0, cus = 0;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    n_cu = cus > 8 ? (cus / 8) * 8 : 8;
-  }
+  static PerDeviceOnce lds_limit;
+  if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
+  int cus = 0;
+  if (hipError_t e = compute_units(&cus); e != hipSuccess) return e;
+  const int n_cu = cus > 8 ? (cus / 8) * 8 : 8;
   const int64_t want = (((int64_t)grp.n_tiles + 7) / 8) * 8;
   const int64_t resident = (int64_t)n_cu * C::PER_CU;  // persistent blocks: as many as fit at once
   const unsigned grid = (unsigned)(want < resident ? want : resident);

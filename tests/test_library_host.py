@@ -350,3 +350,12 @@ def test_forward_batched_argument_errors(lib):
     assert run({}, dict(out_dtype=2)) == 5 and run({}, dict(Y=FAKE + 2)) == 4
     assert run({}, dict(N=1, M=8)) == 6  # a level that needs a prepared workspace
     assert run({}, dict(N=1, M=8, workspace=FAKE, workspace_bytes=16)) == 6
+
+
+def test_weights_beyond_the_grid_limit_are_refused(lib):
+    # O * K above 2^40: some launcher's grid would not fit; reported as a shape error, nothing launched
+    big = 1 << 21
+    assert lib.nm_values_bytes(big, big, 2, 4) == 0
+    assert lib.nm_prune(FAKE, big, big, big, 2, 4, FAKE, None, None) == 2
+    assert lib.nm_unpack(FAKE, FAKE, big, big, 2, 4, FAKE, big, None) == 2
+    assert lib.nm_values_bytes(1 << 20, 1 << 20, 2, 4) == (1 << 40)
