@@ -43,7 +43,7 @@
  *   "host".  The library allocates no device memory.  Its only state: the last HIP
  *   error code of the calling thread, and per device (a process may use several, the
  *   current one at call time is used) a few marks of one-time setup: the dynamic-LDS limit
- *   raised per kernel, the compute-unit count.  No
+ *   raised per kernel, the compute-unit count, the address of the static scratch.  No
  *   environment variable is read.  `stream` is a hipStream_t passed as void* (NULL = the null
  *   stream).  Calls validate their arguments on the host, enqueue their kernels on
  *   `stream` and return without synchronising.  Argument errors are reported before
@@ -228,6 +228,23 @@ int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_
                           int32_t N, int32_t M, const nm_bf16* X, int64_t T, int64_t ldx,
                           const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * nm_linear_forward_static -- nm_linear_forward for callers that cannot allocate device memory and so cannot
+ * bring a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  The
+ * scratch is a fixed array of nm_static_scratch_bytes() bytes (8 MiB) inside the library's device image; every
+ * device the library runs on holds its own copy until the process ends.  The call allocates and frees nothing.
+ *   Arguments and results as nm_linear_forward (same kernels, same bytes written to Y).
+ *   NM_ERR_WORKSPACE  the layer needs more scratch than the array holds
+ *                     (nm_spmm_workspace_bytes(O, K, N, M, T) > nm_static_scratch_bytes()); nothing is launched.
+ * All calls on one device share that device's array: two such calls whose kernels may overlap (different streams,
+ * or threads) race on it; calls on one stream are ordered and safe.  The array keeps the last call's contents;
+ * every call rewrites the part it reads, so nothing needs clearing.
+ */
+size_t nm_static_scratch_bytes(void);
+int32_t nm_linear_forward_static(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K,
+                                 int32_t N, int32_t M, const nm_bf16* X, int64_t T, int64_t ldx,
+                                 const float* bias, void* Y, int64_t ldy, int32_t out_dtype, void* stream);
 
 /*
  * The two halves of nm_linear_forward, for callers whose weights stay fixed across many calls (a

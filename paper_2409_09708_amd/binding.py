@@ -21,6 +21,7 @@ EXPORTS = (
     "nm_status_string", "nm_last_hip_error", "nm_values_bytes", "nm_index_bytes", "nm_mask_bytes",
     "nm_spmm_workspace_bytes", "nm_prune", "nm_pack", "nm_pack_batched", "nm_unpack", "nm_mask_check",
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
+    "nm_static_scratch_bytes", "nm_linear_forward_static",
     "nm_probe_sink_bytes", "nm_probe_matrix_rate", "nm_probe_copy",
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_ranked_batched", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
@@ -109,6 +110,11 @@ def load_library() -> ctypes.CDLL:
                                     c_void_p]
     lib.nm_linear_forward_prepared.restype = c_int32
     lib.nm_linear_forward_prepared.argtypes = lib.nm_linear_forward.argtypes
+    lib.nm_static_scratch_bytes.restype = c_size_t
+    lib.nm_static_scratch_bytes.argtypes = []
+    lib.nm_linear_forward_static.restype = c_int32
+    lib.nm_linear_forward_static.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64,
+                                             c_int64, c_void_p, c_void_p, c_int64, c_int32, c_void_p]
     lib.nm_probe_sink_bytes.restype = c_size_t
     lib.nm_probe_sink_bytes.argtypes = []
     lib.nm_probe_matrix_rate.restype = c_int32
@@ -550,6 +556,35 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
         st = lib.nm_linear_forward(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T, ldx, bias_ptr,
                                    out.data_ptr(), ldy, code, ws_ptr, ws_bytes, _stream_handle(stream))
     _check(st)
+    return out
+
+
+def nm_static_scratch_bytes() -> int:
+    return int(load_library().nm_static_scratch_bytes())
+
+
+def nm_linear_forward_static(values, indices, K: int, N: int, M: int, X, bias=None, out_dtype=None, out=None,
+                             stream=None):
+    """nm_linear_forward on the library's own fixed scratch: the call itself allocates nothing (pass `out`)."""
+    torch = _torch()
+    _need(values, torch.bfloat16, "values")
+    _need(indices, torch.int32, "indices")
+    _need(X, torch.bfloat16, "X")
+    if not values.is_contiguous() or not indices.is_contiguous():
+        raise ValueError("packed tensors must be contiguous")
+    O = int(values.shape[0])
+    T, KX, ldx = _rows(X, "X")
+    if KX != K:
+        raise ValueError("X must be [T, K]")
+    out, ldy, code = _out_matrix(out, out_dtype, T, O, X.device, "out")
+    bias_ptr = None
+    if bias is not None:
+        _need(bias, torch.float32, "bias")
+        if bias.numel() != O or not bias.is_contiguous():
+            raise ValueError("bias must be contiguous [O]")
+        bias_ptr = bias.data_ptr()
+    _check(load_library().nm_linear_forward_static(values.data_ptr(), indices.data_ptr(), O, K, N, M, X.data_ptr(), T,
+                                                   ldx, bias_ptr, out.data_ptr(), ldy, code, _stream_handle(stream)))
     return out
 
 

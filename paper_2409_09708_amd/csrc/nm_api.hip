@@ -5,10 +5,34 @@
 #include "nm_device.h"
 #include "nm_launch.h"
 
+#include <atomic>
+
 namespace {
 
 thread_local int32_t g_last_hip_error = 0;
 
+// Scratch of nm_linear_forward_static: device memory that exists as long as the library is loaded, one copy on
+// every device the library runs on.  In host code the array's name is only a handle; the memory's address on the
+// current device comes from hipGetSymbolAddress (asked once per device) and is what the kernels receive.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<unsigned char*> g_scratch_ptr[nm::kMaxDevices];
+
+hipError_t static_scratch(unsigned char** ptr) {
+  int dev = 0;
+  hipError_t e = nm::current_device_slot(&dev);
+  if (e != hipSuccess) return e;
+  unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    void* addr = nullptr;
+    if ((e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    if (addr == nullptr) return hipErrorInvalidSymbol;
+    p = static_cast<unsigned char*>(addr);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return hipSuccess;
+}
 
 inline int32_t device_status(hipError_t e) {
   if (e == hipSuccess) return NM_OK;
@@ -280,6 +304,25 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
                                    void* stream) {
   return spmm_entry(values, indices, O, K, N, M, X, T, ldx, bias, Y, ldy, out_dtype, const_cast<void*>(workspace),
                     workspace_bytes, stream, nm::SPMM_PRODUCT);
+}
+
+size_t nm_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int32_t nm_linear_forward_static(const nm_bf16* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N,
+                                 int32_t M, const nm_bf16* X, int64_t T, int64_t ldx, const float* bias, void* Y,
+                                 int64_t ldy, int32_t out_dtype, void* stream) {
+  nm::SpmmArgs a;
+  if (int32_t st = spmm_check(values, indices, O, K, N, M, X, T, ldx, bias, Y, ldy, out_dtype, nullptr, 0, true, &a))
+    return st;
+  if (nm::spmm_workspace_bytes(O, K, N, M, T) > kStaticScratchBytes) return NM_ERR_WORKSPACE;
+  unsigned char* ws = nullptr;
+  if (int32_t st = device_status(static_scratch(&ws))) return st;
+  a.workspace = ws;
+  a.workspace_bytes = kStaticScratchBytes;
+  bool workspace_short = false;
+  hipError_t e = nm::launch_spmm(a, (hipStream_t)stream, &workspace_short, nm::SPMM_PREPARE | nm::SPMM_PRODUCT);
+  if (workspace_short) return NM_ERR_WORKSPACE;
+  return device_status(e);
 }
 
 size_t nm_backward_weight_workspace_bytes(int64_t O, int64_t K, int64_t T) {

@@ -352,6 +352,22 @@ def test_forward_batched_argument_errors(lib):
     assert run({}, dict(N=1, M=8, workspace=FAKE, workspace_bytes=16)) == 6
 
 
+def test_static_scratch_entry_argument_errors(lib):
+    # the entry point for callers that cannot allocate: argument errors and the size limit come before any
+    # device call, so they are checked here without a GPU
+    cap = lib.nm_static_scratch_bytes()
+    assert cap == 8 << 20
+    ok = (FAKE, FAKE, 64, 64, 1, 8, FAKE, 16, 64, None, FAKE, 64, 0, None)
+    bad = lambda i, v: lib.nm_linear_forward_static(*(ok[:i] + (v,) + ok[i + 1:]))
+    assert bad(0, None) == 1 and bad(1, None) == 1 and bad(6, None) == 1 and bad(10, None) == 1
+    assert bad(4, 9) == 3 and bad(3, 60) == 2 and bad(7, 0) == 2 and bad(8, 32) == 2 and bad(11, 8) == 2
+    assert bad(12, 2) == 5 and bad(6, FAKE + 1) == 4 and bad(9, FAKE + 2) == 4
+    # a layer whose operand-order copy does not fit the fixed scratch is refused (dense form of 4096 x 4096 at
+    # 65536 tokens: 32 MiB)
+    assert lib.nm_spmm_workspace_bytes(4096, 4096, 4, 8, 65536) > cap
+    assert lib.nm_linear_forward_static(FAKE, FAKE, 4096, 4096, 4, 8, FAKE, 65536, 4096, None, FAKE, 4096, 1, None) == 6
+
+
 def test_weights_beyond_the_grid_limit_are_refused(lib):
     # O * K above 2^40: some launcher's grid would not fit; reported as a shape error, nothing launched
     big = 1 << 21
