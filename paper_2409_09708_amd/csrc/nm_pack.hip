@@ -8,6 +8,9 @@
 // byte or not byte aligned (3-bit fields, 1:16) are assembled into words in LDS first.
 #include "nm_device.h"
 #include "nm_launch.h"
+#include "nm_select.h"
+
+#include <type_traits>
 
 namespace nm {
 
@@ -87,18 +90,25 @@ __device__ __forceinline__ void store_values(bf16_t* __restrict__ dst, const uin
   }
 }
 
+// Levels whose magnitude selection runs on order keys and max/min networks (nm_select.h): about a quarter of the
+// vector instructions of the all-pairs ranking, which is what bounds these kernels.
+template <int N, int M>
+constexpr bool kFastLevel = (N == 1 || N == 2 || N == 4) && N < M;
+
 // Work of one block on 256 consecutive chunks of one contiguous matrix.
 //   values/indices may be NULL (prune only); mask_out / w_masked may be NULL (pack only).
 // SRC: where the selection comes from: 0 = magnitude (Eq. (1)), 1 = the caller's mask words, 2 = stored ranks
 // (4 bits per weight; kept = rank < N)
+// stream_ws (magnitude selection at the fast levels only): the product kernel's operand order, written beside the
+// packed form.
 template <int N, int M, int SRC>
 __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, int64_t chunk0,
                                            const uint32_t* __restrict__ mask_in, bf16_t* __restrict__ values,
                                            uint32_t* __restrict__ indices, uint32_t* __restrict__ mask_out,
                                            bf16_t* w_masked, uint32_t* sbits, unsigned char* stream_ws = nullptr,
                                            int64_t K = 0) {
-  constexpr bool EXTERNAL_MASK = SRC != 0;
-  using Coder = ChunkCoder<N, M, EXTERNAL_MASK>;
+  constexpr bool FAST = SRC == 0 && kFastLevel<N, M>;
+  using Coder = std::conditional_t<FAST, FastChunkCoder<N, M>, ChunkCoder<N, M, SRC != 0>>;
   constexpr int NB = Coder::NB;
   constexpr bool DIRECT_INDEX = (NB == 8 || NB == 16 || NB == 32 || NB == 64);
   constexpr int BLOCK_WORDS = kPackThreads * NB / 32;
@@ -110,22 +120,29 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
     for (int i = tid; i < BLOCK_WORDS + 2; i += kPackThreads) sbits[i] = 0;
     __syncthreads();
   }
-  Coder coder;
   if (active) {
-    uint32_t e[kChunk];
     const uint4* src = reinterpret_cast<const uint4*>(W + c * kChunk);
     const uint4 a = src[0], b = src[1];
     const uint32_t d[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    Coder coder;
+    uint32_t keep16 = 0;
+    if constexpr (FAST) {
+      coder.run(d);
+      if (mask_out || w_masked || (stream_ws && N > 2)) keep16 = coder.keep16();
+    } else {
+      uint32_t e[kChunk];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { e[2 * i] = d[i] & 0xFFFFu; e[2 * i + 1] = d[i] >> 16; }
-    uint32_t mask16 = 0;
-    if (SRC == 1) mask16 = reinterpret_cast<const uint16_t*>(mask_in)[c];
-    if (SRC == 2) {
-      const uint64_t r = reinterpret_cast<const uint64_t*>(mask_in)[c];
+      for (int i = 0; i < 8; ++i) { e[2 * i] = d[i] & 0xFFFFu; e[2 * i + 1] = d[i] >> 16; }
+      uint32_t mask16 = 0;
+      if (SRC == 1) mask16 = reinterpret_cast<const uint16_t*>(mask_in)[c];
+      if (SRC == 2) {
+        const uint64_t r = reinterpret_cast<const uint64_t*>(mask_in)[c];
 #pragma unroll
-      for (int i = 0; i < kChunk; ++i) mask16 |= (((uint32_t)(r >> (4 * i)) & 15u) < (uint32_t)N ? 1u : 0u) << i;
+        for (int i = 0; i < kChunk; ++i) mask16 |= (((uint32_t)(r >> (4 * i)) & 15u) < (uint32_t)N ? 1u : 0u) << i;
+      }
+      coder.run(e, mask16);
+      keep16 = coder.keep16;
     }
-    coder.run(e, mask16);
 
     if (values) store_values<Coder::NV>(values + c * Coder::NV, coder.vals);
     if (indices) {
@@ -135,67 +152,43 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
       else if constexpr (NB == 64) reinterpret_cast<uint64_t*>(indices)[c] = coder.ibits;
       else {
         const int off = tid * NB;
-        const int w = off >> 5, s = off & 31;
-        const uint64_t lo = coder.ibits << s;
-        const uint32_t hi = s ? (uint32_t)(coder.ibits >> (64 - s)) : 0u;
+        const int w = off >> 5, sh = off & 31;
+        const uint64_t lo = coder.ibits << sh;
+        const uint32_t hi = sh ? (uint32_t)(coder.ibits >> (64 - sh)) : 0u;
         if ((uint32_t)lo) atomicOr(&sbits[w], (uint32_t)lo);
         if ((uint32_t)(lo >> 32)) atomicOr(&sbits[w + 1], (uint32_t)(lo >> 32));
         if (hi) atomicOr(&sbits[w + 2], hi);
       }
     }
-    if (mask_out) reinterpret_cast<uint16_t*>(mask_out)[c] = (uint16_t)coder.keep16;
-    if (stream_ws) {
-      // the product kernel's operand order, written beside the packed form (what nm_spmm_prepare would
-      // write from it): this lane's 16 weights are one 16-byte chunk of a row's K step
-      const int64_t per_row = K / kChunk;
-      const int64_t o = c / per_row, kc = c % per_row;
-      if constexpr (N <= 2 && N < M) {
-        // 2:4 form: per run of four the kept weights in ascending position (at most two), zero-filled, and
-        // their 2-bit positions
-        const int64_t nk = K / 64;
-        uint32_t piece[4], sel = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          uint32_t slot0 = 0, slot1 = 0, cnt = 0;
-#pragma unroll
-          for (int p = 0; p < 4; ++p) {
-            const bool k = (coder.keep16 >> (4 * r + p)) & 1u;
-            slot0 = (k && cnt == 0) ? e[4 * r + p] : slot0;
-            slot1 = (k && cnt == 1) ? e[4 * r + p] : slot1;
-            sel |= k ? ((uint32_t)p << (4 * r + 2 * (cnt ? 1 : 0))) : 0u;
-            cnt += k ? 1u : 0u;
-          }
-          piece[r] = slot0 | (slot1 << 16);
+    if (mask_out) reinterpret_cast<uint16_t*>(mask_out)[c] = (uint16_t)keep16;
+    if constexpr (FAST) {
+      if (stream_ws) {
+        // this lane's 16 weights are one 16-byte chunk of a row's K step (2:4 form), or two of them (dense form)
+        const int64_t per_row = K / kChunk;
+        const int64_t o = c / per_row, kc = c % per_row;
+        if constexpr (N <= 2) {
+          const int64_t nk = K / 64;
+          uint32_t piece[4], sel;
+          coder.sparse_operand(piece, sel);
+          *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, kc >> 2, (int)(kc & 3), nk)) =
+              make_uint4(piece[0], piece[1], piece[2], piece[3]);
+          unsigned char* sel_s = stream_ws + (size_t)(n_chunks * 16);  // the values take O*K bytes: 16 per chunk
+          *reinterpret_cast<uint16_t*>(sel_s + stream_selector_offset(o, kc >> 2, (int)(kc & 3), nk)) = (uint16_t)sel;
+        } else {
+          const int64_t nk = K / 32;
+          uint32_t w[8];
+          mask_chunk(d, keep16, w);
+          const int64_t pc = kc * 2;
+          *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, pc >> 2, (int)(pc & 3), nk)) =
+              make_uint4(w[0], w[1], w[2], w[3]);
+          *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, (pc + 1) >> 2, (int)((pc + 1) & 3), nk)) =
+              make_uint4(w[4], w[5], w[6], w[7]);
         }
-        *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, kc >> 2, (int)(kc & 3), nk)) =
-            make_uint4(piece[0], piece[1], piece[2], piece[3]);
-        unsigned char* sel_s = stream_ws + (size_t)(n_chunks * 16);  // the values take O*K bytes: 16 per chunk
-        *reinterpret_cast<uint16_t*>(sel_s + stream_selector_offset(o, kc >> 2, (int)(kc & 3), nk)) = (uint16_t)sel;
-      } else {
-        // dense form: the masked weights, two 16-byte pieces of a 32-wide step
-        const int64_t nk = K / 32;
-        uint32_t w[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const uint32_t lo = ((coder.keep16 >> (2 * i)) & 1u) ? e[2 * i] : 0u;
-          const uint32_t hi = ((coder.keep16 >> (2 * i + 1)) & 1u) ? e[2 * i + 1] : 0u;
-          w[i] = lo | (hi << 16);
-        }
-        const int64_t pc = kc * 2;
-        *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, pc >> 2, (int)(pc & 3), nk)) =
-            make_uint4(w[0], w[1], w[2], w[3]);
-        *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, (pc + 1) >> 2, (int)((pc + 1) & 3), nk)) =
-            make_uint4(w[4], w[5], w[6], w[7]);
       }
     }
     if (w_masked) {
       uint32_t o[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t lo = ((coder.keep16 >> (2 * i)) & 1u) ? e[2 * i] : 0u;
-        const uint32_t hi = ((coder.keep16 >> (2 * i + 1)) & 1u) ? e[2 * i + 1] : 0u;
-        o[i] = lo | (hi << 16);
-      }
+      mask_chunk(d, keep16, o);
       uint4* dst = reinterpret_cast<uint4*>(w_masked + c * kChunk);
       dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
       dst[1] = make_uint4(o[4], o[5], o[6], o[7]);

@@ -928,9 +928,11 @@ nm_stream_kernel(const StreamGroup g) {
     // ---- write the tile out (no LDS memory: the stage ring already holds the next tile).  A lane holds
     // out-features o .. o+3 of token r16 per 16 x 16 block; for bfloat16 two blocks are exchanged between
     // the lane rows kb and kb^1, so that every lane owns 8 consecutive out-features (16 bytes), and a lane
-    // permutation then puts the four pieces of a row's 64-byte segment into four consecutive lanes: a store
-    // instruction is merged only across consecutive lanes, and 16 requests of 64 bytes go through where 64 of
-    // 16 bytes did (2 % of the whole stack).
+    // permutation then puts the eight pieces of a token row's 128 bytes (the wave's 64 out-features) into eight
+    // consecutive lanes: a store instruction is merged only across consecutive lanes, and whole lines leave as
+    // single requests.  The stores carry the non-temporal hint: the output is never read back by this kernel, and
+    // lines that linger in L2 until write-back push out the X rows the neighbouring tiles still need (with the
+    // hint the launch fetches a quarter less; on half lines the same hint costs 40 % more written bytes).
     // int8: the sums are rescaled first, y = fma(float(acc), x_scale * w_scale[o], bias[o]); the tile's scales
     // and bias came with its first stage (pair n mod 2, so the next tile's do not overwrite them)
     f32x4_t sc[I8 ? OT : 1], bi[I8 ? OT : 1];
@@ -965,40 +967,57 @@ nm_stream_kernel(const StreamGroup g) {
     using gpiece_t = __attribute__((address_space(1))) u32x4_t;
     const int first_row = (int)(t_lo - t0);  // rows of a shifted last tile below this one belong to its neighbour
     if (kind_s == 1) {
-      // lane 4m + q takes the piece of lane (token row m, kb = 0, 2, 1, 3 for q = 0 .. 3)
-      const int q4 = lane & 3;
-      const int src_lane = (lane >> 2) + 16 * (((q4 & 1) << 1) | (q4 >> 1));
-      // item n = (token block j, out-feature pair ip): convert, exchange, permute; the permuted piece of one item
-      // is stored while the permutation of the next one is under way
-      auto permuted = [&](int j, int ip) {
+      // Whole 128-byte lines per store: a wave's 64 out-features are one line of a token row.  The two 16-byte
+      // pieces a lane holds for a token block (out-feature pairs 0 and 1, after the exchange between lane rows)
+      // are pushed to the lanes that store them: lane 8m + p stores piece p (0..7) of token row m (first store) and
+      // of token row m + 8 (second store).
+      static_assert(OT == 4, "two out-feature pairs per wave");
+      const int qk = ((kb & 1) << 1) | (kb >> 1);            // place of this lane's piece inside its pair's 64 bytes
+      const int hi_rows = r16 >> 3;                          // this lane's token row belongs to the second store
+      const int dest_a = (8 * (r16 & 7) + 4 * hi_rows + qk) * 4;
+      const int dest_b = (8 * (r16 & 7) + 4 * (1 - hi_rows) + qk) * 4;
+      const bool upper = (lane >> 2) & 1;                    // as a storing lane: pieces 4..7 (out-feature pair 1)
+      auto swapped = [&](int j, int ip) {
         const f32x4_t v0 = value(2 * ip, j), v1 = value(2 * ip + 1, j);
         const uint32_t a0 = pack_bf16x2(v0[0], v0[1]), a1 = pack_bf16x2(v0[2], v0[3]);
         const uint32_t b0 = pack_bf16x2(v1[0], v1[1]), b1 = pack_bf16x2(v1[2], v1[3]);
-        // even lane rows keep their first operand and receive the odd partner's; odd rows receive the
-        // even partner's second operand and keep theirs
         const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
         const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
-        u32x4_t piece = u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) piece[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane * 4, (int)piece[e]);
-        return piece;
+        return u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
       };
-      const int row = wt * 128 + (lane >> 2);                            // this lane's row of the tile in block j = 0
-      const int64_t col = o0 + wo * C::OW + q4 * 8;                      // its out-feature for ip = 0
+      struct Lines { u32x4_t first, second; };
+      auto lines_of = [&](int j) {
+        const u32x4_t p0 = swapped(j, 0), p1 = swapped(j, 1);
+        u32x4_t ra, rb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          // rows 0..7 send pair 0 the first way and pair 1 the second way, rows 8..15 the other way round
+          const int send_a = hi_rows ? (int)p1[e] : (int)p0[e];
+          const int send_b = hi_rows ? (int)p0[e] : (int)p1[e];
+          ra[e] = (uint32_t)__builtin_amdgcn_ds_permute(dest_a, send_a);
+          rb[e] = (uint32_t)__builtin_amdgcn_ds_permute(dest_b, send_b);
+        }
+        Lines l;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          l.first[e] = upper ? rb[e] : ra[e];
+          l.second[e] = upper ? ra[e] : rb[e];
+        }
+        return l;
+      };
+      const int row = wt * 128 + (lane >> 3);                            // this lane's row of the tile in block j = 0, first store
+      const int64_t col = o0 + wo * C::OW + (lane & 7) * 8;              // its out-features
       gbyte_t* dst = (gbyte_t*)y_s + ((t0 + row) * (int64_t)ldy_s + col) * 2;
-      const int64_t block_bytes = (int64_t)ldy_s * 32;                   // 16 token rows further
-      bool col_ok[OT / 2];
+      const int64_t half_bytes = (int64_t)ldy_s * 16;                    // 8 token rows further
+      const bool col_ok = col < o_s;
+      Lines cur = lines_of(0);
 #pragma unroll
-      for (int ip = 0; ip < OT / 2; ++ip) col_ok[ip] = col + 2 * ip * 16 < o_s;
-      constexpr int ITEMS = TT * (OT / 2);
-      u32x4_t cur = permuted(0, 0);
-#pragma unroll
-      for (int n = 0; n < ITEMS; ++n) {
-        const int j = n / (OT / 2), ip = n % (OT / 2);
-        u32x4_t nxt = cur;
-        if (n + 1 < ITEMS) nxt = permuted((n + 1) / (OT / 2), (n + 1) % (OT / 2));
-        if (row + j * 16 >= first_row && col_ok[ip]) *(gpiece_t*)(dst + ip * 64) = cur;
-        if (ip == OT / 2 - 1) dst += block_bytes;
+      for (int j = 0; j < TT; ++j) {
+        Lines nxt = cur;
+        if (j + 1 < TT) nxt = lines_of(j + 1);
+        if (row + j * 16 >= first_row && col_ok) __builtin_nontemporal_store(cur.first, (gpiece_t*)(dst));
+        if (row + j * 16 + 8 >= first_row && col_ok) __builtin_nontemporal_store(cur.second, (gpiece_t*)(dst + half_bytes));
+        dst += 2 * half_bytes;
         cur = nxt;
       }
     } else {
