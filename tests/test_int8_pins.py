@@ -89,3 +89,73 @@ def test_pruned_weights_are_ignored_whatever_they_hold():
     other = wq.copy()
     other[~mask] = 99
     assert np.array_equal(q.nm_accumulate_i8(xq, wq, mask), q.nm_accumulate_i8(xq, other, mask))
+
+
+# ---- the compressed int8 form ---------------------------------------------------------------------------------
+
+def test_packed_int8_hand_example():
+    # the worked 2:4 group of tests/golden/hand_example_2to4.txt scaled to integers: weights (5, -20, 10, -10)
+    # keep positions 1 and 2, so values (-20, 10) and the two 2-bit fields 1, 2 -> nibble 0b1001; a second group
+    # (7, 0, 0, -3) keeps positions 0 and 3 -> fields 0, 3 -> nibble 0b1100; LSB first: byte 0xC9
+    wq = np.array([[5, -20, 10, -10, 7, 0, 0, -3]], dtype=np.int8)
+    mask = np.array([[0, 1, 1, 0, 1, 0, 0, 1]], dtype=bool)
+    values, indices = q.nm_pack_i8(wq, mask, 2, 4)
+    assert values.tolist() == [[-20, 10, 7, -3]]
+    assert indices.tolist() == [[0xC9]]
+    assert np.array_equal(q.nm_unpack_i8(values, indices, 8, 2, 4), np.where(mask, wq, 0))
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (3, 4), (1, 8), (2, 8), (3, 8), (4, 8), (1, 16), (2, 16), (4, 16), (8, 8)])
+def test_packed_int8_index_stream_is_the_float_layers(N, M):
+    # the positions depend on the mask alone: the index words must be those the (pinned) bfloat16 checker writes
+    # for any weight with the same mask; 3-bit fields straddle words at K = 96 (36 bits at 1:8, 108 at 3:8)
+    rng = np.random.default_rng(300 + N + M)
+    O, K = 5, 96 if M == 8 else 64
+    wq = wl.draw_int8(rng, O, K)
+    mask = legal_mask(rng, O, K, N, M)
+    values, indices = q.nm_pack_i8(wq, mask, N, M)
+    wb = wl.f32_to_bf16_bits(wq.astype(np.float32))
+    fvals, findex = orc.nm_pack(wb, mask, N, M)
+    assert np.array_equal(indices, findex)
+    # and the values are the float layer's values (integers up to 127 are exact in bfloat16)
+    assert np.array_equal(values.astype(np.float64), orc.bf16_bits_to_f64(fvals))
+    # sizes: N/M of the weights, log2(M) bits each, rows padded to words
+    assert values.shape == (O, K // M * N) and indices.shape == (O, orc.index_words_per_row(K, N, M))
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (2, 8), (4, 8), (1, 16), (4, 16)])
+def test_packed_int8_round_trip_and_kept_values_by_definition(N, M):
+    rng = np.random.default_rng(400 + N + M)
+    O, K = 4, 4 * M
+    wq = wl.draw_int8(rng, O, K)
+    wq[0, :M] = -128  # the extreme value survives packing
+    mask = legal_mask(rng, O, K, N, M)
+    values, indices = q.nm_pack_i8(wq, mask, N, M)
+    assert np.array_equal(q.nm_unpack_i8(values, indices, K, N, M), np.where(mask, wq, 0))
+    # by definition: the j-th kept weight of group g, counted in ascending position
+    for o in range(O):
+        for g in range(K // M):
+            kept = [int(wq[o, g * M + p]) for p in range(M) if mask[o, g * M + p]]
+            assert values[o, g * N:(g + 1) * N].tolist() == kept
+    # padding bits of the last index word are zero
+    used = (K // M * N * {4: 2, 8: 3, 16: 4}[M]) % 32
+    if used:
+        assert np.all(indices[:, -1] >> np.uint32(used) == 0)
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (2, 8), (4, 16)])
+def test_gather_form_on_the_packed_int8_equals_the_masked_product(N, M):
+    rng = np.random.default_rng(500 + N + M)
+    T, O, K = 3, 4, 2 * M
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = legal_mask(rng, O, K, N, M)
+    values, indices = q.nm_pack_i8(wq, mask, N, M)
+    assert np.array_equal(q.nm_accumulate_i8_packed_loops(values, indices, xq, K, N, M),
+                          q.nm_accumulate_i8_loops(xq, wq, mask))
+
+
+def test_packed_int8_rejects_an_illegal_mask():
+    wq = np.zeros((1, 8), dtype=np.int8)
+    mask = np.array([[1, 1, 1, 0, 0, 0, 0, 1]], dtype=bool)
+    with pytest.raises(ValueError):
+        q.nm_pack_i8(wq, mask, 2, 4)
