@@ -382,6 +382,42 @@ int32_t nm_linear_forward_i8_prepared(const int8_t* Wq, int64_t O, int64_t K, in
                                       int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Compressed form of the int8 layer (Section 1 and Section 2, Fig. 2 upper part, for the quantised sparse weight of
+ * Section 4's Table 6): the kept int8 values of every group in ascending position, int8 [O, K*N/M]
+ * (nm_values_i8_bytes), and for each its log2(M)-bit position in the index stream of the bfloat16 layer
+ * (nm_index_bytes; the positions depend on the mask alone).  Half the bytes of the bfloat16 values, and
+ * N/M * (1 + log2(M)/8) bytes per weight instead of the 1 + 1/8 of dense weight + mask words.
+ *   nm_pack_i8      Wq [O, K] (ld ldw) under `mask` (mask words as nm_prune writes them; a mask without exactly N
+ *                   bits in a group is made usable as in nm_pack: the N lowest set positions, missing ones completed
+ *                   with the lowest unset positions stored as 0) -> values, indices.
+ *   nm_unpack_i8    the inverse: Wq_dense[o, g*M + position] = value, 0 elsewhere; every element of the O x K block
+ *                   is written.
+ *   nm_linear_forward_i8_packed, nm_i8_prepare_packed, nm_linear_forward_i8_packed_prepared
+ *                   nm_linear_forward_i8, nm_i8_prepare and nm_linear_forward_i8_prepared with the weight given in
+ *                   this form; same workspace (nm_i8_workspace_bytes), same bytes in it, same results.  The matrix-core
+ *                   kernels need K % 128 == 0, a 16-byte aligned Xq and ldx a multiple of 16; other shapes run a
+ *                   general kernel on the compressed form.
+ * Errors: NM_ERR_NULL, NM_ERR_LEVEL, NM_ERR_SHAPE, NM_ERR_ALIGN (mask, indices: 4 bytes), NM_ERR_DTYPE,
+ * NM_ERR_WORKSPACE, NM_ERR_DEVICE; nothing is launched on an argument error.
+ */
+size_t nm_values_i8_bytes(int64_t O, int64_t K, int32_t N, int32_t M);
+int32_t nm_pack_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M, const uint32_t* mask,
+                   int8_t* values, uint32_t* indices, void* stream);
+int32_t nm_unpack_i8(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                     int8_t* Wq_dense, int64_t ldw, void* stream);
+int32_t nm_linear_forward_i8_packed(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N,
+                                    int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
+                                    const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+int32_t nm_i8_prepare_packed(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                             int64_t T, void* workspace, size_t workspace_bytes, void* stream);
+int32_t nm_linear_forward_i8_packed_prepared(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K,
+                                             int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx,
+                                             float x_scale, const float* w_scale, const float* bias, void* Y,
+                                             int64_t ldy, int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                             void* stream);
+
+/*
  * nm_pack_prepare_batched -- for every descriptor nm_pack(mask = NULL) followed by nm_spmm_prepare, in as few
  * launches as the shapes allow: a model's layers are compressed and made ready for their products together
  * (Section 3, configuration alpha = (s^1 ... s^L); Section 3.1: the sparse weights are derived from the shared

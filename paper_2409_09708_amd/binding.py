@@ -23,6 +23,8 @@ EXPORTS = (
     "nm_spmm", "nm_linear_forward", "nm_spmm_prepare", "nm_linear_forward_prepared",
     "nm_static_scratch_bytes", "nm_linear_forward_static",
     "nm_probe_sink_bytes", "nm_probe_matrix_rate", "nm_probe_copy",
+    "nm_values_i8_bytes", "nm_pack_i8", "nm_unpack_i8", "nm_linear_forward_i8_packed", "nm_i8_prepare_packed",
+    "nm_linear_forward_i8_packed_prepared",
     "nm_rank_bytes", "nm_rank", "nm_rank_batched", "nm_rank_mask", "nm_pack_ranked", "nm_pack_ranked_batched", "nm_pack_prepare_batched",
     "nm_config_cost", "nm_sample_config",
     "nm_backward_input_workspace_bytes", "nm_backward_weight_workspace_bytes", "nm_linear_backward_input", "nm_linear_backward_weight",
@@ -168,6 +170,21 @@ def load_library() -> ctypes.CDLL:
     lib.nm_i8_prepare.restype = c_int32
     lib.nm_i8_prepare.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int32, c_int32, c_int64, c_void_p, c_size_t,
                                   c_void_p]
+    lib.nm_values_i8_bytes.restype = c_size_t
+    lib.nm_values_i8_bytes.argtypes = [c_int64, c_int64, c_int32, c_int32]
+    lib.nm_pack_i8.restype = c_int32
+    lib.nm_pack_i8.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.nm_unpack_i8.restype = c_int32
+    lib.nm_unpack_i8.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64, c_void_p]
+    i8p_args = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_void_p, c_int64, c_int64, ctypes.c_float,
+                c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_void_p, c_size_t, c_void_p]
+    lib.nm_linear_forward_i8_packed.restype = c_int32
+    lib.nm_linear_forward_i8_packed.argtypes = i8p_args
+    lib.nm_linear_forward_i8_packed_prepared.restype = c_int32
+    lib.nm_linear_forward_i8_packed_prepared.argtypes = i8p_args
+    lib.nm_i8_prepare_packed.restype = c_int32
+    lib.nm_i8_prepare_packed.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int32, c_int32, c_int64, c_void_p, c_size_t,
+                                         c_void_p]
     _LIB = lib
     return lib
 
@@ -795,6 +812,99 @@ def nm_linear_forward_i8_prepared(Wq, mask, N: int, M: int, Xq, workspace, x_sca
     """The product alone, from a workspace filled by nm_i8_prepare."""
     return nm_linear_forward_i8(Wq, mask, N, M, Xq, x_scale, w_scale, bias, out_dtype, out, workspace, stream,
                                 _prepared=True)
+
+
+def nm_pack_i8(Wq, mask, N: int, M: int, stream=None):
+    """Compressed form of the int8 weight under `mask`: (values int8 [O, K*N/M], indices int32 words)."""
+    torch = _torch()
+    O, K, ldw = _i8_weight(Wq, mask)
+    lib = load_library()
+    values = torch.empty((O, K // M * N), dtype=torch.int8, device=Wq.device)
+    indices = torch.empty((O, lib.nm_index_bytes(O, K, N, M) // (4 * O)), dtype=torch.int32, device=Wq.device)
+    _check(lib.nm_pack_i8(Wq.data_ptr(), O, K, ldw, N, M, mask.data_ptr(), values.data_ptr(), indices.data_ptr(),
+                          _stream_handle(stream)))
+    return values, indices
+
+
+def _i8_packed(values, indices):
+    torch = _torch()
+    _need(values, torch.int8, "values")
+    _need(indices, torch.int32, "indices")
+    if not values.is_contiguous() or not indices.is_contiguous():
+        raise ValueError("packed tensors must be contiguous")
+    return int(values.shape[0])
+
+
+def nm_unpack_i8(values, indices, K: int, N: int, M: int, stream=None):
+    torch = _torch()
+    O = _i8_packed(values, indices)
+    out = torch.empty((O, K), dtype=torch.int8, device=values.device)
+    _check(load_library().nm_unpack_i8(values.data_ptr(), indices.data_ptr(), O, K, N, M, out.data_ptr(), K,
+                                       _stream_handle(stream)))
+    return out
+
+
+def nm_i8_prepare_packed(values, indices, K: int, N: int, M: int, T: int, workspace=None, stream=None):
+    """nm_i8_prepare from the compressed form: fills (and returns) the same workspace."""
+    torch = _torch()
+    O = _i8_packed(values, indices)
+    need = nm_i8_workspace_bytes(O, K, N, M, T)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=values.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().nm_i8_prepare_packed(values.data_ptr(), indices.data_ptr(), O, K, N, M, T, ws_ptr, ws_bytes,
+                                               _stream_handle(stream)))
+    return workspace
+
+
+def nm_linear_forward_i8_packed(values, indices, K: int, N: int, M: int, Xq, x_scale: float = 1.0, w_scale=None, bias=None,
+                                out_dtype=None, out=None, workspace=None, stream=None, _prepared=False):
+    """nm_linear_forward_i8 with the weight in its compressed form."""
+    torch = _torch()
+    O = _i8_packed(values, indices)
+    _need(Xq, torch.int8, "Xq")
+    T, KX, ldx = _rows(Xq, "Xq")
+    if KX != K:
+        raise ValueError("Xq must be [T, K]")
+    if out is not None:
+        out_dtype = out.dtype
+    out_dtype = out_dtype or torch.float32
+    codes = {torch.float32: NM_OUT_F32, torch.bfloat16: NM_OUT_BF16, torch.int32: NM_OUT_I32}
+    if out_dtype not in codes:
+        raise ValueError("out dtype must be float32, bfloat16 or int32")
+    if out is None:
+        out = torch.empty((T, O), dtype=out_dtype, device=Xq.device)
+    TY, OY, ldy = _rows(out, "out")
+    if (TY, OY) != (T, O):
+        raise ValueError("out must be [T, O]")
+    ptrs = []
+    for t, name in ((w_scale, "w_scale"), (bias, "bias")):
+        if t is None:
+            ptrs.append(None)
+            continue
+        _need(t, torch.float32, name)
+        if t.numel() != O or not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous [O]")
+        ptrs.append(t.data_ptr())
+    need = nm_i8_workspace_bytes(O, K, N, M, T)
+    if workspace is None and need:
+        if _prepared:
+            raise ValueError("a prepared call needs the workspace nm_i8_prepare_packed filled")
+        workspace = _workspace(need, Xq.device, stream)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    lib = load_library()
+    fn = lib.nm_linear_forward_i8_packed_prepared if _prepared else lib.nm_linear_forward_i8_packed
+    _check(fn(values.data_ptr(), indices.data_ptr(), O, K, N, M, Xq.data_ptr(), T, ldx, float(x_scale), ptrs[0], ptrs[1],
+              out.data_ptr(), ldy, codes[out_dtype], ws_ptr, ws_bytes, _stream_handle(stream)))
+    return out
+
+
+def nm_linear_forward_i8_packed_prepared(values, indices, K: int, N: int, M: int, Xq, workspace, x_scale: float = 1.0,
+                                         w_scale=None, bias=None, out_dtype=None, out=None, stream=None):
+    return nm_linear_forward_i8_packed(values, indices, K, N, M, Xq, x_scale, w_scale, bias, out_dtype, out, workspace,
+                                       stream, _prepared=True)
 
 
 def nm_spmm(values, indices, K: int, N: int, M: int, X, out_dtype=None, out=None, workspace=None, stream=None):

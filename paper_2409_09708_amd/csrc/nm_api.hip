@@ -252,19 +252,25 @@ int32_t spmm_entry(const nm_bf16* values, const uint32_t* indices, int64_t O, in
   return device_status(e);
 }
 
-int32_t i8_entry(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N, int32_t M,
-                 const int8_t* Xq, int64_t T, int64_t ldx, float x_scale, const float* w_scale, const float* bias, void* Y,
-                 int64_t ldy, int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream, int phases) {
+// the int8 layer from the dense weight + mask (values == NULL) or from the compressed form (Wq == NULL)
+int32_t i8_entry(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, const int8_t* values,
+                 const uint32_t* indices, int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
+                 const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype, void* workspace,
+                 size_t workspace_bytes, void* stream, int phases) {
   const bool product = phases & nm::SPMM_PRODUCT;
-  if (!Wq || !mask || (product && (!Xq || !Y))) return NM_ERR_NULL;
+  const bool packed = values != nullptr || indices != nullptr;
+  if (packed ? (!values || !indices) : (!Wq || !mask)) return NM_ERR_NULL;
+  if (product && (!Xq || !Y)) return NM_ERR_NULL;
   if (int32_t s = check_weight(O, K, N, M)) return s;
-  if (T <= 0 || T > (int64_t)1 << 31 || ldw < K) return NM_ERR_SHAPE;
+  if (T <= 0 || T > (int64_t)1 << 31 || (!packed && ldw < K)) return NM_ERR_SHAPE;
   if (product && (ldx < K || ldy < O)) return NM_ERR_SHAPE;
   if (out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16 && out_dtype != NM_OUT_I32) return NM_ERR_DTYPE;
-  if (!aligned(mask, 4) || !aligned(w_scale, 4) || !aligned(bias, 4) || !aligned(Y, out_dtype == NM_OUT_BF16 ? 2 : 4))
+  if (!aligned(mask, 4) || !aligned(indices, 4) || !aligned(w_scale, 4) || !aligned(bias, 4) ||
+      !aligned(Y, out_dtype == NM_OUT_BF16 ? 2 : 4))
     return NM_ERR_ALIGN;
   nm::I8LinearArgs a;
-  a.Wq = Wq; a.ldw = ldw; a.mask = mask; a.O = O; a.K = K; a.N = N; a.M = M;
+  a.Wq = packed ? nullptr : Wq; a.ldw = ldw; a.mask = mask; a.values = values; a.indices = indices;
+  a.O = O; a.K = K; a.N = N; a.M = M;
   a.X = Xq; a.T = T; a.ldx = ldx; a.x_scale = x_scale; a.w_scale = w_scale; a.bias = bias;
   a.Y = Y; a.ldy = ldy; a.out_kind = out_dtype;
   a.workspace = workspace; a.workspace_bytes = workspace_bytes;
@@ -377,22 +383,71 @@ int32_t nm_linear_forward_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw
                              int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale, const float* w_scale,
                              const float* bias, void* Y, int64_t ldy, int32_t out_dtype, void* workspace,
                              size_t workspace_bytes, void* stream) {
-  return i8_entry(Wq, O, K, ldw, mask, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype, workspace,
+  return i8_entry(Wq, O, K, ldw, mask, nullptr, nullptr, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype, workspace,
                   workspace_bytes, stream, nm::SPMM_PREPARE | nm::SPMM_PRODUCT);
 }
 
 int32_t nm_i8_prepare(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask, int32_t N, int32_t M,
                       int64_t T, void* workspace, size_t workspace_bytes, void* stream) {
-  return i8_entry(Wq, O, K, ldw, mask, N, M, nullptr, T, K, 1.f, nullptr, nullptr, nullptr, O, NM_OUT_F32, workspace,
-                  workspace_bytes, stream, nm::SPMM_PREPARE);
+  return i8_entry(Wq, O, K, ldw, mask, nullptr, nullptr, N, M, nullptr, T, K, 1.f, nullptr, nullptr, nullptr, O, NM_OUT_F32,
+                  workspace, workspace_bytes, stream, nm::SPMM_PREPARE);
 }
 
 int32_t nm_linear_forward_i8_prepared(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, const uint32_t* mask,
                                       int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
                                       const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
                                       void* workspace, size_t workspace_bytes, void* stream) {
-  return i8_entry(Wq, O, K, ldw, mask, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype, workspace,
+  return i8_entry(Wq, O, K, ldw, mask, nullptr, nullptr, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype, workspace,
                   workspace_bytes, stream, nm::SPMM_PRODUCT);
+}
+
+size_t nm_values_i8_bytes(int64_t O, int64_t K, int32_t N, int32_t M) {
+  if (check_weight(O, K, N, M) != NM_OK) return 0;
+  return (size_t)O * (size_t)nm::values_per_row(K, N, M);
+}
+
+int32_t nm_pack_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, int32_t N, int32_t M, const uint32_t* mask,
+                   int8_t* values, uint32_t* indices, void* stream) {
+  if (!Wq || !mask || !values || !indices) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(mask, 4) || !aligned(indices, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_pack_i8(Wq, O, K, ldw, N, M, mask, values, indices, (hipStream_t)stream));
+}
+
+int32_t nm_unpack_i8(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                     int8_t* Wq_dense, int64_t ldw, void* stream) {
+  if (!values || !indices || !Wq_dense) return NM_ERR_NULL;
+  if (int32_t s = check_weight(O, K, N, M)) return s;
+  if (ldw < K) return NM_ERR_SHAPE;
+  if (!aligned(indices, 4)) return NM_ERR_ALIGN;
+  return device_status(nm::launch_unpack_i8(values, indices, O, K, N, M, Wq_dense, ldw, (hipStream_t)stream));
+}
+
+int32_t nm_linear_forward_i8_packed(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N,
+                                    int32_t M, const int8_t* Xq, int64_t T, int64_t ldx, float x_scale,
+                                    const float* w_scale, const float* bias, void* Y, int64_t ldy, int32_t out_dtype,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (!values || !indices) return NM_ERR_NULL;
+  return i8_entry(nullptr, O, K, K, nullptr, values, indices, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype,
+                  workspace, workspace_bytes, stream, nm::SPMM_PREPARE | nm::SPMM_PRODUCT);
+}
+
+int32_t nm_i8_prepare_packed(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int32_t N, int32_t M,
+                             int64_t T, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!values || !indices) return NM_ERR_NULL;
+  return i8_entry(nullptr, O, K, K, nullptr, values, indices, N, M, nullptr, T, K, 1.f, nullptr, nullptr, nullptr, O,
+                  NM_OUT_F32, workspace, workspace_bytes, stream, nm::SPMM_PREPARE);
+}
+
+int32_t nm_linear_forward_i8_packed_prepared(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K,
+                                             int32_t N, int32_t M, const int8_t* Xq, int64_t T, int64_t ldx,
+                                             float x_scale, const float* w_scale, const float* bias, void* Y,
+                                             int64_t ldy, int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                                             void* stream) {
+  if (!values || !indices) return NM_ERR_NULL;
+  return i8_entry(nullptr, O, K, K, nullptr, values, indices, N, M, Xq, T, ldx, x_scale, w_scale, bias, Y, ldy, out_dtype,
+                  workspace, workspace_bytes, stream, nm::SPMM_PRODUCT);
 }
 
 int32_t nm_prune_scored(const float* score, int64_t O, int64_t K, int64_t lds, int32_t N, int32_t M, uint32_t* mask,

@@ -29,6 +29,53 @@ namespace nm {
 
 namespace {
 
+// Where a layer's weight comes from: the dense int8 matrix with its mask words, or (Wq == NULL) the compressed form,
+// int8 values [O, K N/M] + the index stream of the bfloat16 layer (Section 1; Section 2, Fig. 2 upper part).
+struct I8Weight {
+  const int8_t* Wq;
+  int64_t ldw;
+  const uint32_t* mask;
+  const int8_t* values;
+  const uint32_t* indices;
+  int N, M;
+};
+
+// One window of 32 consecutive weights of row o (window blk): its mask word and its 32 bytes (byte i of the window in
+// bits [8 (i mod 4), +8) of bytes[i / 4]).  From the dense weight the bytes are whatever the matrix holds (the caller
+// applies the mask); from the compressed form pruned positions are 0.
+__device__ __forceinline__ void load_window(const I8Weight& w, int64_t o, int64_t blk, int64_t K, uint32_t& mw,
+                                            uint32_t (&bytes)[8]) {
+  if (w.Wq != nullptr) {
+    mw = w.mask[o * (K / 32) + blk];
+    const uint4* src = reinterpret_cast<const uint4*>(w.Wq + o * w.ldw + blk * 32);
+    const uint4 a = src[0], b = src[1];
+    bytes[0] = a.x; bytes[1] = a.y; bytes[2] = a.z; bytes[3] = a.w;
+    bytes[4] = b.x; bytes[5] = b.y; bytes[6] = b.z; bytes[7] = b.w;
+    return;
+  }
+  const int B = log2_of(w.M);
+  const int64_t nf = K / w.M * w.N;
+  const int64_t nw = (nf * B + 31) / 32;
+  const uint32_t* row = w.indices + o * nw;
+  const int groups = 32 / w.M;
+  mw = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) bytes[i] = 0;
+  for (int g = 0; g < groups; ++g) {
+    for (int j = 0; j < w.N; ++j) {
+      const int64_t f = (blk * groups + g) * w.N + j;
+      const uint32_t pos = (uint32_t)(g * w.M) + stream_bits(row, nw, f * B, B);
+      const uint32_t v = (uint32_t)(uint8_t)w.values[o * nf + f] << (8 * (pos & 3u));
+      mw |= 1u << pos;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) bytes[i] |= (pos >> 2) == (uint32_t)i ? v : 0u;
+    }
+  }
+}
+__device__ __forceinline__ uint32_t window_byte(const uint32_t (&bytes)[8], int i) {
+  return (bytes[i >> 2] >> (8 * (i & 3))) & 0xFFu;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Pre-pass: one lane per 32 consecutive weights of a row (one mask word).
 // Sparse form: run q (4 weights) owns slots 2q and 2q+1; its first kept weight goes to slot 2q with
@@ -37,14 +84,13 @@ namespace {
 // illegal mask produces one).
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-compress_i8_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O, int64_t K,
-                   int8_t* __restrict__ vals, uint32_t* __restrict__ sel) {
+compress_i8_kernel(const I8Weight src, int64_t O, int64_t K, int8_t* __restrict__ vals, uint32_t* __restrict__ sel) {
   const int64_t per_row = K / 32;
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= O * per_row) return;
   const int64_t o = id / per_row, blk = id % per_row;
-  const uint32_t mw = mask[o * per_row + blk];
-  const int8_t* w = Wq + o * ldw + blk * 32;
+  uint32_t mw, w[8];
+  load_window(src, o, blk, K, mw, w);
   uint32_t out[4] = {0, 0, 0, 0}, selw = 0;
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -54,7 +100,7 @@ compress_i8_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* _
     for (int p = 0; p < 4; ++p) {
       if (((bits >> p) & 1u) && slot < 2) {
         const int s = 2 * q + slot;
-        out[s >> 2] |= (uint32_t)(uint8_t)w[4 * q + p] << (8 * (s & 3));
+        out[s >> 2] |= window_byte(w, 4 * q + p) << (8 * (s & 3));
         selw |= (uint32_t)p << (2 * s);
         ++slot;
       }
@@ -65,21 +111,20 @@ compress_i8_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* _
 }
 
 __global__ void __launch_bounds__(256)
-mask_copy_i8_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O, int64_t K,
-                    int8_t* __restrict__ dense) {
+mask_copy_i8_kernel(const I8Weight src, int64_t O, int64_t K, int8_t* __restrict__ dense) {
   const int64_t per_row = K / 32;
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= O * per_row) return;
   const int64_t o = id / per_row, blk = id % per_row;
-  const uint32_t mw = mask[o * per_row + blk];
-  const int8_t* w = Wq + o * ldw + blk * 32;
+  uint32_t mw, w[8];
+  load_window(src, o, blk, K, mw, w);
   uint32_t out[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     out[i] = 0;
 #pragma unroll
     for (int b = 0; b < 4; ++b)
-      if ((mw >> (4 * i + b)) & 1u) out[i] |= (uint32_t)(uint8_t)w[4 * i + b] << (8 * b);
+      if ((mw >> (4 * i + b)) & 1u) out[i] |= window_byte(w, 4 * i + b) << (8 * b);
   }
   uint4* dst = reinterpret_cast<uint4*>(dense + o * K + blk * 32);
   dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
@@ -90,16 +135,16 @@ mask_copy_i8_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* 
 // 256-row tiles; a K step is 128 wide in the 2:4 form (64 compressed bytes per row: the lane's 16 bytes are
 // piece blk % 4 of step blk / 4) and 64 wide in the dense form (the lane's 32 bytes are two pieces of step blk / 2).
 __global__ void __launch_bounds__(256)
-compress_i8_stream_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O,
-                          int64_t O_pad, int64_t K, unsigned char* __restrict__ vals_s, unsigned char* __restrict__ sel_s) {
+compress_i8_stream_kernel(const I8Weight src, int64_t O, int64_t O_pad, int64_t K, unsigned char* __restrict__ vals_s,
+                          unsigned char* __restrict__ sel_s) {
   const int64_t per_row = K / 32;
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= O_pad * per_row) return;
   const int64_t o = id / per_row, blk = id % per_row;
   uint32_t out[4] = {0, 0, 0, 0}, selw = 0;
   if (o < O) {
-    const uint32_t mw = mask[o * per_row + blk];
-    const int8_t* w = Wq + o * ldw + blk * 32;
+    uint32_t mw, w[8];
+    load_window(src, o, blk, K, mw, w);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const uint32_t bits = (mw >> (4 * q)) & 15u;
@@ -108,7 +153,7 @@ compress_i8_stream_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint
       for (int p = 0; p < 4; ++p) {
         if (((bits >> p) & 1u) && slot < 2) {
           const int s = 2 * q + slot;
-          out[s >> 2] |= (uint32_t)(uint8_t)w[4 * q + p] << (8 * (s & 3));
+          out[s >> 2] |= window_byte(w, 4 * q + p) << (8 * (s & 3));
           selw |= (uint32_t)p << (2 * s);
           ++slot;
         }
@@ -121,21 +166,20 @@ compress_i8_stream_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint
 }
 
 __global__ void __launch_bounds__(256)
-mask_copy_i8_stream_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O,
-                           int64_t O_pad, int64_t K, unsigned char* __restrict__ dense_s) {
+mask_copy_i8_stream_kernel(const I8Weight src, int64_t O, int64_t O_pad, int64_t K, unsigned char* __restrict__ dense_s) {
   const int64_t per_row = K / 32;
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= O_pad * per_row) return;
   const int64_t o = id / per_row, blk = id % per_row;
   uint32_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (o < O) {
-    const uint32_t mw = mask[o * per_row + blk];
-    const int8_t* w = Wq + o * ldw + blk * 32;
+    uint32_t mw, w[8];
+    load_window(src, o, blk, K, mw, w);
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
       for (int b = 0; b < 4; ++b)
-        if ((mw >> (4 * i + b)) & 1u) out[i] |= (uint32_t)(uint8_t)w[4 * i + b] << (8 * b);
+        if ((mw >> (4 * i + b)) & 1u) out[i] |= window_byte(w, 4 * i + b) << (8 * b);
   }
   const int64_t nk = K / 64, step = blk >> 1;
   const int c0 = (int)(blk & 1) * 2;
@@ -387,18 +431,30 @@ nm_i8_gemm_kernel(const I8Args a) {
   }
 }
 
-// Any shape and alignment: one lane per output, reading the dense weight and the mask words directly.
+// Any shape and alignment: one lane per output, reading the dense weight and the mask words (or the compressed
+// form: decode the position, select the activation, multiply, add) directly.
 __global__ void __launch_bounds__(256)
-i8_general_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O, int64_t K,
-                  const int8_t* __restrict__ X, int64_t T, int64_t ldx, float x_scale, const float* __restrict__ w_scale,
-                  const float* __restrict__ bias, void* __restrict__ Y, int64_t ldy, int out_kind) {
+i8_general_kernel(const I8Weight w, int64_t O, int64_t K, const int8_t* __restrict__ X, int64_t T, int64_t ldx,
+                  float x_scale, const float* __restrict__ w_scale, const float* __restrict__ bias, void* __restrict__ Y,
+                  int64_t ldy, int out_kind) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= T * O) return;
   const int64_t t = id / O, o = id % O;
-  const int64_t mw = (K + 31) / 32;
   int acc = 0;
-  for (int64_t k = 0; k < K; ++k)
-    if ((mask[o * mw + (k >> 5)] >> (k & 31)) & 1u) acc += (int)Wq[o * ldw + k] * (int)X[t * ldx + k];
+  if (w.Wq != nullptr) {
+    const int64_t mw = (K + 31) / 32;
+    for (int64_t k = 0; k < K; ++k)
+      if ((w.mask[o * mw + (k >> 5)] >> (k & 31)) & 1u) acc += (int)w.Wq[o * w.ldw + k] * (int)X[t * ldx + k];
+  } else {
+    const int B = log2_of(w.M);
+    const int64_t nf = K / w.M * w.N;
+    const int64_t nw = (nf * B + 31) / 32;
+    const uint32_t* row = w.indices + o * nw;
+    for (int64_t f = 0; f < nf; ++f) {
+      const int64_t k = (f / w.N) * w.M + stream_bits(row, nw, f * B, B);
+      acc += (int)w.values[o * nf + f] * (int)X[t * ldx + k];
+    }
+  }
   if (out_kind == 2) {
     reinterpret_cast<int*>(Y)[t * ldy + o] = acc;
     return;
@@ -406,6 +462,79 @@ i8_general_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __
   const float y = fmaf((float)acc, x_scale * (w_scale ? w_scale[o] : 1.f), bias ? bias[o] : 0.f);
   if (out_kind == 1) reinterpret_cast<bf16_t*>(Y)[t * ldy + o] = (bf16_t)f32_to_bf16_rne(y);
   else reinterpret_cast<float*>(Y)[t * ldy + o] = y;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Compressed form of the int8 weight: the kept values of every group in ascending position and the index stream
+// of the bfloat16 layer.  A caller's mask is made usable as in the bfloat16 packing (the N lowest set positions;
+// missing ones completed with the lowest unset positions, stored as 0).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t group_mask_bits(const uint32_t* __restrict__ mask, int64_t K, int64_t o, int64_t g, int M) {
+  const int64_t k0 = g * M;
+  return (mask[o * ((K + 31) / 32) + (k0 >> 5)] >> (k0 & 31)) & ((1u << M) - 1u);
+}
+
+__global__ void __launch_bounds__(256)
+pack_i8_values_kernel(const int8_t* __restrict__ Wq, int64_t ldw, const uint32_t* __restrict__ mask, int64_t O, int64_t K,
+                      int N, int M, int8_t* __restrict__ values) {
+  const int64_t G = K / M;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * G) return;
+  const int64_t o = id / G, g = id % G;
+  uint32_t filled;
+  const uint32_t km = legalize_mask(group_mask_bits(mask, K, o, g, M), N, M, &filled);
+  int j = 0;
+  for (int i = 0; i < M; ++i)
+    if ((km >> i) & 1u) {
+      values[o * (G * N) + g * N + j] = ((filled >> i) & 1u) ? (int8_t)0 : Wq[o * ldw + g * M + i];
+      ++j;
+    }
+}
+
+// one lane per index word: the fields that overlap it, from the mask words of their groups
+__global__ void __launch_bounds__(256)
+pack_i8_index_kernel(const uint32_t* __restrict__ mask, int64_t O, int64_t K, int N, int M, uint32_t* __restrict__ indices) {
+  const int b = log2_of(M);
+  const int64_t nf = K / M * N;
+  const int64_t nw = (nf * b + 31) / 32;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * nw) return;
+  const int64_t o = id / nw, w = id % nw;
+  const int64_t bit0 = w * 32;
+  const int64_t f_lo = bit0 / b;
+  int64_t f_hi = (bit0 + 31) / b;
+  if (f_hi > nf - 1) f_hi = nf - 1;
+  uint32_t word = 0, km = 0, filled;
+  int64_t g_cached = -1;
+  for (int64_t f = f_lo; f <= f_hi; ++f) {
+    const int64_t g = f / N;
+    if (g != g_cached) { km = legalize_mask(group_mask_bits(mask, K, o, g, M), N, M, &filled); g_cached = g; }
+    int want = (int)(f % N);
+    uint64_t p = 0;
+    for (int i = 0; i < M; ++i)
+      if ((km >> i) & 1u) { if (want == 0) { p = (uint64_t)i; break; } --want; }
+    const int64_t off = f * b - bit0;  // negative for a field that began in the previous word
+    word |= off >= 0 ? (uint32_t)(p << off) : (uint32_t)(p >> (-off));
+  }
+  indices[o * nw + w] = word;
+}
+
+__global__ void __launch_bounds__(256)
+unpack_i8_kernel(const int8_t* __restrict__ values, const uint32_t* __restrict__ indices, int64_t O, int64_t K, int N, int M,
+                 int8_t* __restrict__ Wd, int64_t ldw) {
+  const int b = log2_of(M);
+  const int64_t G = K / M;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= O * G) return;
+  const int64_t o = id / G, g = id % G;
+  const int64_t nf = G * N;
+  const int64_t nw = (nf * b + 31) / 32;
+  int8_t* dst = Wd + o * ldw + g * M;
+  for (int i = 0; i < M; ++i) dst[i] = 0;
+  for (int j = 0; j < N; ++j) {
+    const int64_t f = g * N + j;
+    dst[stream_bits(indices + o * nw, nw, f * b, b)] = values[o * nf + f];
+  }
 }
 
 inline bool aligned_to(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
@@ -444,18 +573,42 @@ size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   return sparse_form ? (size_t)(rows * K / 2) + (size_t)(rows * K / 8) : (size_t)(rows * K);
 }
 
+hipError_t launch_pack_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, int N, int M, const uint32_t* mask,
+                          int8_t* values, uint32_t* indices, hipStream_t s) {
+  const int64_t ng = O * (K / M);
+  hipLaunchKernelGGL(pack_i8_values_kernel, dim3((unsigned)((ng + 255) / 256)), dim3(256), 0, s, Wq, ldw, mask, O, K, N, M,
+                     values);
+  const int64_t nw = O * index_words_per_row(K, N, M);
+  hipLaunchKernelGGL(pack_i8_index_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, mask, O, K, N, M, indices);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_i8(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M, int8_t* Wd,
+                            int64_t ldw, hipStream_t s) {
+  const int64_t ng = O * (K / M);
+  hipLaunchKernelGGL(unpack_i8_kernel, dim3((unsigned)((ng + 255) / 256)), dim3(256), 0, s, values, indices, O, K, N, M, Wd,
+                     ldw);
+  return hipGetLastError();
+}
+
 hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspace_short, int phases) {
   *workspace_short = false;
   const bool prepare = phases & SPMM_PREPARE, product = phases & SPMM_PRODUCT;
+  const bool packed = a.Wq == nullptr;
+  const I8Weight src{a.Wq, a.ldw, a.mask, a.values, a.indices, a.N, a.M};
   const bool tiles = (a.K % 128 == 0) && a.O <= (1 << 24) && a.K <= (1 << 24) && a.T <= (1ll << 31);
   const bool operands_ok = !product || (aligned_to(a.X, 16) && (a.ldx % 16 == 0) && a.ldx <= (1 << 24));
-  const bool weight_ok = aligned_to(a.Wq, 16) && (a.ldw % 16 == 0);  // the same answer in both phases
+  // the same answer in both phases; the compressed form is read element by element (no alignment needed)
+  const bool weight_ok = packed || (aligned_to(a.Wq, 16) && (a.ldw % 16 == 0));
+  auto general = [&]() {
+    if (a.T * a.O > 0x7FFFFFFFll * 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(i8_general_kernel, dim3((unsigned)((a.T * a.O + 255) / 256)), dim3(256), 0, s, src, a.O, a.K, a.X, a.T,
+                       a.ldx, a.x_scale, a.w_scale, a.bias, a.Y, a.ldy, a.out_kind);
+    return hipGetLastError();
+  };
   if (!tiles || !operands_ok || !weight_ok) {
     if (!product) return hipSuccess;
-    if (a.T * a.O > 0x7FFFFFFFll * 256) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(i8_general_kernel, dim3((unsigned)((a.T * a.O + 255) / 256)), dim3(256), 0, s, a.Wq, a.ldw, a.mask,
-                       a.O, a.K, a.X, a.T, a.ldx, a.x_scale, a.w_scale, a.bias, a.Y, a.ldy, a.out_kind);
-    return hipGetLastError();
+    return general();
   }
   const size_t need = i8_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256)) {
@@ -467,16 +620,16 @@ hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspac
   if (stream_i8_takes(a.O, a.K, a.T, a.N, a.M)) {
     // large layers: the persistent kernel, operands in its stream order.  It writes Y in 16-byte pieces and
     // fetches scales and bias in 16-byte pieces; a call whose output or constants are not aligned for that runs
-    // the general kernel (it reads Wq and the mask itself).
+    // the general kernel (it reads the weight itself).
     const int64_t o_pad = ((a.O + 255) / 256) * 256;
     unsigned char* sel_s = ws + (size_t)(o_pad * a.K / 2);
     if (prepare) {
       const int64_t n = o_pad * (a.K / 32);
       const dim3 grid((unsigned)((n + 255) / 256));
       if (sparse_form)
-        hipLaunchKernelGGL(compress_i8_stream_kernel, grid, dim3(256), 0, s, a.Wq, a.ldw, a.mask, a.O, o_pad, a.K, ws, sel_s);
+        hipLaunchKernelGGL(compress_i8_stream_kernel, grid, dim3(256), 0, s, src, a.O, o_pad, a.K, ws, sel_s);
       else
-        hipLaunchKernelGGL(mask_copy_i8_stream_kernel, grid, dim3(256), 0, s, a.Wq, a.ldw, a.mask, a.O, o_pad, a.K, ws);
+        hipLaunchKernelGGL(mask_copy_i8_stream_kernel, grid, dim3(256), 0, s, src, a.O, o_pad, a.K, ws);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
@@ -484,12 +637,7 @@ hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspac
     const int per_piece = a.out_kind == 1 ? 8 : 4;
     const bool vec = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) && a.ldy <= 0x7FFFFFFF &&
                      aligned_to(a.w_scale, 16) && aligned_to(a.bias, 16) && (a.O % 4 == 0);
-    if (!vec) {
-      if (a.T * a.O > 0x7FFFFFFFll * 256) return hipErrorInvalidValue;
-      hipLaunchKernelGGL(i8_general_kernel, dim3((unsigned)((a.T * a.O + 255) / 256)), dim3(256), 0, s, a.Wq, a.ldw, a.mask,
-                         a.O, a.K, a.X, a.T, a.ldx, a.x_scale, a.w_scale, a.bias, a.Y, a.ldy, a.out_kind);
-      return hipGetLastError();
-    }
+    if (!vec) return general();
     StreamI8Args g;
     g.values = reinterpret_cast<const int8_t*>(ws); g.sel = sparse_form ? reinterpret_cast<const uint32_t*>(sel_s) : nullptr;
     g.sparse_form = sparse_form; g.X = a.X; g.w_scale = a.w_scale; g.bias = a.bias; g.x_scale = a.x_scale;
@@ -501,8 +649,8 @@ hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspac
   if (prepare) {
     const int64_t n = a.O * (a.K / 32);
     const dim3 grid((unsigned)((n + 255) / 256));
-    if (sparse_form) hipLaunchKernelGGL(compress_i8_kernel, grid, dim3(256), 0, s, a.Wq, a.ldw, a.mask, a.O, a.K, vals, sel);
-    else hipLaunchKernelGGL(mask_copy_i8_kernel, grid, dim3(256), 0, s, a.Wq, a.ldw, a.mask, a.O, a.K, vals);
+    if (sparse_form) hipLaunchKernelGGL(compress_i8_kernel, grid, dim3(256), 0, s, src, a.O, a.K, vals, sel);
+    else hipLaunchKernelGGL(mask_copy_i8_kernel, grid, dim3(256), 0, s, src, a.O, a.K, vals);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -171,9 +171,11 @@ hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream
 
 // nm_int8.hip: the int8 layer.  Phases as for launch_spmm.
 struct I8LinearArgs {
-  const int8_t* Wq;      // dense int8 weight [O, K], ld ldw
+  const int8_t* Wq;      // dense int8 weight [O, K], ld ldw; NULL = the weight comes compressed (values, indices)
   int64_t ldw;
   const uint32_t* mask;  // mask words [O, ceil(K/32)]
+  const int8_t* values;  // compressed form: kept values [O, K N/M] ...
+  const uint32_t* indices;  // ... and the index stream of the bfloat16 layer
   int64_t O, K;
   int N, M;
   const int8_t* X;
@@ -189,5 +191,10 @@ struct I8LinearArgs {
 };
 size_t i8_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);
 hipError_t launch_linear_i8(const I8LinearArgs& a, hipStream_t s, bool* workspace_short, int phases);
+// compressed form of the int8 weight under a mask, and back
+hipError_t launch_pack_i8(const int8_t* Wq, int64_t O, int64_t K, int64_t ldw, int N, int M, const uint32_t* mask,
+                          int8_t* values, uint32_t* indices, hipStream_t s);
+hipError_t launch_unpack_i8(const int8_t* values, const uint32_t* indices, int64_t O, int64_t K, int N, int M, int8_t* Wd,
+                            int64_t ldw, hipStream_t s);
 
 }  // namespace nm

@@ -4,7 +4,7 @@
 //  * matrix rate: a loop of nothing but matrix instructions on register operands (finite pseudo-random bf16
 //    patterns; constant operands would let the clock run higher than real data does), 32 independent
 //    accumulator blocks per wave, two waves per SIMD, every compute unit busy.
-//  * copy rate: a plain streaming copy, 16 bytes per lane, every compute unit busy.  Its known traffic also
+//  * copy rate: a plain streaming copy, 16 bytes per lane, eight blocks per compute unit.  Its known traffic also
 //    scales the profiler's byte counters.
 #include "nm_device.h"
 #include "nm_launch.h"
@@ -66,14 +66,21 @@ __global__ void __launch_bounds__(256, 2) matrix_rate_kernel(int iters, float* s
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-__global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n; i += 4 * stride) {
-    const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-    dst[i] = v0; dst[i + stride] = v1; dst[i + 2 * stride] = v2; dst[i + 3 * stride] = v3;
+// every block copies one contiguous share, four 16-byte pieces per lane in flight, loads and stores with the
+// non-temporal hint (nothing is reused): of the forms tried (grid-strided or block-contiguous, with and without the
+// hint, 2 to 32 blocks per compute unit) this one was the fastest that is also steady from run to run
+__global__ void __launch_bounds__(256) copy_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n) {
+  const size_t per = (n + gridDim.x - 1) / gridDim.x;
+  const size_t b0 = (size_t)blockIdx.x * per, b1 = b0 + per < n ? b0 + per : n;
+  size_t i = b0 + threadIdx.x;
+  for (; i + 3 * 256 < b1; i += 4 * 256) {
+    u32x4_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(v[u], dst + i + u * 256);
   }
-  for (; i < n; i += stride) dst[i] = src[i];
+  for (; i < b1; i += 256) dst[i] = src[i];
 }
 
 }  // namespace
@@ -95,8 +102,8 @@ size_t probe_sink_bytes() { return (size_t)kMaxProbeBlocks * 256 * sizeof(float)
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
   int cus = 0;
   if (hipError_t e = compute_units(&cus); e != hipSuccess) return e;
-  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)cus * 8), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
-                     reinterpret_cast<uint4*>(dst), bytes / 16);
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)cus * 8), dim3(256), 0, s, reinterpret_cast<const u32x4_t*>(src),
+                     reinterpret_cast<u32x4_t*>(dst), bytes / 16);
   return hipGetLastError();
 }
 

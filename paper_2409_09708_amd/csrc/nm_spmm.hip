@@ -27,55 +27,8 @@
 namespace nm {
 
 // ---------------------------------------------------------------------------------------------
-// Pre-pass: re-code an N:M weight with N <= 2 as a 2:4 weight (values [O, K/2], one 32-bit
-// selector word per 32 weights).  One lane per 32 consecutive weights.
-// Slot rule: run q (4 weights) owns slots 2q and 2q+1; the first kept value of the run goes to
-// slot 2q with selector = its offset in the run, a second one to slot 2q+1; free slots hold +0
-// with selector 0 (the matrix instruction is a plain multiplexer per slot, so any selector of a
-// zero slot is harmless).
-// ---------------------------------------------------------------------------------------------
-template <int N, int M>
-__global__ void __launch_bounds__(256)
-recode_to_2of4_kernel(const bf16_t* __restrict__ values, const uint32_t* __restrict__ indices, int64_t O, int64_t K,
-                      bf16_t* __restrict__ values24, uint32_t* __restrict__ sel24) {
-  constexpr int B = log2_of(M);
-  constexpr int G = 32 / M;       // groups per lane
-  constexpr int RUNS = M / 4;     // 4-runs per group
-  const int64_t per_row = K / 32;
-  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (id >= O * per_row) return;
-  const int64_t o = id / per_row, blk = id % per_row;
-  const int64_t nf = K / M * N;
-  const int64_t nw = (nf * B + 31) / 32;
-  const int64_t f0 = blk * G * N;  // first field of this lane
-  const uint32_t fields = stream_bits(indices + o * nw, nw, f0 * B, G * N * B);
-  uint32_t out[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) out[i] = 0;
-  uint32_t sel = 0;
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    uint32_t prev_run = 0xFFFFFFFFu;
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-      const uint32_t p = (fields >> ((g * N + j) * B)) & (M - 1);
-      const uint32_t v = values[o * nf + f0 + g * N + j];
-      const uint32_t run = p >> 2, within = p & 3u;
-      const uint32_t second = (run == prev_run) ? 1u : 0u;
-      prev_run = run;
-#pragma unroll
-      for (int r = 0; r < RUNS; ++r) out[g * RUNS + r] |= (run == (uint32_t)r) ? (v << (16 * second)) : 0u;
-      sel |= within << (4 * (g * RUNS + run) + 2 * second);
-    }
-  }
-  uint4* dst = reinterpret_cast<uint4*>(values24 + o * (K / 2) + blk * 16);
-  dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
-  dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
-  sel24[o * per_row + blk] = sel;
-}
-
-// ---------------------------------------------------------------------------------------------
-// Pre-pass for the persistent kernel: the weight in "stream order", i.e. exactly the LDS image
+// Pre-pass: the weight in "stream order", the form every matrix-core kernel here reads it in (the persistent
+// kernel always; the tiled kernel except at 2:4 and N = M, whose packed layouts it reads as they lie): exactly the LDS image
 // of every (16-row group, K step) as one contiguous 1 KB block, so that the product kernel's
 // loads are whole contiguous kilobytes (a 16-row x 64-byte slice of a row-major weight touches 16
 // cache lines for one kilobyte, and the selector words one line per 8 bytes).
@@ -84,6 +37,10 @@ recode_to_2of4_kernel(const bf16_t* __restrict__ values, const uint32_t* __restr
 //     LDS swizzle; a step is 32 compressed values = 64 dense k, or 32 dense weights)
 //   selector block (o_tile, ks) at ((o_tile * nk) + ks) * 2048: row r of the tile at r*8, 2 words
 // Rows from O up to the next multiple of 256 are written as zeros.
+// Levels with N <= 2 are re-coded as a 2:4 weight.  Slot rule: run q (4 weights) owns slots 2q and 2q+1; the first
+// kept value of the run goes to slot 2q with selector = its offset in the run, a second one to slot 2q+1; free slots
+// hold +0 with selector 0 (the matrix instruction is a plain multiplexer per slot, so any selector of a zero slot
+// is harmless).
 // ---------------------------------------------------------------------------------------------
 
 template <int N, int M>
@@ -206,7 +163,8 @@ struct GemmArgs {
   int64_t O, K, T, ldx, ldy;
   int n_o_tiles, n_t_tiles;
   int out_bf16;
-  int vec_store;  // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
+  int vec_store;    // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
+  int stream_form;  // A (and sel) lie in stream order (the pre-pass's output), else row-major as packed
 };
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES_>
@@ -257,9 +215,13 @@ __device__ __forceinline__ f32x4_t bias_init(const float* bias, int64_t o, int64
 
 // One tile of one layer; `block` is the block's number among the layer's blocks (a multiple of 8 of them, so
 // that block mod 8 is the XCD the block runs on).
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
+// STREAM: the weight lies in stream order (the pre-pass's output: every 16-row x K-step slice one contiguous,
+// already swizzled kilobyte; selector words interleaved per 32-row pair), else row-major (the packed 2:4 layout
+// or a dense level's values, read as they lie).
+template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES, bool STREAM>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, unsigned char* smem) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+  static_assert(!STREAM || (OT % 2 == 0 && C::BO % 32 == 0 && 256 % C::BO == 0), "stream order: whole 32-row pairs inside one 256-row tile");
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   // XCD-aware tile order: consecutive block ids land on different XCDs (8 of them, each with its
@@ -295,46 +257,72 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
     x_voff[i] = (uint32_t)((row * a.ldx + c * 8) * 2);
     x_dst[i] = (uint32_t)(j * 1024);
   }
+  const int nk = (int)(a.K / C::KC);
 #pragma unroll
   for (int i = 0; i < C::A_PW; ++i) {
     const int j = (wave + i * C::NW) % C::A_LOADS;
-    int64_t row;
-    int c;
-    if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 1) & 3); }
-    else { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (int)(row & 7); }
-    if (row > o_last) row = o_last;
-    a_voff[i] = (uint32_t)((row * a_ld + c * 8) * 2);
-    a_dst[i] = (uint32_t)(C::X_BYTES + j * 1024);
+    if constexpr (STREAM) {
+      // load j brings one kilobyte: 16-row group rg of the tile at the stage's K step (2:4 form), or at its
+      // first (h = 0) or second (h = 1) 32-wide step (dense form, two stream steps per stage)
+      constexpr int GROUPS = C::BO / 16;
+      const int rg = j % GROUPS, h = j / GROUPS;
+      a_voff[i] = (uint32_t)((((o0 >> 4) + rg) * (int64_t)(SPARSE ? nk : 2 * nk) + h) << 10) + (uint32_t)(lane * 16);
+      a_dst[i] = (uint32_t)(C::X_BYTES + h * (C::BO * 64) + rg * 1024);
+    } else {
+      int64_t row;
+      int c;
+      if (SPARSE) { row = 16 * j + (lane >> 2); c = (lane & 3) ^ (int)((row >> 1) & 3); }
+      else { row = 8 * j + (lane >> 3); c = (lane & 7) ^ (int)(row & 7); }
+      if (row > o_last) row = o_last;
+      a_voff[i] = (uint32_t)((row * a_ld + c * 8) * 2);
+      a_dst[i] = (uint32_t)(C::X_BYTES + j * 1024);
+    }
   }
   if (SPARSE) {
 #pragma unroll
     for (int i = 0; i < C::S_PW; ++i) {
       const int j = (wave + i * C::NW) % C::S_LOADS;
-      int64_t row = 32 * j + (lane >> 1);
-      if (row > o_last) row = o_last;
-      s_voff[i] = (uint32_t)((row * (a.K >> 5) + (lane & 1)) * 4);
+      if constexpr (STREAM) {
+        // the tile's share of the (256-row tile, step) selector block: 256 bytes per 32-row pair
+        s_voff[i] = (uint32_t)(((o0 >> 8) * (int64_t)nk << 11) + (((o0 & 255) >> 5) + j) * 256 + lane * 4);
+      } else {
+        int64_t row = 32 * j + (lane >> 1);
+        if (row > o_last) row = o_last;
+        s_voff[i] = (uint32_t)((row * (a.K >> 5) + (lane & 1)) * 4);
+      }
       s_dst[i] = (uint32_t)(C::X_BYTES + C::A_BYTES + j * 256);
     }
   }
   const bf16_t* x_base = a.X + t0 * a.ldx;
-  const bf16_t* a_base = a.A + o0 * a_ld;
-  const uint32_t* s_base = SPARSE ? a.sel + o0 * (a.K >> 5) : nullptr;
+  const bf16_t* a_base = STREAM ? a.A : a.A + o0 * a_ld;
+  const uint32_t* s_base = SPARSE ? (STREAM ? a.sel : a.sel + o0 * (a.K >> 5)) : nullptr;
+  // elements the weight and selector pointers advance per stage
+  constexpr int A_STEP = STREAM ? (SPARSE ? 512 : 1024) : (SPARSE ? 32 : 64);
+  constexpr int S_STEP = STREAM ? 512 : 2;
 
-  // the d-th of this wave's LPW loads of stage ks into LDS buffer buf (d is a compile-time index)
-  auto issue_one = [&](auto d_tag, int ks, int buf) {
+  // The stage to be loaded next, as three running uniform pointers (X rows at the stage's k, weight, selectors),
+  // advanced by constants: the step loop then holds no address products.
+  uniform_ptr_t x_next = make_uniform(x_base), a_next = make_uniform(a_base), s_next = make_uniform(s_base);
+  // the d-th of this wave's LPW loads of that stage into LDS buffer buf (d is a compile-time index)
+  auto issue_one = [&](auto d_tag, int buf) {
     constexpr int d = decltype(d_tag)::value;
     const uint32_t lds = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)buf * C::STAGE);
     if constexpr (d < C::X_PW) {
-      dma16(make_uniform(x_base + (int64_t)ks * 64), x_voff[d], lds + x_dst[d]);
+      dma16(x_next, x_voff[d], lds + x_dst[d]);
     } else if constexpr (d < C::X_PW + C::A_PW) {
-      dma16(make_uniform(a_base + (int64_t)ks * (SPARSE ? 32 : 64)), a_voff[d - C::X_PW], lds + a_dst[d - C::X_PW]);
+      dma16(a_next, a_voff[d - C::X_PW], lds + a_dst[d - C::X_PW]);
     } else {
-      dma4(make_uniform(s_base + (int64_t)ks * 2), s_voff[d - C::X_PW - C::A_PW], lds + s_dst[d - C::X_PW - C::A_PW]);
+      dma4(s_next, s_voff[d - C::X_PW - C::A_PW], lds + s_dst[d - C::X_PW - C::A_PW]);
+    }
+    if constexpr (d == C::LPW - 1) {  // the stage is out: on to the next one
+      x_next += 64 * sizeof(bf16_t);
+      a_next += A_STEP * sizeof(bf16_t);
+      s_next += S_STEP * sizeof(uint32_t);
     }
   };
-  auto issue_stage = [&](int ks, int buf) {
+  auto issue_stage = [&](int buf) {
     [&]<int... D>(std::integer_sequence<int, D...>) {
-      (issue_one(std::integral_constant<int, D>{}, ks, buf), ...);
+      (issue_one(std::integral_constant<int, D>{}, buf), ...);
     }(std::make_integer_sequence<int, C::LPW>{});
   };
 
@@ -349,9 +337,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
   // fragment read offsets inside a stage (the XOR undoes the swizzle applied by the loads)
   const int x_sw = r16 & 7;
   const int x_row = (wt * TT * 16 + r16) * 128;
-  const int a_row = C::X_BYTES + (wo * OT * 16 + r16) * C::A_ROWB;
-  const int a_sw = SPARSE ? ((r16 >> 1) & 3) : (r16 & 7);
-  const int s_row = C::X_BYTES + C::A_BYTES + (wo * OT * 16 + r16) * 8 + (kb >> 1) * 4;
+  // stream order keeps 64-byte weight rows in both forms (the dense stage is two such sub-tiles)
+  constexpr int A_ROWB = STREAM ? 64 : C::A_ROWB;
+  const int a_row = C::X_BYTES + (wo * OT * 16 + r16) * A_ROWB;
+  const int a_sw = (SPARSE || STREAM) ? ((r16 >> 1) & 3) : (r16 & 7);
+  const int s_row = STREAM ? C::X_BYTES + C::A_BYTES + (wo * OT / 2) * 256 + r16 * 16 + kb * 4
+                           : C::X_BYTES + C::A_BYTES + (wo * OT * 16 + r16) * 8 + (kb >> 1) * 4;
 
   // One sub-step = 32 matrix instructions per wave.  SPARSE: a stage is one sub-step (K = 64 through
   // v_smfmac 16x16x64).  Dense: a stage is two sub-steps of K = 32 (v_mfma 16x16x32), h selects the half.
@@ -368,9 +359,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
     if (SPARSE) {
 #pragma unroll
       for (int i = 0; i < OT; ++i) {
-        af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + ((kb ^ a_sw) * 16));
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_row + i * 16 * 8);
-        sel[i] = (int)(w >> ((kb & 1) * 16));
+        af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * A_ROWB + ((kb ^ a_sw) * 16));
+        if constexpr (STREAM) {
+          // one word serves the two 16-row blocks of a pair: low half / high half, picked by the instruction
+          sel[i] = (int)*reinterpret_cast<const uint32_t*>(base + s_row + (i / 2) * 256);
+        } else {
+          const uint32_t w = *reinterpret_cast<const uint32_t*>(base + s_row + i * 16 * 8);
+          sel[i] = (int)(w >> ((kb & 1) * 16));
+        }
       }
 #pragma unroll
       for (int j = 0; j < TT; ++j) {
@@ -381,8 +377,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < OT; ++i)
-        af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * C::A_ROWB + (((h * 4 + kb) ^ a_sw) * 16));
+      for (int i = 0; i < OT; ++i) {
+        if constexpr (STREAM)
+          af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + h * (C::BO * 64) + i * 16 * A_ROWB + ((kb ^ a_sw) * 16));
+        else
+          af[i] = *reinterpret_cast<const u32x4_t*>(base + a_row + i * 16 * A_ROWB + (((h * 4 + kb) ^ a_sw) * 16));
+      }
 #pragma unroll
       for (int j = 0; j < TT; ++j)
         bd[j] = *reinterpret_cast<const u32x4_t*>(base + x_row + j * 16 * 128 + (((h * 4 + kb) ^ x_sw) * 16));
@@ -392,19 +392,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
   // between them, one every few instructions, so that the memory pipe is fed evenly instead of in bursts
   constexpr int MMA = OT * TT;
   constexpr int EVERY = MMA / C::LPW > 0 ? MMA / C::LPW : 1;
-  auto multiply = [&](bool load, int lks, int lbuf) {
+  auto multiply = [&](bool load, int lbuf) {
     [&]<int... Q>(std::integer_sequence<int, Q...>) {
       ([&] {
         constexpr int j = Q / OT, i = Q % OT;
         if (SPARSE)
           acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
                                                                 __builtin_bit_cast(bf16x16_t, bs[j]), acc[i][j],
-                                                                sel[i], 0, 0);
+                                                                sel[i], 0, STREAM ? (i & 1) : 0);
         else
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
                                                               __builtin_bit_cast(bf16x8_t, bd[j]), acc[i][j], 0, 0, 0);
         if constexpr (Q % EVERY == EVERY - 1 && Q / EVERY < C::LPW) {
-          if (load) issue_one(std::integral_constant<int, Q / EVERY>{}, lks, lbuf);
+          if (load) issue_one(std::integral_constant<int, Q / EVERY>{}, lbuf);
           __builtin_amdgcn_sched_barrier(0);
         }
       }(), ...);
@@ -418,16 +418,33 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
     else wait_loads_outstanding<0>();
   };
 
-  const int nk = (int)(a.K / C::KC);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s)
-    if (s < STAGES - 1 && s < nk) issue_stage(s, s);
+    if (s < STAGES - 1 && s < nk) issue_stage(s);
 
   // One barrier per stage; the buffer multiplied in the previous step is refilled right after the barrier,
-  // STAGES-1 stages ahead.
+  // STAGES-1 stages ahead.  A wave issues one instruction at a time, so whatever the step spends on addresses and
+  // conditions its matrix instructions do not get: the steady state (every step has a stage to load) runs STAGES
+  // steps at a time, which makes every LDS buffer a constant and leaves the step without branches; the last steps
+  // run the general form.
+  int ks = 0;
+  for (; ks + 2 * STAGES - 2 < nk; ks += STAGES) {
+    [&]<int... B>(std::integer_sequence<int, B...>) {
+      ([&] {
+        constexpr int buf = B, nbuf = (B + STAGES - 1) % STAGES;
+        wait_stage(STAGES == 3 ? 1 : 0);
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+          read_frags(buf, h);
+          multiply(h == 0, nbuf);
+        }
+      }(), ...);
+    }(std::make_integer_sequence<int, STAGES>{});
+  }
   {
-    int buf = 0;
-    for (int ks = 0; ks < nk; ++ks) {
+    int buf = 0;  // ks is a multiple of STAGES here
+    for (; ks < nk; ++ks) {
       wait_stage((STAGES == 3 && ks + 1 < nk) ? 1 : 0);
       __builtin_amdgcn_s_barrier();
       int nbuf = buf + STAGES - 1;
@@ -435,7 +452,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
 #pragma unroll
       for (int h = 0; h < H; ++h) {
         read_frags(buf, h);
-        multiply(h == 0 && ks + STAGES - 1 < nk, ks + STAGES - 1, nbuf);
+        multiply(h == 0 && ks + STAGES - 1 < nk, nbuf);
       }
       if (++buf == STAGES) buf = 0;
     }
@@ -459,11 +476,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
   }
 }
 
+// Both weight orders live in one kernel (a block-uniform branch): the layers of a launch may differ in it (2:4 and
+// N = M are read as packed, the other levels in stream order), and every launch more is a partly filled chip more.
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
 __global__ void __launch_bounds__(WO * WT * 64)
 nm_gemm_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  gemm_tile<SPARSE, WO, WT, OT, TT, STAGES>(a, blockIdx.x, smem);
+  if (a.stream_form) gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, true>(a, blockIdx.x, smem);
+  else gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, false>(a, blockIdx.x, smem);
 }
 
 // The tiles of many small layers of one operand form in one launch: products of a few tokens are a handful of
@@ -488,7 +508,8 @@ nm_gemm_group_kernel(const GemmGroup g) {
     else hi = mid;
   }
   const unsigned first = lo ? g.block_end[lo - 1] : 0u;
-  gemm_tile<SPARSE, WO, WT, OT, TT, STAGES>(g.layer[lo], blockIdx.x - first, smem);
+  if (g.layer[lo].stream_form) gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, true>(g.layer[lo], blockIdx.x - first, smem);
+  else gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, false>(g.layer[lo], blockIdx.x - first, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1085,35 +1106,53 @@ static bool tiles_ok(int64_t K, const void* X, int64_t ldx, const void* values, 
   return true;
 }
 
-// Which product kernel a layer of O out-features runs at T tokens: 0 = the persistent 256 x 256 kernel
-// (needs the weight in stream order), 1.. = the tiled kernel with smaller tiles (row-major operand form).
-static int pick_tile(int64_t O, int64_t T) {
+// Which product kernel a layer of O out-features runs at T tokens: 0 = the persistent 256 x 256 kernel (needs the
+// weight in stream order), 2 = the tiled kernel with 128 x 128 tiles, 3 = with 64 x 64 tiles (row-major operand
+// forms).  The choice is the smaller of two estimated durations (microseconds), a model fitted to measured
+// launches on DeiT- and Swin-shaped layers:
+//   persistent: one block per compute unit walks ceil(tiles / 256) tiles of `stream_steps` K steps each, about
+//               0.8 us per step plus 4.5 us to write a tile out, plus the launch;
+//   tiled:      a compute unit works through ceil(tiles / 256) tiles of 128 x 128 (one after the other or two at
+//               a time, the rate per unit is the same), `tiled_step_us` per K step of 64 (0.5 us in the 2:4
+//               form, 1.0 us in the dense form, whose step holds twice the matrix instructions).
+// A layer with fewer than 64 tiles of 128 x 128 takes 64 x 64 tiles: the few tiles there are finish sooner.
+// The persistent kernel used to be taken only with 256 tiles or more; with half as many it is still ahead of the
+// tiled kernel on long reductions (12608 tokens, 3072 -> 768: 44 us against 71 us).
+static int pick_tile(int64_t O, int64_t T, int64_t stream_steps, int64_t tiled_steps, double tiled_step_us) {
   const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
   const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
-  int pick = tiles_big >= 256 ? 0 : (tiles_mid >= 256 ? 2 : 3);
-  if (pick == 0 && T < 256) pick = 2;
-  return pick;
+  if (tiles_mid < 64) return 3;
+  if (T < 256) return 2;
+  const double est_stream = (double)((tiles_big + 255) / 256) * ((double)stream_steps * 0.8 + 4.5) + 4.0;
+  const double est_tiled = (double)((tiles_mid + 255) / 256) * ((double)tiled_steps * tiled_step_us + 1.5) + 3.0;
+  return est_stream <= est_tiled ? 0 : 2;
+}
+static int pick_tile(int64_t O, int64_t K, int64_t T, bool sparse_form) {
+  return pick_tile(O, T, sparse_form ? K / 64 : K / 32, K / 64, sparse_form ? 0.5 : 1.0);
 }
 
-// Whether the product at T tokens reads this layer's weight in stream order (the persistent kernel), and if
-// so in which form (2:4 values + selectors, or dense).
-bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* sparse_form) {
+// The form in which the product kernels read a layer's weight at T tokens.
+//   FORM_PACKED  as packed: the gather kernel (K % 64 != 0), or the tiled kernel at 2:4 and at N = M, whose packed
+//                layouts already are the row-major 2:4 / dense operands
+//   FORM_STREAM  stream order in the workspace (2:4 form for N <= 2, dense form otherwise): every other level, and
+//                every level on the persistent kernel
+enum { FORM_PACKED = 0, FORM_STREAM = 1 };
+static int operand_form(int64_t O, int64_t K, int64_t T, int N, int M, bool* sparse_form) {
   *sparse_form = N <= 2 && N < M;
-  if (K % 64) return false;
-  const int pk = pick_tile(O, T);
-  return pk == 0;
+  if (K % 64) return FORM_PACKED;
+  const bool as_packed = (N == 2 && M == 4) || N == M;
+  return (pick_tile(O, K, T, *sparse_form) != 0 && as_packed) ? FORM_PACKED : FORM_STREAM;
+}
+
+bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* sparse_form) {
+  return operand_form(O, K, T, N, M, sparse_form) == FORM_STREAM;
 }
 
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
-  if (K % 64) return 0;  // general kernel reads the packed layout itself
-  const bool sparse_form = N <= 2 && N < M;
-  if (pick_tile(O, T) == 0) {
-    const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // stream order, whole 256-row tiles
-    return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
-  }
-  if (N == 2 && M == 4) return 0;  // packed layout is the row-major operand form
-  if (N == M) return 0;            // values are the dense weight
-  return sparse_form ? (size_t)(O * K) + (size_t)(O * K / 8) : (size_t)(O * K) * 2;
+  bool sparse_form = false;
+  if (operand_form(O, K, T, N, M, &sparse_form) != FORM_STREAM) return 0;
+  const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // whole 256-row tiles
+  return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
 }
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
@@ -1217,7 +1256,7 @@ bool stream_i8_takes(int64_t O, int64_t K, int64_t T, int N, int M) {
   const bool sparse_form = N <= 2 && N < M;
   const int64_t kstep = sparse_form ? 128 : 64;
   // the per-tile constants alternate between two LDS slices, which needs tiles of at least three steps
-  return pick_tile(O, T) == 0 && K % kstep == 0 && K / kstep >= 3 && O <= (1 << 24) && T < (1ll << 31) && K <= (1 << 22);
+  return pick_tile(O, T, K / kstep, K / 128, sparse_form ? 0.5 : 1.0) == 0 && K % kstep == 0 && K / kstep >= 3 && O <= (1 << 24) && T < (1ll << 31) && K <= (1 << 22);
 }
 
 hipError_t launch_stream_i8(const StreamI8Args& a, hipStream_t s) {
@@ -1258,7 +1297,7 @@ static hipError_t launch_general(const SpmmArgs& a, hipStream_t s) {
 // stream order first (a pass over the weight only), then it is an ordinary product with I out-features and a
 // reduction of R.  Shapes: enough 256 x 256 tiles, R % 64 == 0, Out rows in whole aligned 16-byte pieces.
 size_t dense_transposed_workspace_bytes(int64_t R, int64_t I, int64_t T) {
-  if ((R % 64) || pick_tile(I, T) != 0) return 0;
+  if ((R % 64) || pick_tile(I, R, T, false) != 0) return 0;
   return (size_t)(((I + 255) / 256) * 256) * (size_t)R * 2;
 }
 
@@ -1283,9 +1322,57 @@ hipError_t launch_dense_transposed(const bf16_t* Ws, int64_t R, int64_t I, int64
   g.X = Q; g.bias = nullptr; g.Y = Out;
   g.O = I; g.K = R; g.T = T; g.ldx = ldq; g.ldy = ldo;
   g.n_o_tiles = g.n_t_tiles = 0;
-  g.out_bf16 = out_bf16; g.vec_store = 1;
+  g.out_bf16 = out_bf16; g.vec_store = 1; g.stream_form = 1;
   *taken = true;
   return dispatch_gemm<false>(g, 0, s);
+}
+
+// The stream-order pre-pass of a layer into its workspace.
+static hipError_t launch_stream_prepass(const SpmmArgs& a, bool sparse_form, hipStream_t s) {
+  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
+  const int64_t o_pad = ((a.O + 255) / 256) * 256;
+  if (sparse_form) {
+    unsigned char* sel_s = ws + (size_t)o_pad * (size_t)a.K;
+    const int64_t n = o_pad * (a.K / 32);
+    const dim3 grid((unsigned)((n + 255) / 256));
+    switch (a.N * 32 + a.M) {
+#define X(n_, m_)                                                                                              \
+  case n_ * 32 + m_:                                                                                           \
+    hipLaunchKernelGGL((recode_stream_kernel<n_, m_>), grid, dim3(256), 0, s, a.values, a.indices, a.O, o_pad, a.K, \
+                       ws, sel_s);                                                                             \
+    break;
+      X(1, 4) X(2, 4) X(1, 8) X(2, 8) X(1, 16) X(2, 16)
+#undef X
+      default: return hipErrorInvalidValue;
+    }
+  } else {
+    const int64_t n = o_pad * (a.K / 8);
+    hipLaunchKernelGGL(expand_stream_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.values, a.indices,
+                       a.O, o_pad, a.K, a.N, a.M, ws);
+  }
+  return hipGetLastError();
+}
+
+// Operands of the matrix-core kernels for a layer whose form is known.
+static void fill_gemm_args(const SpmmArgs& a, int form, bool sparse_form, GemmArgs* g) {
+  g->X = a.X; g->bias = a.bias; g->Y = a.Y;
+  g->O = a.O; g->K = a.K; g->T = a.T; g->ldx = a.ldx; g->ldy = a.ldy;
+  g->out_bf16 = a.out_bf16;
+  g->n_o_tiles = g->n_t_tiles = 0;
+  // 16-byte pieces of Y rows: every row start and the row end fall on a piece boundary
+  const int per_piece = a.out_bf16 ? 8 : 4;
+  g->vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
+                 (a.bias == nullptr || aligned_to(a.bias, 16));
+  g->stream_form = form == FORM_STREAM;
+  if (form == FORM_STREAM) {
+    const int64_t o_pad = ((a.O + 255) / 256) * 256;
+    unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
+    g->A = reinterpret_cast<const bf16_t*>(ws);
+    g->sel = sparse_form ? reinterpret_cast<const uint32_t*>(ws + (size_t)o_pad * (size_t)a.K) : nullptr;
+  } else {
+    g->A = a.values;  // 2:4: values + index words are the row-major 2:4 operand; N = M: the dense weight
+    g->sel = sparse_form ? a.indices : nullptr;
+  }
 }
 
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases) {
@@ -1295,148 +1382,47 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
     if (!product) return hipSuccess;  // the gather kernel reads the packed layout itself
     return launch_general(a, s);
   }
+  bool sparse_form = false;
+  const int form = operand_form(a.O, a.K, a.T, a.N, a.M, &sparse_form);
   const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256))) {
     *workspace_short = true;
     return hipSuccess;
   }
-  const int pick = pick_tile(a.O, a.T);
-  const bool sparse_form = a.N <= 2 && a.N < a.M;
+  const int pick = pick_tile(a.O, a.K, a.T, sparse_form);
   GemmArgs g;
-  g.X = a.X; g.bias = a.bias; g.Y = a.Y;
-  g.O = a.O; g.K = a.K; g.T = a.T; g.ldx = a.ldx; g.ldy = a.ldy;
-  g.out_bf16 = a.out_bf16;
-  g.n_o_tiles = g.n_t_tiles = 0;
-  g.sel = nullptr;
-  // 16-byte pieces of Y rows: every row start and the row end fall on a piece boundary
-  const int per_piece = a.out_bf16 ? 8 : 4;
-  g.vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
-                (a.bias == nullptr || aligned_to(a.bias, 16));
-  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
-
-  if (pick == 0) {
-    // persistent kernel: every level goes through the stream-order pre-pass; it writes Y in 16-byte pieces only
-    if (product && (!g.vec_store || a.ldy > 0x7FFFFFFF)) return launch_general(a, s);  // reads the packed layout itself
-    const int64_t o_pad = ((a.O + 255) / 256) * 256;
-    if (sparse_form) {
-      unsigned char* vals_s = ws;
-      unsigned char* sel_s = ws + (size_t)o_pad * (size_t)a.K;
-      if (prepare) {
-        const int64_t n = o_pad * (a.K / 32);
-        const dim3 grid((unsigned)((n + 255) / 256));
-        switch (a.N * 32 + a.M) {
-#define X(n_, m_)                                                                                              \
-  case n_ * 32 + m_:                                                                                           \
-    hipLaunchKernelGGL((recode_stream_kernel<n_, m_>), grid, dim3(256), 0, s, a.values, a.indices, a.O, o_pad, a.K, \
-                       vals_s, sel_s);                                                                         \
-    break;
-          X(1, 4) X(2, 4) X(1, 8) X(2, 8) X(1, 16) X(2, 16)
-#undef X
-          default: return hipErrorInvalidValue;
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-      }
-      g.A = reinterpret_cast<const bf16_t*>(vals_s);
-      g.sel = reinterpret_cast<const uint32_t*>(sel_s);
-      return product ? dispatch_gemm<true>(g, pick, s) : hipSuccess;
-    }
-    if (prepare) {
-      const int64_t n = o_pad * (a.K / 8);
-      hipLaunchKernelGGL(expand_stream_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.values, a.indices,
-                         a.O, o_pad, a.K, a.N, a.M, ws);
-      hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return e;
-    }
-    g.A = reinterpret_cast<const bf16_t*>(ws);
-    return product ? dispatch_gemm<false>(g, pick, s) : hipSuccess;
+  fill_gemm_args(a, form, sparse_form, &g);
+  // the persistent kernel writes Y in 16-byte pieces only; other outputs go to the gather kernel, which reads the
+  // packed layout itself
+  const bool gather = pick == 0 && (!g.vec_store || a.ldy > 0x7FFFFFFF);
+  if (prepare && form == FORM_STREAM && !(gather && product)) {
+    hipError_t e = launch_stream_prepass(a, sparse_form, s);
+    if (e != hipSuccess) return e;
   }
-
-  // tiled kernel with smaller tiles: row-major operand forms
-  if (sparse_form) {
-    if (a.N == 2 && a.M == 4) {
-      g.A = a.values; g.sel = a.indices;
-    } else {
-      bf16_t* v24 = reinterpret_cast<bf16_t*>(ws);
-      uint32_t* s24 = reinterpret_cast<uint32_t*>(ws + (size_t)(a.O * a.K));
-      if (prepare) {
-        const int64_t n = a.O * (a.K / 32);
-        const dim3 grid((unsigned)((n + 255) / 256));
-        switch (a.N * 32 + a.M) {
-#define X(n_, m_)                                                                                                 \
-  case n_ * 32 + m_:                                                                                              \
-    hipLaunchKernelGGL((recode_to_2of4_kernel<n_, m_>), grid, dim3(256), 0, s, a.values, a.indices, a.O, a.K, v24, s24); \
-    break;
-          X(1, 4) X(1, 8) X(2, 8) X(1, 16) X(2, 16)
-#undef X
-          default: return hipErrorInvalidValue;
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-      }
-      g.A = v24; g.sel = s24;
-    }
-    return product ? dispatch_gemm<true>(g, pick, s) : hipSuccess;
-  }
-  if (a.N == a.M) {
-    g.A = a.values;
-  } else {
-    bf16_t* wd = reinterpret_cast<bf16_t*>(ws);
-    if (prepare) {
-      hipError_t e = launch_unpack(a.values, a.indices, a.O, a.K, a.N, a.M, wd, a.K, s);
-      if (e != hipSuccess) return e;
-    }
-    g.A = wd;
-  }
-  return product ? dispatch_gemm<false>(g, pick, s) : hipSuccess;
+  if (!product) return hipSuccess;
+  if (gather) return launch_general(a, s);
+  return sparse_form ? dispatch_gemm<true>(g, pick, s) : dispatch_gemm<false>(g, pick, s);
 }
 
 // The product of a prepared layer on the tiled kernel, as a table entry (the operands launch_spmm would hand the
 // kernel): false when the layer takes another path.
 static bool tiled_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form, int* pick) {
   if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
-  *pick = pick_tile(a.O, a.T);
+  const int form = operand_form(a.O, a.K, a.T, a.N, a.M, sparse_form);
+  *pick = pick_tile(a.O, a.K, a.T, *sparse_form);
   if (*pick == 0) return false;
-  *sparse_form = a.N <= 2 && a.N < a.M;
-  g->X = a.X; g->bias = a.bias; g->Y = a.Y;
-  g->O = a.O; g->K = a.K; g->T = a.T; g->ldx = a.ldx; g->ldy = a.ldy;
-  g->out_bf16 = a.out_bf16;
-  g->n_o_tiles = g->n_t_tiles = 0;
-  g->sel = nullptr;
-  const int per_piece = a.out_bf16 ? 8 : 4;
-  g->vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
-                 (a.bias == nullptr || aligned_to(a.bias, 16));
-  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
-  if (*sparse_form) {
-    if (a.N == 2 && a.M == 4) {
-      g->A = a.values; g->sel = a.indices;
-    } else {
-      g->A = reinterpret_cast<const bf16_t*>(ws);
-      g->sel = reinterpret_cast<const uint32_t*>(ws + (size_t)(a.O * a.K));
-    }
-  } else {
-    g->A = a.N == a.M ? a.values : reinterpret_cast<const bf16_t*>(ws);
-  }
+  fill_gemm_args(a, form, *sparse_form, g);
   return true;
 }
 
 // The product of a prepared layer on the persistent kernel, as a table entry: false when this layer takes
 // another path (too few tiles, a shape or alignment the kernel does not handle).
 static bool stream_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form) {
-  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T) || pick_tile(a.O, a.T) != 0) return false;
-  const int per_piece = a.out_bf16 ? 8 : 4;
-  const bool vec = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
-                   (a.bias == nullptr || aligned_to(a.bias, 16));
-  if (!vec || a.ldy > 0x7FFFFFFF) return false;
-  *sparse_form = a.N <= 2 && a.N < a.M;
-  unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
-  const int64_t o_pad = ((a.O + 255) / 256) * 256;
-  g->A = reinterpret_cast<const bf16_t*>(ws);
-  g->sel = *sparse_form ? reinterpret_cast<const uint32_t*>(ws + (size_t)o_pad * (size_t)a.K) : nullptr;
-  g->X = a.X; g->bias = a.bias; g->Y = a.Y;
-  g->O = a.O; g->K = a.K; g->T = a.T; g->ldx = a.ldx; g->ldy = a.ldy;
-  g->n_o_tiles = g->n_t_tiles = 0;
-  g->out_bf16 = a.out_bf16; g->vec_store = 1;
+  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
+  const int form = operand_form(a.O, a.K, a.T, a.N, a.M, sparse_form);
+  if (pick_tile(a.O, a.K, a.T, *sparse_form) != 0) return false;
+  fill_gemm_args(a, form, *sparse_form, g);
+  if (!g->vec_store || a.ldy > 0x7FFFFFFF) return false;
   return true;
 }
 

@@ -206,3 +206,73 @@ def test_deit_b_fc1_at_batch256_sampled():
         acc = nm.nm_linear_forward_i8(Wd, words, N, M, Xd, out_dtype=torch.int32)
         got = acc[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.int64)
         assert np.array_equal(got, q.nm_accumulate_i8(xq[rows], wq, mask)), (N, M)
+
+
+# ---- the compressed int8 form -----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,M", LEVELS)
+def test_pack_i8_bit_exact_and_round_trip(N, M):
+    # values and index words against the checker; a K whose 3-bit index rows straddle words; unpack restores W (.) m
+    rng = np.random.default_rng(7600 + N * 17 + M)
+    O, K = 37, 480 if M != 16 else 512
+    wq = wl.draw_int8(rng, O, K)
+    wq[0, :M] = -128
+    mask = random_mask(rng, O, K, N, M)
+    vals, idx = q.nm_pack_i8(wq, mask, N, M)
+    v, i = nm.nm_pack_i8(dev_i8(wq), dev_words(orc.mask_to_words(mask)), N, M)
+    assert np.array_equal(v.cpu().numpy(), vals)
+    assert np.array_equal(i.cpu().numpy().view(np.uint32), idx)
+    back = nm.nm_unpack_i8(v, i, K, N, M)
+    assert np.array_equal(back.cpu().numpy(), np.where(mask, wq, 0))
+
+
+def test_pack_i8_from_a_strided_weight_view():
+    rng = np.random.default_rng(7601)
+    O, K, N, M = 20, 64, 2, 8
+    big = wl.draw_int8(rng, O, K + 32)
+    wq = big[:, :K]
+    mask = random_mask(rng, O, K, N, M)
+    v, i = nm.nm_pack_i8(dev_i8(big)[:, :K], dev_words(orc.mask_to_words(mask)), N, M)
+    vals, idx = q.nm_pack_i8(np.ascontiguousarray(wq), mask, N, M)
+    assert np.array_equal(v.cpu().numpy(), vals) and np.array_equal(i.cpu().numpy().view(np.uint32), idx)
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (2, 4), (1, 8), (2, 8), (4, 8), (1, 16), (4, 16), (8, 8)])
+@pytest.mark.parametrize("shape", ["tiled", "persistent", "general"])
+def test_products_from_the_compressed_form(N, M, shape):
+    # the same integers whether the weight comes dense + mask or compressed, on every kernel family, and equal to
+    # the checker's; the prepared workspace is the same bytes from both sources
+    rng = np.random.default_rng(7700 + N * 17 + M + len(shape))
+    T, K, O = {"tiled": (300, 384, 200), "persistent": (129 * 256 - 3, 384, 500), "general": (50, 96, 40)}[shape]
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = random_mask(rng, O, K, N, M)
+    words = dev_words(orc.mask_to_words(mask))
+    Wd, Xd = dev_i8(wq), dev_i8(xq)
+    v, i = nm.nm_pack_i8(Wd, words, N, M)
+    acc_dense = nm.nm_linear_forward_i8(Wd, words, N, M, Xd, out_dtype=torch.int32)
+    acc_packed = nm.nm_linear_forward_i8_packed(v, i, K, N, M, Xd, out_dtype=torch.int32)
+    assert torch.equal(acc_dense, acc_packed)
+    rows = np.unique(np.concatenate([np.arange(0, min(T, 40)), np.arange(max(0, T - 40), T)]))
+    ref = q.nm_accumulate_i8(xq[rows], wq, mask)
+    assert np.array_equal(acc_packed[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.int64), ref)
+    if nm.nm_i8_workspace_bytes(O, K, N, M, T):
+        ws_d = nm.nm_i8_prepare(Wd, words, N, M, T)
+        ws_p = nm.nm_i8_prepare_packed(v, i, K, N, M, T)
+        assert torch.equal(ws_d, ws_p)
+        y = nm.nm_linear_forward_i8_packed_prepared(v, i, K, N, M, Xd, ws_p, out_dtype=torch.int32)
+        assert torch.equal(y, acc_dense)
+
+
+def test_rescaled_output_from_the_compressed_form():
+    rng = np.random.default_rng(7800)
+    T, K, O, N, M = 257, 256, 264, 2, 8
+    xq, wq = wl.draw_int8(rng, T, K), wl.draw_int8(rng, O, K)
+    mask = magnitude_mask(wq, N, M)
+    w_scale = (0.001 + 0.002 * rng.random(O)).astype(np.float32)
+    bias = rng.standard_normal(O).astype(np.float32)
+    v, i = nm.nm_pack_i8(dev_i8(wq), dev_words(orc.mask_to_words(mask)), N, M)
+    Y = nm.nm_linear_forward_i8_packed(v, i, K, N, M, dev_i8(xq), x_scale=0.02, w_scale=torch.from_numpy(w_scale).cuda(),
+                                       bias=torch.from_numpy(bias).cuda(), out_dtype=torch.float32)
+    acc = q.nm_accumulate_i8(xq, wq, mask)
+    Yref = q.nm_linear_i8(xq, wq, mask, np.float32(0.02), w_scale, bias)
+    check_scaled(host_output(Y), Yref, acc, np.float32(0.02) * w_scale, bias, False, "packed int8")

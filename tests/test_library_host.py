@@ -58,8 +58,8 @@ def test_workspace_sizes(lib):
     assert lib.nm_spmm_workspace_bytes(768, 768, 1, 8, 100) == 768 * 768 + 768 * 768 // 8
     assert lib.nm_spmm_workspace_bytes(768, 768, 4, 8, 100) == 768 * 768 * 2
     assert lib.nm_spmm_workspace_bytes(8, 24, 1, 8, 100) == 0          # general kernel, no scratch
-    # enough 256 x 256 tiles for the persistent kernel: every level is rewritten into stream order,
-    # rows padded to whole tiles (768 -> 768, 700 -> 768)
+    # the persistent kernel (long token counts) reads every level in stream order, rows padded to whole
+    # 256-row tiles (768 -> 768, 700 -> 768)
     assert lib.nm_spmm_workspace_bytes(768, 768, 2, 4, 50432) == 768 * 768 + 768 * 768 // 8
     assert lib.nm_spmm_workspace_bytes(700, 768, 1, 16, 50432) == 768 * 768 + 768 * 768 // 8
     assert lib.nm_spmm_workspace_bytes(768, 768, 4, 8, 50432) == 768 * 768 * 2
@@ -186,7 +186,7 @@ def test_spmm_argument_errors(lib):
     # a level that needs scratch: missing, short and misaligned workspaces are refused before any launch
     assert call(N=1, M=8) == 6
     need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 16)
-    assert need == 64 * 64 + 64 * 64 // 8
+    assert need == 256 * 64 + 256 * 64 // 8  # stream order: rows padded to a whole 256-row tile
     assert call(N=1, M=8, ws=FAKE, wsb=need - 1) == 6
     assert call(N=1, M=8, ws=FAKE + 16, wsb=need) == 6
     assert call(N=4, M=8, ws=None, wsb=0) == 6
@@ -318,6 +318,35 @@ def test_int8_argument_errors_and_sizes(lib):
     assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, 16, None, 0, None) == 6
     assert lib.nm_i8_prepare(FAKE, 64, 128, 128, FAKE, 2, 4, 0, FAKE, need, None) == 2
     assert lib.nm_i8_prepare(FAKE, 64, 48, 48, FAKE, 1, 8, 16, None, 0, None) == 0  # nothing to prepare
+
+
+def test_int8_compressed_form_argument_errors_and_sizes(lib):
+    assert lib.nm_values_i8_bytes(768, 768, 2, 8) == 768 * 768 // 4
+    assert lib.nm_values_i8_bytes(768, 770, 2, 8) == 0 and lib.nm_values_i8_bytes(768, 768, 9, 8) == 0
+    pk = lib.nm_pack_i8
+    assert pk(None, 4, 16, 16, 2, 4, FAKE, FAKE, FAKE, None) == 1 and pk(FAKE, 4, 16, 16, 2, 4, None, FAKE, FAKE, None) == 1
+    assert pk(FAKE, 4, 16, 16, 2, 4, FAKE, None, FAKE, None) == 1 and pk(FAKE, 4, 16, 16, 2, 4, FAKE, FAKE, None, None) == 1
+    assert pk(FAKE, 4, 16, 8, 2, 4, FAKE, FAKE, FAKE, None) == 2 and pk(FAKE, 4, 18, 18, 2, 4, FAKE, FAKE, FAKE, None) == 2
+    assert pk(FAKE, 4, 16, 16, 5, 4, FAKE, FAKE, FAKE, None) == 3 and pk(FAKE, 4, 16, 16, 2, 4, FAKE + 2, FAKE, FAKE, None) == 4
+    up = lib.nm_unpack_i8
+    assert up(None, FAKE, 4, 16, 2, 4, FAKE, 16, None) == 1 and up(FAKE, FAKE, 4, 16, 2, 4, FAKE, 8, None) == 2
+    assert up(FAKE, FAKE + 1, 4, 16, 2, 4, FAKE, 16, None) == 4
+
+    def call(fn=lib.nm_linear_forward_i8_packed, **kw):
+        a = dict(v=FAKE, i=FAKE, O=64, K=128, N=1, M=8, Xq=FAKE, T=16, ldx=128, Y=FAKE, ldy=64, dt=2, ws=FAKE, wsb=1 << 20)
+        a.update(kw)
+        return fn(a["v"], a["i"], a["O"], a["K"], a["N"], a["M"], a["Xq"], a["T"], a["ldx"], 1.0, None, None, a["Y"],
+                  a["ldy"], a["dt"], a["ws"], a["wsb"], None)
+
+    for fn in (lib.nm_linear_forward_i8_packed, lib.nm_linear_forward_i8_packed_prepared):
+        assert call(fn, v=None) == 1 and call(fn, i=None) == 1 and call(fn, Xq=None) == 1 and call(fn, Y=None) == 1
+        assert call(fn, N=0) == 3 and call(fn, K=132) == 2 and call(fn, T=0) == 2 and call(fn, ldx=64) == 2
+        assert call(fn, dt=7) == 5 and call(fn, i=FAKE + 2) == 4
+        assert call(fn, ws=None, wsb=0) == 6
+    need = lib.nm_i8_workspace_bytes(64, 128, 1, 8, 16)
+    assert lib.nm_i8_prepare_packed(FAKE, FAKE, 64, 128, 1, 8, 16, FAKE, need - 1, None) == 6
+    assert lib.nm_i8_prepare_packed(None, FAKE, 64, 128, 1, 8, 16, FAKE, need, None) == 1
+    assert lib.nm_i8_prepare_packed(FAKE, FAKE, 64, 48, 1, 8, 16, None, 0, None) == 0  # general kernel: nothing to prepare
 
 
 def test_prune_scored_argument_errors(lib):
