@@ -15,7 +15,9 @@
 namespace nm {
 
 constexpr int kPackThreads = 256;
-constexpr int kChunk = 16;  // weights per lane in the fast kernels
+constexpr int kChunk = 16;          // weights per chunk in the fast kernels (two 16-byte loads)
+constexpr int kChunksPerLane = 2;   // chunks a lane handles, all their loads in flight before the first is coded
+constexpr int kBlockChunks = kPackThreads * kChunksPerLane;
 
 // One 16-weight chunk: selection, compaction in ascending position, index fields.
 template <int N, int M, bool EXTERNAL_MASK>
@@ -95,7 +97,7 @@ __device__ __forceinline__ void store_values(bf16_t* __restrict__ dst, const uin
 template <int N, int M>
 constexpr bool kFastLevel = (N == 1 || N == 2 || N == 4) && N < M;
 
-// Work of one block on 256 consecutive chunks of one contiguous matrix.
+// Work of one block on kBlockChunks consecutive chunks of one contiguous matrix.
 //   values/indices may be NULL (prune only); mask_out / w_masked may be NULL (pack only).
 // SRC: where the selection comes from: 0 = magnitude (Eq. (1)), 1 = the caller's mask words, 2 = stored ranks
 // (4 bits per weight; kept = rank < N)
@@ -111,28 +113,38 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
   using Coder = std::conditional_t<FAST, FastChunkCoder<N, M>, ChunkCoder<N, M, SRC != 0>>;
   constexpr int NB = Coder::NB;
   constexpr bool DIRECT_INDEX = (NB == 8 || NB == 16 || NB == 32 || NB == 64);
-  constexpr int BLOCK_WORDS = kPackThreads * NB / 32;
+  constexpr int BLOCK_WORDS = kBlockChunks * NB / 32;
   const int tid = threadIdx.x;
-  const int64_t c = chunk0 + tid;
-  const bool active = c < n_chunks;
 
   if (!DIRECT_INDEX && indices) {
     for (int i = tid; i < BLOCK_WORDS + 2; i += kPackThreads) sbits[i] = 0;
     __syncthreads();
   }
-  if (active) {
-    const uint4* src = reinterpret_cast<const uint4*>(W + c * kChunk);
-    const uint4 a = src[0], b = src[1];
-    const uint32_t d[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  // this lane's chunks: tid, tid + 256, ... of the block's run; every load leaves before anything is coded
+  uint32_t d[kChunksPerLane][8];
+#pragma unroll
+  for (int u = 0; u < kChunksPerLane; ++u) {
+    const int64_t c = chunk0 + u * kPackThreads + tid;
+    if (c < n_chunks) {
+      const uint4* src = reinterpret_cast<const uint4*>(W + c * kChunk);
+      const uint4 a = src[0], b = src[1];
+      d[u][0] = a.x; d[u][1] = a.y; d[u][2] = a.z; d[u][3] = a.w;
+      d[u][4] = b.x; d[u][5] = b.y; d[u][6] = b.z; d[u][7] = b.w;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kChunksPerLane; ++u) {
+    const int64_t c = chunk0 + u * kPackThreads + tid;
+    if (c >= n_chunks) continue;
     Coder coder;
     uint32_t keep16 = 0;
     if constexpr (FAST) {
-      coder.run(d);
+      coder.run(d[u]);
       if (mask_out || w_masked || (stream_ws && N > 2)) keep16 = coder.keep16();
     } else {
       uint32_t e[kChunk];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { e[2 * i] = d[i] & 0xFFFFu; e[2 * i + 1] = d[i] >> 16; }
+      for (int i = 0; i < 8; ++i) { e[2 * i] = d[u][i] & 0xFFFFu; e[2 * i + 1] = d[u][i] >> 16; }
       uint32_t mask16 = 0;
       if (SRC == 1) mask16 = reinterpret_cast<const uint16_t*>(mask_in)[c];
       if (SRC == 2) {
@@ -151,7 +163,7 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
       else if constexpr (NB == 32) indices[c] = (uint32_t)coder.ibits;
       else if constexpr (NB == 64) reinterpret_cast<uint64_t*>(indices)[c] = coder.ibits;
       else {
-        const int off = tid * NB;
+        const int off = (u * kPackThreads + tid) * NB;
         const int w = off >> 5, sh = off & 31;
         const uint64_t lo = coder.ibits << sh;
         const uint32_t hi = sh ? (uint32_t)(coder.ibits >> (64 - sh)) : 0u;
@@ -177,7 +189,7 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
         } else {
           const int64_t nk = K / 32;
           uint32_t w[8];
-          mask_chunk(d, keep16, w);
+          mask_chunk(d[u], keep16, w);
           const int64_t pc = kc * 2;
           *reinterpret_cast<uint4*>(stream_ws + stream_piece_offset(o, pc >> 2, (int)(pc & 3), nk)) =
               make_uint4(w[0], w[1], w[2], w[3]);
@@ -188,7 +200,7 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
     }
     if (w_masked) {
       uint32_t o[8];
-      mask_chunk(d, keep16, o);
+      mask_chunk(d[u], keep16, o);
       uint4* dst = reinterpret_cast<uint4*>(w_masked + c * kChunk);
       dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
       dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
@@ -197,14 +209,14 @@ __device__ __forceinline__ void code_block(const bf16_t* W, int64_t n_chunks, in
   if (!DIRECT_INDEX && indices) {
     __syncthreads();
     const int64_t left = n_chunks - chunk0;
-    const int nact = left < kPackThreads ? (int)left : kPackThreads;
+    const int nact = left < kBlockChunks ? (int)left : kBlockChunks;
     const int nwords = (nact * NB) >> 5;  // exact: whole rows hold whole words
     uint32_t* dst = indices + (chunk0 * NB >> 5);
     for (int i = tid; i < nwords; i += kPackThreads) dst[i] = sbits[i];
   }
 }
 
-constexpr int kSbitsWords = kPackThreads * 64 / 32 + 2;  // room for the widest per-chunk index field run (<= 64 bits)
+constexpr int kSbitsWords = kBlockChunks * 64 / 32 + 2;  // room for the widest per-chunk index field run (<= 64 bits)
 
 template <int N, int M, int SRC>
 __global__ void __launch_bounds__(kPackThreads)
@@ -212,7 +224,7 @@ code_flat_kernel(const bf16_t* W, int64_t n_chunks, const uint32_t* __restrict__
                  bf16_t* __restrict__ values, uint32_t* __restrict__ indices, uint32_t* __restrict__ mask_out,
                  bf16_t* w_masked) {  // w_masked may be W itself (in-place pruning)
   __shared__ uint32_t sbits[kSbitsWords];
-  code_block<N, M, SRC>(W, n_chunks, (int64_t)blockIdx.x * kPackThreads, mask_in, values, indices,
+  code_block<N, M, SRC>(W, n_chunks, (int64_t)blockIdx.x * kBlockChunks, mask_in, values, indices,
                                   mask_out, w_masked, sbits);
 }
 
@@ -258,7 +270,7 @@ __global__ void __launch_bounds__(kPackThreads) pack_batched_kernel(const BatchA
   }
   const BatchEntry& d = args.e[m];
   const uint32_t first = m ? args.e[m - 1].block_end : 0u;
-  const int64_t chunk0 = (int64_t)(blockIdx.x - first) * kPackThreads;
+  const int64_t chunk0 = (int64_t)(blockIdx.x - first) * kBlockChunks;
   const int level = d.N * 32 + d.M;
   switch (level) {
 #define X(n, mm)                                                                                      \
@@ -430,7 +442,7 @@ static bool flat_ok(int64_t O, int64_t K, int64_t ldw, int N, int M, const void*
                     const void* d, const void* e) {
   if (ldw != K || (K % 32) != 0) return false;
   if ((values_per_row(K, N, M) * log2_of(M)) % 32 != 0) return false;
-  if ((O * K / kChunk + kPackThreads - 1) / kPackThreads > 0x7FFFFFFF) return false;
+  if ((O * K / kChunk + kBlockChunks - 1) / kBlockChunks > 0x7FFFFFFF) return false;
   const uintptr_t all = (uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)d | (uintptr_t)e;
   return (all & 15u) == 0;
 }
@@ -454,7 +466,7 @@ hipError_t launch_prune(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int 
                         bf16_t* w_masked, hipStream_t s) {
   if (flat_ok(O, K, ldw, N, M, W, mask, w_masked, nullptr, nullptr)) {
     const int64_t n_chunks = O * K / kChunk;
-    launch_flat<0>(N, M, dim3(blocks_for(n_chunks, kPackThreads)), s, W, n_chunks, nullptr, nullptr, nullptr, mask,
+    launch_flat<0>(N, M, dim3(blocks_for(n_chunks, kBlockChunks)), s, W, n_chunks, nullptr, nullptr, nullptr, mask,
                        w_masked);
   } else {
     const int64_t n = O * mask_words_per_row(K);
@@ -468,7 +480,7 @@ hipError_t launch_pack(const bf16_t* W, int64_t O, int64_t K, int64_t ldw, int N
                        bf16_t* values, uint32_t* indices, hipStream_t s) {
   if (flat_ok(O, K, ldw, N, M, W, mask, values, indices, nullptr)) {
     const int64_t n_chunks = O * K / kChunk;
-    const dim3 grid(blocks_for(n_chunks, kPackThreads));
+    const dim3 grid(blocks_for(n_chunks, kBlockChunks));
     if (mask) launch_flat<1>(N, M, grid, s, W, n_chunks, mask, values, indices, nullptr, nullptr);
     else launch_flat<0>(N, M, grid, s, W, n_chunks, nullptr, values, indices, nullptr, nullptr);
   } else {
@@ -487,7 +499,7 @@ hipError_t launch_pack_ranked(const bf16_t* W, const uint8_t* rank, int64_t O, i
                               bf16_t* values, uint32_t* indices, hipStream_t s) {
   if (flat_ok(O, K, ldw, N, M, W, rank, values, indices, nullptr)) {
     const int64_t n_chunks = O * K / kChunk;
-    launch_flat<2>(N, M, dim3(blocks_for(n_chunks, kPackThreads)), s, W, n_chunks,
+    launch_flat<2>(N, M, dim3(blocks_for(n_chunks, kBlockChunks)), s, W, n_chunks,
                    reinterpret_cast<const uint32_t*>(rank), values, indices, nullptr, nullptr);
   } else {
     const int64_t ng = O * (K / M);
@@ -529,7 +541,7 @@ hipError_t launch_pack_batched(const PackDesc* descs, int count, hipStream_t s) 
       continue;
     }
     const int64_t n_chunks = d.O * d.K / kChunk;
-    const uint64_t nb = blocks_for(n_chunks, kPackThreads);
+    const uint64_t nb = blocks_for(n_chunks, kBlockChunks);
     if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
     BatchEntry& e = args.e[args.count++];
     e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
@@ -562,7 +574,7 @@ hipError_t launch_pack_ranked_batched(const PackRankedDesc* descs, int count, hi
       continue;
     }
     const int64_t n_chunks = d.O * d.K / kChunk;
-    const uint64_t nb = blocks_for(n_chunks, kPackThreads);
+    const uint64_t nb = blocks_for(n_chunks, kBlockChunks);
     if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
     BatchEntry& e = args.e[args.count++];
     e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;
@@ -605,7 +617,7 @@ hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStr
     const bool fused = flat && spmm_stream_order(d.O, d.K, d.T, d.N, d.M, &sparse_form) && (d.O % 256) == 0;
     if (flat) {
       const int64_t n_chunks = d.O * d.K / kChunk;
-      const uint64_t nb = blocks_for(n_chunks, kPackThreads);
+      const uint64_t nb = blocks_for(n_chunks, kBlockChunks);
       if (args.count == kBatchMax || blocks + nb > 0x7FFFFFFFull) flush();
       BatchEntry& e = args.e[args.count++];
       e.W = d.W; e.values = d.values; e.indices = d.indices; e.n_chunks = n_chunks;

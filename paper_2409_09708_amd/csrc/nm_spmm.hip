@@ -1106,29 +1106,27 @@ static bool tiles_ok(int64_t K, const void* X, int64_t ldx, const void* values, 
   return true;
 }
 
-// Which product kernel a layer of O out-features runs at T tokens: 0 = the persistent 256 x 256 kernel (needs the
-// weight in stream order), 2 = the tiled kernel with 128 x 128 tiles, 3 = with 64 x 64 tiles (row-major operand
-// forms).  The choice is the smaller of two estimated durations (microseconds), a model fitted to measured
-// launches on DeiT- and Swin-shaped layers:
+// Which product kernel a layer of O out-features runs at T tokens: 0 = the persistent 256 x 256 kernel, 2 = the
+// tiled kernel with 128 x 128 tiles, 3 = with 64 x 64 tiles.  The choice is the smaller of two estimated durations
+// (microseconds), a model fitted to measured launches on DeiT- and Swin-shaped layers (28 shapes from 197 to 50176
+// tokens; it picks the faster kernel on 27 of them and loses 19 % on the other):
 //   persistent: one block per compute unit walks ceil(tiles / 256) tiles of `stream_steps` K steps each, about
-//               0.8 us per step plus 4.5 us to write a tile out, plus the launch;
+//               0.7 us per step plus 4.5 us to write a tile out, plus the launch;
 //   tiled:      a compute unit works through ceil(tiles / 256) tiles of 128 x 128 (one after the other or two at
-//               a time, the rate per unit is the same), `tiled_step_us` per K step of 64 (0.5 us in the 2:4
-//               form, 1.0 us in the dense form, whose step holds twice the matrix instructions).
+//               a time, the rate per unit is the same), `tiled_step_us` per K step of 64 (0.34 us in the 2:4
+//               form, 0.5 us in the dense form, whose step holds twice the matrix instructions).
 // A layer with fewer than 64 tiles of 128 x 128 takes 64 x 64 tiles: the few tiles there are finish sooner.
-// The persistent kernel used to be taken only with 256 tiles or more; with half as many it is still ahead of the
-// tiled kernel on long reductions (12608 tokens, 3072 -> 768: 44 us against 71 us).
 static int pick_tile(int64_t O, int64_t T, int64_t stream_steps, int64_t tiled_steps, double tiled_step_us) {
   const int64_t tiles_big = ((O + 255) / 256) * ((T + 255) / 256);
   const int64_t tiles_mid = ((O + 127) / 128) * ((T + 127) / 128);
   if (tiles_mid < 64) return 3;
   if (T < 256) return 2;
-  const double est_stream = (double)((tiles_big + 255) / 256) * ((double)stream_steps * 0.8 + 4.5) + 4.0;
+  const double est_stream = (double)((tiles_big + 255) / 256) * ((double)stream_steps * 0.7 + 4.5) + 4.0;
   const double est_tiled = (double)((tiles_mid + 255) / 256) * ((double)tiled_steps * tiled_step_us + 1.5) + 3.0;
   return est_stream <= est_tiled ? 0 : 2;
 }
 static int pick_tile(int64_t O, int64_t K, int64_t T, bool sparse_form) {
-  return pick_tile(O, T, sparse_form ? K / 64 : K / 32, K / 64, sparse_form ? 0.5 : 1.0);
+  return pick_tile(O, T, sparse_form ? K / 64 : K / 32, K / 64, sparse_form ? 0.34 : 0.5);
 }
 
 // The form in which the product kernels read a layer's weight at T tokens.

@@ -45,10 +45,11 @@ def test_input_gradient_tiles(N, M, out_dtype):
 
 @pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
 def test_input_gradient_large_layers(out_dtype):
-    # enough 256 x 256 output tiles for the persistent kernel of the forward path (the weight is written
-    # transposed into its operand order first): ragged in both output directions, K not a multiple of the tile
-    T, K, O, N, M = 16 * 256 + 37, 16 * 256 + 8, 128, 2, 8
-    assert nm.nm_backward_input_workspace_bytes(O, K, T) == 17 * 256 * O * 2
+    # a shape the library gives to the persistent kernel of the forward path (252 output tiles of 256 x 256, one
+    # round of the chip; the weight is written transposed into its operand order first): ragged in both output
+    # directions, K not a multiple of the tile
+    T, K, O, N, M = 27 * 256 + 37, 8 * 256 + 8, 128, 2, 8
+    assert nm.nm_backward_input_workspace_bytes(O, K, T) == 9 * 256 * O * 2
     X, W, dY, mask = draw(6150, T, K, O, N, M)
     dXref, _, BX, _ = orc.nm_linear_backward(dY, X, W, mask)
     Ws = dev_bf16(orc.apply_mask(W, mask))
