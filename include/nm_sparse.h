@@ -75,7 +75,7 @@ enum {
   NM_ERR_LEVEL = 3,     /* M not in {4, 8, 16} or N outside [1, M] */
   NM_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
   NM_ERR_DTYPE = 5,     /* out_dtype is not one the call offers */
-  NM_ERR_WORKSPACE = 6, /* workspace is NULL or smaller than nm_spmm_workspace_bytes() */
+  NM_ERR_WORKSPACE = 6, /* workspace is NULL or smaller than nm_spmm_workspace_bytes() and the shape needs one */
   NM_ERR_DEVICE = 7,    /* a HIP call failed; see nm_last_hip_error() */
   NM_ERR_EXHAUSTED = 8  /* nm_sample_config ran out of random numbers before a configuration fell into the interval */
 };
@@ -210,6 +210,11 @@ int32_t nm_pack_ranked_batched(const nm_pack_ranked_desc* descs, int32_t count, 
  *   workspace        scratch of at least nm_spmm_workspace_bytes(O,K,N,M,T) bytes, 256-byte
  *                    aligned; may be NULL when that size is 0.  Its contents are undefined
  *                    after the call; concurrent calls need distinct workspaces.
+ *                    Without a workspace (NULL, or too small), a product of T <= 208 tokens at a level of
+ *                    {1:4, 1:8, 2:8, 4:8, 1:16, 2:16, 4:16} with K % 64 == 0 and O % 4 == 0 still runs: a
+ *                    kernel reads the packed format itself (Fig. 2: values + positions, decoded on the fly;
+ *                    slower than the workspace path, nothing to prepare).  Every other shape reports
+ *                    NM_ERR_WORKSPACE.
  * The matrix-core kernels need K % 64 == 0, 16-byte aligned X, values and Y and ldx, ldy
  * multiples of 8; other shapes run a slower general kernel with the same results.  Rows of X and Y
  * that start on 128-byte boundaries (ldx, ldy multiples of 64) are fastest.

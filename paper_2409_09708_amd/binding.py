@@ -525,8 +525,10 @@ def nm_linear_forward_prepared(values, indices, K: int, N: int, M: int, X, works
 
 
 def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out_dtype=None, out=None,
-                      workspace=None, stream=None, _prepared=False):
-    """Y = X * W_s^T (+ bias) from the packed weight; Y is float32 (default) or bfloat16 [T, O]."""
+                      workspace=None, stream=None, _prepared=False, from_packed=False):
+    """Y = X * W_s^T (+ bias) from the packed weight; Y is float32 (default) or bfloat16 [T, O].
+    from_packed: hand the library no workspace, so that a product of up to 208 tokens runs straight from the packed
+    format (the library reports a missing workspace for shapes that path does not take)."""
     torch = _torch()
     _need(values, torch.bfloat16, "values")
     _need(indices, torch.int32, "indices")
@@ -547,7 +549,7 @@ def nm_linear_forward(values, indices, K: int, N: int, M: int, X, bias=None, out
     TY, OY, ldy = _rows(out, "out")
     if (TY, OY) != (T, O):
         raise ValueError("out must be [T, O]")
-    need = nm_spmm_workspace_bytes(O, K, N, M, T)
+    need = 0 if from_packed else nm_spmm_workspace_bytes(O, K, N, M, T)
     if workspace is None and need:
         if _prepared:
             raise ValueError("a prepared call needs the workspace nm_spmm_prepare filled")
@@ -907,5 +909,7 @@ def nm_linear_forward_i8_packed_prepared(values, indices, K: int, N: int, M: int
                                        stream, _prepared=True)
 
 
-def nm_spmm(values, indices, K: int, N: int, M: int, X, out_dtype=None, out=None, workspace=None, stream=None):
-    return nm_linear_forward(values, indices, K, N, M, X, None, out_dtype, out, workspace, stream)
+def nm_spmm(values, indices, K: int, N: int, M: int, X, out_dtype=None, out=None, workspace=None, stream=None,
+            from_packed=False):
+    return nm_linear_forward(values, indices, K, N, M, X, None, out_dtype, out, workspace, stream,
+                             from_packed=from_packed)

@@ -11,7 +11,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libnm_sparse.so")
-SOURCES = ("nm_api.hip", "nm_grad.hip", "nm_int8.hip", "nm_pack.hip", "nm_probe.hip", "nm_rank.hip", "nm_search.hip", "nm_spmm.hip")
+SOURCES = ("nm_api.hip", "nm_fewtok.hip", "nm_grad.hip", "nm_int8.hip", "nm_pack.hip", "nm_probe.hip", "nm_rank.hip", "nm_search.hip", "nm_spmm.hip")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-fno-gpu-rdc",

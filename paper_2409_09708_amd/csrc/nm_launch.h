@@ -128,6 +128,11 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
 bool spmm_workspace_short(const SpmmArgs& a);
 hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s);
 
+// nm_fewtok.hip: products at few tokens straight from the packed format (no workspace)
+bool fewtok_shape(int64_t O, int64_t K, int N, int M, int64_t T);
+bool fewtok_takes(const SpmmArgs& a);
+hipError_t launch_fewtok(const SpmmArgs* const* layers, int count, hipStream_t s);
+
 // Out[t, i] = sum_r Q[t, r] * Ws[r, i] on the persistent dense product kernel (weight transposed into stream
 // order in the workspace first); *taken stays false, and nothing is launched, when the shape, the alignment or
 // the workspace do not allow it.

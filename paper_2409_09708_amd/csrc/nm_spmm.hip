@@ -537,12 +537,15 @@ nm_gemm_group_kernel(const GemmGroup g) {
 // ---------------------------------------------------------------------------------------------
 template <bool SPARSE, int WO_, int WT_, int STAGES_, bool I8 = false>
 struct StreamCfg {
-  // Tiles are 256 out-features x (128 WT) tokens, a wave's share is 128 tokens wide.  The layout in use is
-  // WO 4, WT 2: one block of 8 waves (64 x 128 outputs each) per CU, two waves per SIMD, three stages (four
-  // for the dense form, whose stages are 32 KiB).  Measured and slower on transformer-sized layers: WO 2
-  // (4 waves of 128 x 128, one per SIMD with the 512-register budget: a lone wave does not hide its own LDS
-  // and issue latency) and WT 1 with two stages (256 x 128 tiles, two blocks of 4 waves per CU).
-  static constexpr int WO = WO_, WT = WT_, BO = 256, BT = 128 * WT, OT = BO / (WO * 16), TT = 8;
+  // Tiles are 256 out-features x 256 tokens on 8 waves (one block per CU, two waves per SIMD), three stages (four
+  // for the dense form, whose stages are 32 KiB); a wave holds 32 accumulator blocks of 16 x 16.  The layout in
+  // use is WO 4, WT 2 (64 out-features x 128 tokens per wave, 20 KiB of fragment reads per wave and step).
+  // Measured and no faster on transformer-sized layers: WO 2, WT 4 (128 x 64 per wave: a fifth fewer fragment
+  // bytes, the same time in the 2:4 form and 4 % more in the dense form), 4 waves of 128 x 128 (one per SIMD
+  // with the 512-register budget: a lone wave does not hide its own LDS and issue latency), and 256 x 128 tiles
+  // with two stages (two blocks of 4 waves per CU).
+  static constexpr int WO = WO_, WT = WT_, BO = 256, OT = BO / (WO * 16), TT = 32 / OT;  // 32 accumulator blocks per wave
+  static constexpr int TW = TT * 16, BT = TW * WT;       // tokens per wave, per tile
   static constexpr int NW = WO * WT, NT = NW * 64, STAGES = STAGES_;
   static constexpr int PER_CU = (NW == 4 && STAGES == 2) ? 2 : 1;  // co-resident blocks
   static constexpr int OW = OT * 16;                     // out-features per wave
@@ -590,6 +593,7 @@ struct StreamLayer {
   int32_t out_kind;     // NM_OUT_F32 / NM_OUT_BF16 / NM_OUT_I32 (int8 only)
   int32_t reserved;
 };
+constexpr int kStreamWO = 4, kStreamWT = 2;  // wave layout of the bfloat16 launches
 constexpr int kStreamLayersMax = 44;
 struct StreamGroup {
   int32_t count, n_tiles;
@@ -670,11 +674,16 @@ nm_stream_kernel(const StreamGroup g) {
       at.begin += share;
       share = xcd_share(++at.layer);
     }
-    const int local = xcd * ((g.layer[at.layer].n_tiles + 7) >> 3) + (entry - at.begin);
-    const int n_o = g.layer[at.layer].n_o_tiles;
+    // The table is read at this point of the program and not earlier: a scalar load the compiler starts before
+    // the K steps for use after them stays in flight through the steps, and with it in flight every wait for a
+    // fragment read has to drain the wave's whole LDS queue (scalar loads return out of order).
+    int layer = at.layer;
+    asm volatile("" : "+s"(layer));
+    const int local = xcd * ((g.layer[layer].n_tiles + 7) >> 3) + (entry - at.begin);
+    const int n_o = g.layer[layer].n_o_tiles;
     o_tile = local % n_o;
     t_lo = (int64_t)(local / n_o) * C::BT;
-    const int64_t T = g.layer[at.layer].T;
+    const int64_t T = g.layer[layer].T;
     t0 = t_lo + C::BT <= T ? t_lo : T - C::BT;
   };
 
@@ -779,8 +788,8 @@ nm_stream_kernel(const StreamGroup g) {
   FragAddr at0;
   at0.a = (uint32_t)(C::X_BYTES + (wo * C::OW + r16) * C::A_ROWB + ((kb ^ ((r16 >> 1) & 3)) * 16));
   at0.s = (uint32_t)(C::X_BYTES + C::A_BYTES + (I8 ? wo * OT : wo * C::OW / 32) * 256 + r16 * 16 + kb * 4);
-  at0.xlo = (uint32_t)((wt * 128 + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 1) & 3)) * 16)));
-  at0.xhi = (uint32_t)((wt * 128 + r16) * C::X_ROWB + ((4 + kb) ^ (r16 & 7)) * 16);
+  at0.xlo = (uint32_t)((wt * C::TW + r16) * C::X_ROWB + (SPARSE ? ((kb ^ (r16 & 7)) * 16) : ((kb ^ ((r16 >> 1) & 3)) * 16)));
+  at0.xhi = (uint32_t)((wt * C::TW + r16) * C::X_ROWB + ((4 + kb) ^ (r16 & 7)) * 16);
   auto frag_addr = [&](uint32_t stage_off) {
     return FragAddr{at0.a + stage_off, at0.s + stage_off, at0.xlo + stage_off, at0.xhi + stage_off};
   };
@@ -805,14 +814,17 @@ nm_stream_kernel(const StreamGroup g) {
   };
 
   // ---- prologue: three stages in flight, the first one landed, its first fragments in registers
-  // A stage's loads leave one at a time, SPREAD groups apart, from the barrier that frees the buffer (after group
-  // TT-3) round to the groups before the next step's barrier: load d after group (TT - 3 + d SPREAD) mod TT.
+  // A stage's loads leave LPG at a time (one, when there are as many groups as loads), SPREAD groups apart, from
+  // the barrier that frees the buffer (after group TT-3) round to the groups before the next step's barrier:
+  // loads d LPG .. d LPG + LPG - 1 after group (TT - 3 + d SPREAD) mod TT.
   // HEAD of them fall into the step that freed the buffer, the others into the next one.  The requests of the
   // eight waves then reach the CU's one load path spread over the step instead of in one burst, behind which
   // every wave's matrix instructions would queue (a wave issues in order).
-  constexpr int SPREAD = C::LPW <= 4 ? 2 : 1;
-  constexpr int HEAD = (3 + SPREAD - 1) / SPREAD;
-  static_assert(HEAD <= C::LPW && (C::LPW - 1) * SPREAD < C::TT, "the last load must be out before the next step's wait");
+  constexpr int LPG = (C::LPW + C::TT - 1) / C::TT;                     // loads that leave together
+  constexpr int SLOTS = (C::LPW + LPG - 1) / LPG;
+  constexpr int SPREAD = 2 * SLOTS <= C::TT ? 2 : 1;
+  constexpr int HEAD = ((3 + SPREAD - 1) / SPREAD) * LPG < C::LPW ? ((3 + SPREAD - 1) / SPREAD) * LPG : C::LPW;
+  static_assert((SLOTS - 1) * SPREAD < C::TT, "the last load must be out before the next step's wait");
   cursor_tile(0);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s) {
@@ -896,9 +908,16 @@ nm_stream_kernel(const StreamGroup g) {
           // the load that leaves after this group, if any: into the buffer this step has consumed (free since the
           // barrier), or the rest of the stage begun in the previous step into the buffer consumed there
           constexpr int since = (j - (TT - 3) + TT) % TT;  // groups since the barrier
-          if constexpr (since % SPREAD == 0 && since / SPREAD < C::LPW) {
-            issue_one(std::integral_constant<int, since / SPREAD>{}, j >= TT - 3 ? cur_off : prev_off);
-            if constexpr (since / SPREAD == C::LPW - 1) cursor_advance();
+          if constexpr (since % SPREAD == 0 && since / SPREAD < SLOTS) {
+            [&]<int... Q>(std::integer_sequence<int, Q...>) {
+              ([&] {
+                constexpr int d = since / SPREAD * LPG + Q;
+                if constexpr (d < C::LPW) {
+                  issue_one(std::integral_constant<int, d>{}, j >= TT - 3 ? cur_off : prev_off);
+                  if constexpr (d == C::LPW - 1) cursor_advance();
+                }
+              }(), ...);
+            }(std::make_integer_sequence<int, LPG>{});
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -930,6 +949,16 @@ nm_stream_kernel(const StreamGroup g) {
         for (int j = 0; j < TT; ++j) acc[i][j] = b;
       }
     }
+
+    // The layer's output geometry goes into registers now: read through the table entry after the steps, every
+    // store would wait for a scalar load of its own (and for everything else the wave has in flight with it).
+    int32_t ldy_s = L.ldy, o_s = L.O, kind_s = L.out_kind;
+    uint64_t y_s = reinterpret_cast<uint64_t>(L.Y);
+    asm volatile("" : "+s"(ldy_s), "+s"(o_s), "+s"(kind_s), "+s"(y_s));
+    // Nothing of this wave's LDS or scalar reads is in flight when the steps begin (it costs nothing here: all of
+    // them have just been used); the compiler then counts the fragment reads inside the steps exactly instead of
+    // draining the queue at the first waits of every pair of steps.
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
 
     // steps in pairs, so that every tile starts with fragment set 0; an odd count ends with a copy
     for (int ks = 0; ks + 1 < nk; ks += 2) {
@@ -978,11 +1007,6 @@ nm_stream_kernel(const StreamGroup g) {
         return acc[i][j];
       }
     };
-    // The layer's output geometry goes into registers first: read through the table entry, every store would
-    // wait for a scalar load of its own (and for everything else the wave has in flight with it).
-    int32_t ldy_s = L.ldy, o_s = L.O, kind_s = L.out_kind;
-    uint64_t y_s = reinterpret_cast<uint64_t>(L.Y);
-    asm volatile("" : "+s"(ldy_s), "+s"(o_s), "+s"(kind_s), "+s"(y_s));
     // global address space, so that the stores are not counted with the LDS operations
     using gbyte_t = __attribute__((address_space(1))) unsigned char;
     using gpiece_t = __attribute__((address_space(1))) u32x4_t;
@@ -992,13 +1016,14 @@ nm_stream_kernel(const StreamGroup g) {
       // pieces a lane holds for a token block (out-feature pairs 0 and 1, after the exchange between lane rows)
       // are pushed to the lanes that store them: lane 8m + p stores piece p (0..7) of token row m (first store) and
       // of token row m + 8 (second store).
-      static_assert(OT == 4, "two out-feature pairs per wave");
+      static_assert(OT % 4 == 0, "a line is two out-feature pairs");
+      constexpr int LINES = OT / 4;  // 128-byte lines per token row of the wave
       const int qk = ((kb & 1) << 1) | (kb >> 1);            // place of this lane's piece inside its pair's 64 bytes
       const int hi_rows = r16 >> 3;                          // this lane's token row belongs to the second store
       const int dest_a = (8 * (r16 & 7) + 4 * hi_rows + qk) * 4;
       const int dest_b = (8 * (r16 & 7) + 4 * (1 - hi_rows) + qk) * 4;
       const bool upper = (lane >> 2) & 1;                    // as a storing lane: pieces 4..7 (out-feature pair 1)
-      auto swapped = [&](int j, int ip) {
+      auto swapped = [&](int j, int ip) {  // ip: out-feature pair (blocks 2 ip and 2 ip + 1)
         const f32x4_t v0 = value(2 * ip, j), v1 = value(2 * ip + 1, j);
         const uint32_t a0 = pack_bf16x2(v0[0], v0[1]), a1 = pack_bf16x2(v0[2], v0[3]);
         const uint32_t b0 = pack_bf16x2(v1[0], v1[1]), b1 = pack_bf16x2(v1[2], v1[3]);
@@ -1007,8 +1032,9 @@ nm_stream_kernel(const StreamGroup g) {
         return u32x4_t{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
       };
       struct Lines { u32x4_t first, second; };
-      auto lines_of = [&](int j) {
-        const u32x4_t p0 = swapped(j, 0), p1 = swapped(j, 1);
+      auto lines_of = [&](int q) {  // q = j * LINES + line
+        const int j = q / LINES, h = q % LINES;
+        const u32x4_t p0 = swapped(j, 2 * h), p1 = swapped(j, 2 * h + 1);
         u32x4_t ra, rb;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -1026,23 +1052,27 @@ nm_stream_kernel(const StreamGroup g) {
         }
         return l;
       };
-      const int row = wt * 128 + (lane >> 3);                            // this lane's row of the tile in block j = 0, first store
-      const int64_t col = o0 + wo * C::OW + (lane & 7) * 8;              // its out-features
+      const int row = wt * C::TW + (lane >> 3);                            // this lane's row of the tile in block j = 0, first store
+      const int64_t col = o0 + wo * C::OW + (lane & 7) * 8;              // its out-features in line 0
       gbyte_t* dst = (gbyte_t*)y_s + ((t0 + row) * (int64_t)ldy_s + col) * 2;
       const int64_t half_bytes = (int64_t)ldy_s * 16;                    // 8 token rows further
-      const bool col_ok = col < o_s;
+      bool col_ok[LINES];
+#pragma unroll
+      for (int h = 0; h < LINES; ++h) col_ok[h] = col + h * 64 < o_s;
       Lines cur = lines_of(0);
 #pragma unroll
-      for (int j = 0; j < TT; ++j) {
+      for (int q = 0; q < TT * LINES; ++q) {
+        const int j = q / LINES, h = q % LINES;
         Lines nxt = cur;
-        if (j + 1 < TT) nxt = lines_of(j + 1);
-        if (row + j * 16 >= first_row && col_ok) __builtin_nontemporal_store(cur.first, (gpiece_t*)(dst));
-        if (row + j * 16 + 8 >= first_row && col_ok) __builtin_nontemporal_store(cur.second, (gpiece_t*)(dst + half_bytes));
-        dst += 2 * half_bytes;
+        if (q + 1 < TT * LINES) nxt = lines_of(q + 1);
+        if (row + j * 16 >= first_row && col_ok[h]) __builtin_nontemporal_store(cur.first, (gpiece_t*)(dst + h * 128));
+        if (row + j * 16 + 8 >= first_row && col_ok[h])
+          __builtin_nontemporal_store(cur.second, (gpiece_t*)(dst + half_bytes + h * 128));
+        if (h == LINES - 1) dst += 2 * half_bytes;
         cur = nxt;
       }
     } else {
-      const int row = wt * 128 + r16;
+      const int row = wt * C::TW + r16;
       const int64_t col = o0 + wo * C::OW + kb * 4;
       gbyte_t* dst = (gbyte_t*)y_s + ((t0 + row) * (int64_t)ldy_s + col) * 4;
       const int64_t block_bytes = (int64_t)ldy_s * 64;
@@ -1209,8 +1239,9 @@ static hipError_t launch_gemm_group(GemmGroup& grp, hipStream_t s) {
 
 template <bool SPARSE, bool I8 = false>
 static hipError_t launch_stream_group(const StreamGroup& grp, hipStream_t s) {
-  using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;  // dense stages are half the size: four fit
-  auto kern = nm_stream_kernel<SPARSE, 4, 2, SPARSE ? 3 : 4, I8>;
+  constexpr int WO = I8 ? 4 : kStreamWO, WT = I8 ? 2 : kStreamWT;
+  using C = StreamCfg<SPARSE, WO, WT, SPARSE ? 3 : 4, I8>;  // dense stages are half the size: four fit
+  auto kern = nm_stream_kernel<SPARSE, WO, WT, SPARSE ? 3 : 4, I8>;
   static PerDeviceOnce lds_limit;
   if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
   int cus = 0;
@@ -1226,7 +1257,7 @@ static hipError_t launch_stream_group(const StreamGroup& grp, hipStream_t s) {
 // Appends a layer to the table of a launch; false when its tiles would overflow the list.
 template <bool SPARSE>
 static bool group_append(StreamGroup& grp, const GemmArgs& g) {
-  using C = StreamCfg<SPARSE, 4, 2, SPARSE ? 3 : 4>;
+  using C = StreamCfg<SPARSE, kStreamWO, kStreamWT, SPARSE ? 3 : 4>;
   const int64_t n_o = (g.O + C::BO - 1) / C::BO, n_t = (g.T + C::BT - 1) / C::BT;
   const int64_t end = (int64_t)grp.n_tiles + n_o * n_t;
   if (grp.count >= kStreamLayersMax || end > 0x7FFFFFF0) return false;
@@ -1373,6 +1404,15 @@ static void fill_gemm_args(const SpmmArgs& a, int form, bool sparse_form, GemmAr
   }
 }
 
+// A layer whose operand-order workspace is missing (or too small) and which the few-token kernel can multiply
+// from the packed format instead.
+static bool packed_path(const SpmmArgs& a) {
+  if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
+  const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
+  if (!need || (a.workspace != nullptr && a.workspace_bytes >= need && aligned_to(a.workspace, 256))) return false;
+  return fewtok_takes(a);
+}
+
 hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, int phases) {
   *workspace_short = false;
   const bool prepare = phases & SPMM_PREPARE, product = phases & SPMM_PRODUCT;
@@ -1384,7 +1424,12 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
   const int form = operand_form(a.O, a.K, a.T, a.N, a.M, &sparse_form);
   const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256))) {
-    *workspace_short = true;
+    // no workspace: few tokens can still be multiplied straight from the packed format
+    if (!packed_path(a)) *workspace_short = true;
+    else if (product) {
+      const SpmmArgs* one = &a;
+      return launch_fewtok(&one, 1, s);
+    }
     return hipSuccess;
   }
   const int pick = pick_tile(a.O, a.K, a.T, sparse_form);
@@ -1405,6 +1450,7 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
 // The product of a prepared layer on the tiled kernel, as a table entry (the operands launch_spmm would hand the
 // kernel): false when the layer takes another path.
 static bool tiled_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form, int* pick) {
+  if (packed_path(a)) return false;
   if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
   const int form = operand_form(a.O, a.K, a.T, a.N, a.M, sparse_form);
   *pick = pick_tile(a.O, a.K, a.T, *sparse_form);
@@ -1416,6 +1462,7 @@ static bool tiled_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form, int* 
 // The product of a prepared layer on the persistent kernel, as a table entry: false when this layer takes
 // another path (too few tiles, a shape or alignment the kernel does not handle).
 static bool stream_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form) {
+  if (packed_path(a)) return false;
   if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
   const int form = operand_form(a.O, a.K, a.T, a.N, a.M, sparse_form);
   if (pick_tile(a.O, a.K, a.T, *sparse_form) != 0) return false;
@@ -1427,6 +1474,7 @@ static bool stream_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form) {
 // Products of many prepared layers: those the persistent kernel takes share launches (one table per operand
 // form, flushed when full), the others are launched one by one.  Results are those of the single calls.
 bool spmm_workspace_short(const SpmmArgs& a) {
+  if (packed_path(a)) return false;
   if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;  // the gather kernel needs none
   const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   return need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256));
@@ -1482,9 +1530,25 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
       mid_tiles += ((layers[i].O + 127) / 128) * ((layers[i].T + 127) / 128);
   }
   const bool promote = mid_tiles >= 256;
+  // few tokens and no workspace: all such layers of the call in one launch of the kernel that reads the packed format
+  {
+    constexpr int kChunk = 64;
+    const SpmmArgs* few[kChunk];
+    int n_few = 0;
+    for (int i = 0; i < count; ++i) {
+      if (!packed_path(layers[i])) continue;
+      few[n_few++] = &layers[i];
+      if (n_few == kChunk) {
+        if ((e = launch_fewtok(few, n_few, s)) != hipSuccess) return e;
+        n_few = 0;
+      }
+    }
+    if (n_few && (e = launch_fewtok(few, n_few, s)) != hipSuccess) return e;
+  }
   for (int i = 0; i < count; ++i) {
     GemmArgs g;
     bool sparse_form = false;
+    if (packed_path(layers[i])) continue;
     if (stream_entry(layers[i], &g, &sparse_form)) {
       StreamGroup& grp = sparse_form ? sparse_grp : dense_grp;
       bool ok = sparse_form ? group_append<true>(grp, g) : group_append<false>(grp, g);

@@ -183,31 +183,32 @@ def test_spmm_argument_errors(lib):
     assert call(K=66) == 2 and call(T=0) == 2 and call(ldx=32) == 2 and call(ldy=8) == 2
     assert call(dt=2) == 5
     assert call(X=FAKE + 1) == 4 and call(Y=FAKE + 2) == 4
-    # a level that needs scratch: missing, short and misaligned workspaces are refused before any launch
-    assert call(N=1, M=8) == 6
-    need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 16)
+    # a level that needs scratch: missing, short and misaligned workspaces are refused before any launch (above 208
+    # tokens; with fewer the product runs straight from the packed format when no workspace is given)
+    assert call(N=1, M=8, T=300) == 6
+    need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 300)
     assert need == 256 * 64 + 256 * 64 // 8  # stream order: rows padded to a whole 256-row tile
-    assert call(N=1, M=8, ws=FAKE, wsb=need - 1) == 6
-    assert call(N=1, M=8, ws=FAKE + 16, wsb=need) == 6
-    assert call(N=4, M=8, ws=None, wsb=0) == 6
+    assert call(N=1, M=8, T=300, ws=FAKE, wsb=need - 1) == 6
+    assert call(N=1, M=8, T=300, ws=FAKE + 16, wsb=need) == 6
+    assert call(N=4, M=8, T=300, ws=None, wsb=0) == 6
     lf = lib.nm_linear_forward(FAKE, FAKE, 64, 64, 2, 4, FAKE, 16, 64, FAKE + 2, FAKE, 64, 0, None, 0, None)
     assert lf == 4  # bias must be 4-byte aligned
 
 
 def test_prepare_and_prepared_argument_errors(lib):
-    need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 16)
-    assert lib.nm_spmm_prepare(None, FAKE, 64, 64, 1, 8, 16, FAKE, need, None) == 1
-    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 9, 8, 16, FAKE, need, None) == 3
-    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 60, 1, 8, 16, FAKE, need, None) == 2
+    need = lib.nm_spmm_workspace_bytes(64, 64, 1, 8, 300)
+    assert lib.nm_spmm_prepare(None, FAKE, 64, 64, 1, 8, 300, FAKE, need, None) == 1
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 9, 8, 300, FAKE, need, None) == 3
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 60, 1, 8, 300, FAKE, need, None) == 2
     assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 0, FAKE, need, None) == 2
-    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 16, None, 0, None) == 6
-    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 16, FAKE, need - 1, None) == 6
-    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 2, 4, 16, None, 0, None) == 0   # nothing to prepare at 2:4
-    assert lib.nm_spmm_prepare(FAKE, FAKE, 8, 24, 1, 8, 16, None, 0, None) == 0    # general kernel: no scratch
-    args = (FAKE, FAKE, 64, 64, 1, 8, FAKE, 16, 64, None, FAKE, 64, 0)
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 300, None, 0, None) == 6
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 1, 8, 300, FAKE, need - 1, None) == 6
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 64, 64, 2, 4, 300, None, 0, None) == 0   # nothing to prepare at 2:4
+    assert lib.nm_spmm_prepare(FAKE, FAKE, 8, 24, 1, 8, 300, None, 0, None) == 0    # general kernel: no scratch
+    args = (FAKE, FAKE, 64, 64, 1, 8, FAKE, 300, 64, None, FAKE, 64, 0)
     assert lib.nm_linear_forward_prepared(*args, None, 0, None) == 6
-    assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, None, 16, 64, None, FAKE, 64, 0, FAKE, need, None) == 1
-    assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, FAKE, 16, 32, None, FAKE, 64, 0, FAKE, need, None) == 2
+    assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, None, 300, 64, None, FAKE, 64, 0, FAKE, need, None) == 1
+    assert lib.nm_linear_forward_prepared(FAKE, FAKE, 64, 64, 1, 8, FAKE, 300, 32, None, FAKE, 64, 0, FAKE, need, None) == 2
 
 
 def test_pack_prepare_batched_argument_errors(lib):
@@ -377,8 +378,8 @@ def test_forward_batched_argument_errors(lib):
     assert run({}, dict(values=None)) == 1 and run({}, dict(X=None)) == 1 and run({}, dict(Y=None)) == 1
     assert run({}, dict(N=3, M=2)) == 3 and run({}, dict(K=66)) == 2 and run({}, dict(ldy=8)) == 2
     assert run({}, dict(out_dtype=2)) == 5 and run({}, dict(Y=FAKE + 2)) == 4
-    assert run({}, dict(N=1, M=8)) == 6  # a level that needs a prepared workspace
-    assert run({}, dict(N=1, M=8, workspace=FAKE, workspace_bytes=16)) == 6
+    assert run({}, dict(N=1, M=8, T=300)) == 6  # a level that needs a prepared workspace at this token count
+    assert run({}, dict(N=1, M=8, T=300, workspace=FAKE, workspace_bytes=16)) == 6
 
 
 def test_static_scratch_entry_argument_errors(lib):
