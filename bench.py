@@ -563,11 +563,23 @@ def main():
 
         q_ms = timed(int8_products)
         q_useful = sum(layers[j].useful_flops for j in train_layers)
+        # floors of the four products: int8 X once, the compressed int8 weight (values + positions) once, bf16 Y
+        # once; matrix instructions at the int8 dense rate, twice that on the 2:4 form
+        q_bytes = q_math_ms = 0.0
+        for j in train_layers:
+            L = layers[j]
+            fields = L.K // L.M * L.N
+            q_bytes += L.T * L.K + L.O * (fields + (fields * INDEX_BITS[L.M] + 31) // 32 * 4) + 2.0 * L.T * L.O
+            q_math_ms += L.dense_flops * (0.5 if L.N <= 2 and L.N < L.M else 1.0) / (PEAK_INT8_DENSE_TOPS * 1e12) * 1e3
+        q_hbm_ms = q_bytes / (PEAK_HBM_GBS * 1e9) * 1e3
+        q_mfma = mfma_roofline(q_useful, q_ms, peak=PEAK_INT8_DENSE_TOPS, unit="TOP/s", floor_ms=q_math_ms)
+        q_hbm = hbm_roofline(q_bytes, q_ms, floor_ms=q_hbm_ms)
         out["int8_products"] = {
             "workload": "one DeiT-B block at batch 256 (qkv, proj, fc1, fc2 at their seed-0 levels), int8 operands, "
-                        "int32 sums rescaled to bf16; useful operations 2*T*O*K*N/M",
-            "ms": q_ms, "dense_equivalent_tops": block_flops / q_ms / 1e9,
-            "roofline": mfma_roofline(q_useful, q_ms, peak=PEAK_INT8_DENSE_TOPS, unit="TOP/s")}
+                        "int32 sums rescaled to bf16; useful operations 2*T*O*K*N/M; bound = the later floor",
+            "ms": q_ms, "dense_equivalent_tops": block_flops / q_ms / 1e9, "algorithmic_bytes": q_bytes,
+            "roofline": q_hbm if q_hbm_ms >= q_math_ms else q_mfma,
+            "other_roof": q_mfma if q_hbm_ms >= q_math_ms else q_hbm}
         del q_masks, q_w, q_x, q_scale, q_ws
 
         # ---- context, not part of the path: the vendor library's dense bf16 product (torch.matmul) on the same four
