@@ -77,3 +77,43 @@ def test_a_recorded_step_replays_like_the_eager_calls():
         assert np.array_equal(host_bits(packed_g[n][0]), vals) and np.array_equal(host_words(packed_g[n][1]), idx)
         Yref, B = orc.nm_linear(X_host[n], W_host[n], mask)
         check_output(host_output(Yg[n]), Yref, B, K // M * N, dt == torch.float32, f"layer {n}")
+
+
+def test_the_entry_point_on_the_fixed_scratch_replays_like_its_eager_calls():
+    # the calls that cannot allocate are the ones a caller records: three layers in a row on the library's scratch
+    rng = np.random.default_rng(31000)
+    lib = nm.load_library()
+    # (T, K, O, N, M): a re-coded level on the tiled kernel, a dense-form level, a 2:4 layer
+    shapes = [(197, 768, 384, 1, 8), (300, 256, 512, 4, 8), (64, 128, 96, 2, 4)]
+    layers = []
+    for (T, K, O, N, M) in shapes:
+        X = dev_bf16(wl.draw_activations(rng, T, K))
+        v, i = nm.nm_pack(dev_bf16(wl.draw_weights(rng, O, K)), N, M)
+        bias = torch.from_numpy(rng.standard_normal(O).astype(np.float32)).cuda()
+        eager = nm.nm_linear_forward(v, i, K, N, M, X, bias=bias, out_dtype=torch.bfloat16)
+        out = torch.zeros((T, O), dtype=torch.bfloat16, device="cuda")
+        layers.append((T, K, O, N, M, X, v, i, bias, eager, out))
+
+    def static_calls(stream):
+        for (T, K, O, N, M, X, v, i, bias, _, out) in layers:
+            st = lib.nm_linear_forward_static(v.data_ptr(), i.data_ptr(), O, K, N, M, X.data_ptr(), T, X.stride(0),
+                                              bias.data_ptr(), out.data_ptr(), out.stride(0), 1, stream)
+            assert st == 0, nm.nm_status_string(st)
+
+    # first use outside the capture: kernel attributes and the scratch address are set up once per device
+    static_calls(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        static_calls(torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        for layer in layers:
+            layer[-1].fill_(3.0)          # eager work between the replays; the replay must overwrite it
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (T, K, O, N, M, X, v, i, bias, eager, out) in layers:
+            assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), (rep, T, K, O, N, M)
+        # an eager call of the same entry point between replays (it shares the scratch)
+        static_calls(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
