@@ -210,6 +210,11 @@ int32_t nm_pack_ranked_batched(const nm_pack_ranked_desc* descs, int32_t count, 
  *   workspace        scratch of at least nm_spmm_workspace_bytes(O,K,N,M,T) bytes, 256-byte
  *                    aligned; may be NULL when that size is 0.  Its contents are undefined
  *                    after the call; concurrent calls need distinct workspaces.
+ *                    A layer with few output tiles and a long reduction (one image through a wide layer: T = 197,
+ *                    K = 3072) is cut into 2 .. 8 ranges along K; their fp32 partial sums live behind the
+ *                    operand-order copy in the workspace (nm_spmm_workspace_bytes counts them) and a second launch
+ *                    adds them in range order.  A workspace that holds the operand-order copy only gives the uncut
+ *                    product (same result up to rounding order).
  *                    Without a workspace (NULL, or too small), a product of T <= 208 tokens at a level of
  *                    {1:4, 1:8, 2:8, 4:8, 1:16, 2:16, 4:16} with K % 64 == 0 and O % 4 == 0 still runs: a
  *                    kernel reads the packed format itself (Fig. 2: values + positions, decoded on the fly;
@@ -279,7 +284,9 @@ int32_t nm_linear_forward_prepared(const nm_bf16* values, const uint32_t* indice
  * product kernel, whose blocks walk the tiles of all of them as one list.  For the independent products of a
  * stack of layers (each with its own input; Section 3: one level per layer) this removes the partial last round
  * of tiles every single launch ends with.  Small layers (a few tokens: batch-1 inference) likewise share launches
- * of the tiled kernel, which no one of them could fill.  Results are bit-identical to the single calls.
+ * of the tiled kernel, which no one of them could fill.  Results are bit-identical to the single calls, with one
+ * exception: a layer whose reduction a single call cuts into ranges (few tiles, long K; see nm_spmm) is not cut
+ * inside a call that fills the chip anyway, and its sums then differ in rounding order.
  *   descs  HOST array of `count` descriptors, read before the call returns.  Fields as the arguments of
  *          nm_linear_forward_prepared; the outputs must not overlap each other or any input.
  * Errors as for nm_linear_forward_prepared (the first offending descriptor decides); nothing is launched on an

@@ -320,7 +320,7 @@ int32_t nm_linear_forward_static(const nm_bf16* values, const uint32_t* indices,
   nm::SpmmArgs a;
   if (int32_t st = spmm_check(values, indices, O, K, N, M, X, T, ldx, bias, Y, ldy, out_dtype, nullptr, 0, true, &a))
     return st;
-  if (nm::spmm_workspace_bytes(O, K, N, M, T) > kStaticScratchBytes) return NM_ERR_WORKSPACE;
+  if (nm::spmm_operand_workspace_bytes(O, K, N, M, T) > kStaticScratchBytes) return NM_ERR_WORKSPACE;
   unsigned char* ws = nullptr;
   if (int32_t st = device_status(static_scratch(&ws))) return st;
   a.workspace = ws;

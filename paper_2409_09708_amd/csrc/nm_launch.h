@@ -116,6 +116,7 @@ struct SpmmArgs {
   size_t workspace_bytes;
 };
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);
+size_t spmm_operand_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T);  // the part that is required
 bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* sparse_form);
 // phases: SPMM_PREPARE rewrites the packed weight into matrix-core operand order in the workspace,
 // SPMM_PRODUCT multiplies (expects a prepared workspace); both = the whole call.

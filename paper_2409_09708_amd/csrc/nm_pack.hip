@@ -594,7 +594,7 @@ hipError_t launch_pack_prepare_batched(const LayerDesc* descs, int count, hipStr
   *workspace_short = false;
   for (int i = 0; i < count; ++i) {
     const LayerDesc& d = descs[i];
-    const size_t need = spmm_workspace_bytes(d.O, d.K, d.N, d.M, d.T);
+    const size_t need = spmm_operand_workspace_bytes(d.O, d.K, d.N, d.M, d.T);
     if (need && (d.workspace == nullptr || d.workspace_bytes < need || ((uintptr_t)d.workspace & 255u))) {
       *workspace_short = true;
       return hipSuccess;

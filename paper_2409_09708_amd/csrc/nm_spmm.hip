@@ -160,11 +160,13 @@ struct GemmArgs {
   const bf16_t* X;
   const float* bias;
   void* Y;
+  float* partial;       // splits > 1: fp32 partial sums [splits][T][O] (rows of O floats), added up by the reduce kernel
   int64_t O, K, T, ldx, ldy;
   int n_o_tiles, n_t_tiles;
-  int out_bf16;
-  int vec_store;    // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
-  int stream_form;  // A (and sel) lie in stream order (the pre-pass's output), else row-major as packed
+  uint8_t out_bf16;
+  uint8_t vec_store;    // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
+  uint8_t stream_form;  // A (and sel) lie in stream order (the pre-pass's output), else row-major as packed
+  uint8_t splits;       // ranges the reduction is cut into (tiled kernel only; 1 = the whole K in one block)
 };
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES_>
@@ -226,10 +228,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
 
   // XCD-aware tile order: consecutive block ids land on different XCDs (8 of them, each with its
   // own L2); give every XCD a contiguous range of tiles so that the blocks sharing an L2 share X rows.
-  const int n_tiles = a.n_o_tiles * a.n_t_tiles;
-  const int per_xcd = (n_tiles + 7) >> 3;
-  const int tile = (int)(block & 7) * per_xcd + (int)(block >> 3);
-  if (tile >= n_tiles) return;
+  // A layer with few tiles and a long reduction is cut along K as well: unit = (tile, K range); every range of a
+  // tile writes fp32 partial sums of its own, which splitk_reduce_kernel adds in range order.
+  const int n_splits = a.splits > 1 ? a.splits : 1;
+  const int n_units = a.n_o_tiles * a.n_t_tiles * n_splits;
+  const int per_xcd = (n_units + 7) >> 3;
+  const int unit = (int)(block & 7) * per_xcd + (int)(block >> 3);
+  if (unit >= n_units) return;
+  const int tile = unit / n_splits, split = unit - tile * n_splits;
   const int o_tile = tile % a.n_o_tiles;
   const int t_tile = tile / a.n_o_tiles;
   const int64_t o0 = (int64_t)o_tile * C::BO;
@@ -257,7 +263,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
     x_voff[i] = (uint32_t)((row * a.ldx + c * 8) * 2);
     x_dst[i] = (uint32_t)(j * 1024);
   }
-  const int nk = (int)(a.K / C::KC);
+  const int nk_all = (int)(a.K / C::KC);               // K steps of the layer
+  const int per_split = (nk_all + n_splits - 1) / n_splits;
+  const int ks0 = split * per_split;                    // this block's steps: ks0 .. ks0 + nk - 1
+  const int nk = nk_all - ks0 < per_split ? nk_all - ks0 : per_split;
 #pragma unroll
   for (int i = 0; i < C::A_PW; ++i) {
     const int j = (wave + i * C::NW) % C::A_LOADS;
@@ -266,7 +275,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
       // first (h = 0) or second (h = 1) 32-wide step (dense form, two stream steps per stage)
       constexpr int GROUPS = C::BO / 16;
       const int rg = j % GROUPS, h = j / GROUPS;
-      a_voff[i] = (uint32_t)((((o0 >> 4) + rg) * (int64_t)(SPARSE ? nk : 2 * nk) + h) << 10) + (uint32_t)(lane * 16);
+      a_voff[i] = (uint32_t)((((o0 >> 4) + rg) * (int64_t)(SPARSE ? nk_all : 2 * nk_all) + h) << 10) + (uint32_t)(lane * 16);
       a_dst[i] = (uint32_t)(C::X_BYTES + h * (C::BO * 64) + rg * 1024);
     } else {
       int64_t row;
@@ -284,7 +293,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
       const int j = (wave + i * C::NW) % C::S_LOADS;
       if constexpr (STREAM) {
         // the tile's share of the (256-row tile, step) selector block: 256 bytes per 32-row pair
-        s_voff[i] = (uint32_t)(((o0 >> 8) * (int64_t)nk << 11) + (((o0 & 255) >> 5) + j) * 256 + lane * 4);
+        s_voff[i] = (uint32_t)(((o0 >> 8) * (int64_t)nk_all << 11) + (((o0 & 255) >> 5) + j) * 256 + lane * 4);
       } else {
         int64_t row = 32 * j + (lane >> 1);
         if (row > o_last) row = o_last;
@@ -293,12 +302,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
       s_dst[i] = (uint32_t)(C::X_BYTES + C::A_BYTES + j * 256);
     }
   }
-  const bf16_t* x_base = a.X + t0 * a.ldx;
-  const bf16_t* a_base = STREAM ? a.A : a.A + o0 * a_ld;
-  const uint32_t* s_base = SPARSE ? (STREAM ? a.sel : a.sel + o0 * (a.K >> 5)) : nullptr;
   // elements the weight and selector pointers advance per stage
   constexpr int A_STEP = STREAM ? (SPARSE ? 512 : 1024) : (SPARSE ? 32 : 64);
   constexpr int S_STEP = STREAM ? 512 : 2;
+  const bf16_t* x_base = a.X + t0 * a.ldx + (int64_t)ks0 * 64;
+  const bf16_t* a_base = (STREAM ? a.A : a.A + o0 * a_ld) + (int64_t)ks0 * A_STEP;
+  const uint32_t* s_base = SPARSE ? (STREAM ? a.sel : a.sel + o0 * (a.K >> 5)) + (int64_t)ks0 * S_STEP : nullptr;
+  // where the block's sums go: the output, or its range's partial sums (plain fp32 rows of O, no bias yet)
+  void* out_ptr = a.Y;
+  int64_t out_ld = a.ldy;
+  bool out_bf16 = a.out_bf16 != 0, out_vec = a.vec_store != 0;
+  const float* bias = a.bias;
+  if (a.splits > 1) {
+    out_ptr = a.partial + (int64_t)split * a.T * a.O;
+    out_ld = a.O;
+    out_bf16 = false;
+    out_vec = (a.O & 3) == 0;
+    bias = nullptr;
+  }
 
   // The stage to be loaded next, as three running uniform pointers (X rows at the stage's k, weight, selectors),
   // advanced by constants: the step loop then holds no address products.
@@ -329,7 +350,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
   f32x4_t acc[OT][TT];
 #pragma unroll
   for (int i = 0; i < OT; ++i) {
-    const f32x4_t b = bias_init(a.bias, o0 + (wo * OT + i) * 16 + kb * 4, a.O, a.vec_store);
+    const f32x4_t b = bias_init(bias, o0 + (wo * OT + i) * 16 + kb * 4, a.O, a.vec_store);
 #pragma unroll
     for (int j = 0; j < TT; ++j) acc[i][j] = b;
   }
@@ -466,13 +487,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
   auto get = [&](int i, int j) { return __builtin_bit_cast(u32x4_t, acc[i][j]); };
   const int64_t row0 = t0 + wt * TT * 16, col0 = o0 + wo * OT * 16;
   static_assert(C::NW * wave_tile_slice_bytes<OT, 4>() <= C::LDS_BYTES, "write-out slices");
-  if (a.vec_store) {
-    if (a.out_bf16)
-      write_wave_tile_pieces<OT, TT, 2>(smem + wave * wave_tile_slice_bytes<OT, 2>(), lane, get, a.Y, a.ldy, row0, col0, a.T, a.O);
+  if (out_vec) {
+    if (out_bf16)
+      write_wave_tile_pieces<OT, TT, 2>(smem + wave * wave_tile_slice_bytes<OT, 2>(), lane, get, out_ptr, out_ld, row0, col0, a.T, a.O);
     else
-      write_wave_tile_pieces<OT, TT, 4>(smem + wave * wave_tile_slice_bytes<OT, 4>(), lane, get, a.Y, a.ldy, row0, col0, a.T, a.O);
+      write_wave_tile_pieces<OT, TT, 4>(smem + wave * wave_tile_slice_bytes<OT, 4>(), lane, get, out_ptr, out_ld, row0, col0, a.T, a.O);
   } else {
-    write_wave_tile_elements<OT, TT>(lane, get, a.Y, a.ldy, row0, col0, a.T, a.O, a.out_bf16 != 0);
+    write_wave_tile_elements<OT, TT>(lane, get, out_ptr, out_ld, row0, col0, a.T, a.O, out_bf16);
   }
 }
 
@@ -510,6 +531,69 @@ nm_gemm_group_kernel(const GemmGroup g) {
   const unsigned first = lo ? g.block_end[lo - 1] : 0u;
   if (g.layer[lo].stream_form) gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, true>(g.layer[lo], blockIdx.x - first, smem);
   else gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, false>(g.layer[lo], blockIdx.x - first, smem);
+}
+
+// The partial sums of layers whose reduction was cut into ranges, added up in range order (so the result does not
+// depend on which block finished first), plus the bias, rounded to the output type.  One launch serves every such
+// layer of a call; a thread owns four consecutive out-features of one token.
+constexpr int kSplitLayersMax = 60;
+struct SplitLayer {
+  const float* partial;  // [splits][T][O]
+  const float* bias;     // nullable
+  void* Y;
+  int64_t ldy;
+  int32_t T, O, splits, out_bf16;
+  uint32_t block_end;    // exclusive prefix end, in blocks of 256 threads
+  int32_t vec;           // Y rows in whole aligned pieces of four outputs
+};
+struct SplitGroup {
+  int32_t count;
+  SplitLayer layer[kSplitLayersMax];
+};
+static_assert(sizeof(SplitGroup) <= 4096, "the table must fit the kernel argument segment");
+
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const SplitGroup g) {
+  int l = 0;
+#pragma unroll 4
+  for (int i = 0; i + 1 < g.count; ++i) l += blockIdx.x >= g.layer[i].block_end ? 1 : 0;
+  const SplitLayer& L = g.layer[l];
+  const unsigned first = l ? g.layer[l - 1].block_end : 0u;
+  const int quads = (L.O + 3) >> 2;
+  const int64_t q = (int64_t)(blockIdx.x - first) * 256 + threadIdx.x;
+  if (q >= (int64_t)L.T * quads) return;
+  const int64_t t = q / quads;
+  const int o = (int)(q - t * quads) * 4;
+  const int64_t plane = (int64_t)L.T * L.O;
+  const float* src = L.partial + t * L.O + o;
+  float y[4] = {0.f, 0.f, 0.f, 0.f};
+  const int n = L.O - o < 4 ? L.O - o : 4;
+  if ((L.O & 3) == 0) {
+    for (int sp = 0; sp < L.splits; ++sp) {
+      const float4 v = *reinterpret_cast<const float4*>(src + sp * plane);
+      y[0] += v.x; y[1] += v.y; y[2] += v.z; y[3] += v.w;
+    }
+  } else {
+    for (int sp = 0; sp < L.splits; ++sp)
+      for (int e = 0; e < n; ++e) y[e] += src[sp * plane + e];
+  }
+  if (L.bias != nullptr)
+    for (int e = 0; e < n; ++e) y[e] += L.bias[o + e];
+  if (L.out_bf16) {
+    bf16_t* dst = reinterpret_cast<bf16_t*>(L.Y) + t * L.ldy + o;
+    if (L.vec) {
+      uint2 pk;
+      pk.x = pack_bf16x2(y[0], y[1]);
+      pk.y = pack_bf16x2(y[2], y[3]);
+      *reinterpret_cast<uint2*>(dst) = pk;
+    } else {
+      for (int e = 0; e < n; ++e) dst[e] = (bf16_t)f32_to_bf16_rne(y[e]);
+    }
+  } else {
+    float* dst = reinterpret_cast<float*>(L.Y) + t * L.ldy + o;
+    if (L.vec) *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+    else
+      for (int e = 0; e < n; ++e) dst[e] = y[e];
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1176,11 +1260,66 @@ bool spmm_stream_order(int64_t O, int64_t K, int64_t T, int N, int M, bool* spar
   return operand_form(O, K, T, N, M, sparse_form) == FORM_STREAM;
 }
 
+// Ranges the reduction of a layer on the tiled kernel is cut into: a layer with far fewer tiles than the chip has
+// compute units and a long K (one image through a wide MLP: 197 tokens, K = 3072) leaves most units idle for many
+// steps; cut into ranges of at least 12 steps, it fills them, at the price of fp32 partial sums through memory and
+// a reduce launch (about 5 us: below 64 steps the cut gains nothing; measured on ViT-S .. ViT-H shaped layers).
+// A function of the shape alone.
+static int split_count(int64_t O, int64_t K, int64_t T, bool sparse_form) {
+  if (K % 64) return 1;
+  const int pick = pick_tile(O, K, T, sparse_form);
+  if (pick == 0) return 1;
+  const int64_t side = pick == 2 ? 128 : 64;
+  const int64_t tiles = ((O + side - 1) / side) * ((T + side - 1) / side);
+  const int64_t steps = K / 64;
+  if (tiles >= 128 || steps < 64) return 1;
+  int64_t n = 256 / tiles;
+  if (n > steps / 12) n = steps / 12;
+  if (n > 8) n = 8;
+  while (n > 1 && (n - 1) * ((steps + n - 1) / n) >= steps) --n;  // no empty range
+  return n < 2 ? 1 : (int)n;
+}
+static size_t operand_bytes(int64_t O, int64_t K, int N, int M, int64_t T, bool* sparse_form) {
+  if (operand_form(O, K, T, N, M, sparse_form) != FORM_STREAM) return 0;
+  const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // whole 256-row tiles
+  return *sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
+}
+
+// The part of the workspace a product cannot do without: the operand-order copy.  With no more than that the
+// reduction stays in one piece.
+size_t spmm_operand_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
+  bool sparse_form = false;
+  return operand_bytes(O, K, N, M, T, &sparse_form);
+}
+
+// Workspace of a product: the operand-order copy (if the level needs one), then the partial sums of a cut reduction.
 size_t spmm_workspace_bytes(int64_t O, int64_t K, int N, int M, int64_t T) {
   bool sparse_form = false;
-  if (operand_form(O, K, T, N, M, &sparse_form) != FORM_STREAM) return 0;
-  const size_t o_pad = (size_t)((O + 255) / 256) * 256;  // whole 256-row tiles
-  return sparse_form ? o_pad * (size_t)K + o_pad * (size_t)K / 8 : o_pad * (size_t)K * 2;
+  const size_t operand = operand_bytes(O, K, N, M, T, &sparse_form);
+  const int splits = split_count(O, K, T, sparse_form);
+  if (splits < 2) return operand;
+  return ((operand + 255) / 256) * 256 + (size_t)splits * (size_t)T * (size_t)O * 4;
+}
+
+// The reduce launch of layers whose reduction was cut: split_group_append lists a layer (false: table full),
+// launch_split_reduce adds their partial sums up.
+static bool split_group_append(SplitGroup& sg, const GemmArgs& g) {
+  if (sg.count >= kSplitLayersMax) return false;
+  const int64_t quads = g.T * ((g.O + 3) / 4);
+  const int64_t first = sg.count ? sg.layer[sg.count - 1].block_end : 0;
+  if (first + (quads + 255) / 256 > 0x7FFFFFF0) return false;
+  SplitLayer& L = sg.layer[sg.count++];
+  L.partial = g.partial; L.bias = g.bias; L.Y = g.Y; L.ldy = g.ldy;
+  L.T = (int32_t)g.T; L.O = (int32_t)g.O; L.splits = g.splits; L.out_bf16 = g.out_bf16;
+  L.block_end = (uint32_t)(first + (quads + 255) / 256);
+  L.vec = (g.O % 4 == 0) && (g.ldy % 4 == 0) && aligned_to(g.Y, g.out_bf16 ? 8 : 16);
+  return true;
+}
+static hipError_t launch_split_reduce(SplitGroup& sg, hipStream_t s) {
+  if (sg.count == 0) return hipSuccess;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(sg.layer[sg.count - 1].block_end), dim3(256), 0, s, sg);
+  sg.count = 0;
+  return hipGetLastError();
 }
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
@@ -1191,11 +1330,18 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
   if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
   g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
   g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
-  const int64_t n_tiles = (int64_t)g.n_o_tiles * g.n_t_tiles;
-  const int64_t grid = ((n_tiles + 7) / 8) * 8;
+  const int64_t n_units = (int64_t)g.n_o_tiles * g.n_t_tiles * (g.splits > 1 ? g.splits : 1);
+  const int64_t grid = ((n_units + 7) / 8) * 8;
   if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s, g);
-  return hipGetLastError();
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  if (g.splits > 1) {
+    SplitGroup sg;
+    sg.count = 0;
+    split_group_append(sg, g);
+    return launch_split_reduce(sg, s);
+  }
+  return hipSuccess;
 }
 
 // Tiled kernel, many layers in one launch.  tile_group_append fills the table (false: full, launch it and retry;
@@ -1205,7 +1351,7 @@ static bool tile_group_append(GemmGroup& grp, GemmArgs g) {
   using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
   g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
   g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
-  const int64_t blocks = (((int64_t)g.n_o_tiles * g.n_t_tiles + 7) / 8) * 8;
+  const int64_t blocks = (((int64_t)g.n_o_tiles * g.n_t_tiles * (g.splits > 1 ? g.splits : 1) + 7) / 8) * 8;
   const int64_t first = grp.count ? grp.block_end[grp.count - 1] : 0;
   if (grp.count >= kTileLayersMax || first + blocks > 0x7FFFFFF0) return false;
   grp.block_end[grp.count] = (uint32_t)(first + blocks);
@@ -1229,7 +1375,8 @@ static hipError_t launch_gemm_group(GemmGroup& grp, hipStream_t s) {
   }
   uint32_t end = 0;
   for (int i = 0; i < grp.count; ++i) {
-    end += (uint32_t)((((int64_t)grp.layer[i].n_o_tiles * grp.layer[i].n_t_tiles + 7) / 8) * 8);
+    const GemmArgs& L = grp.layer[i];
+    end += (uint32_t)((((int64_t)L.n_o_tiles * L.n_t_tiles * (L.splits > 1 ? L.splits : 1) + 7) / 8) * 8);
     grp.block_end[i] = end;
   }
   hipLaunchKernelGGL(kern, dim3(end), dim3(C::NT), C::LDS_BYTES, s, grp);
@@ -1351,7 +1498,7 @@ hipError_t launch_dense_transposed(const bf16_t* Ws, int64_t R, int64_t I, int64
   g.X = Q; g.bias = nullptr; g.Y = Out;
   g.O = I; g.K = R; g.T = T; g.ldx = ldq; g.ldy = ldo;
   g.n_o_tiles = g.n_t_tiles = 0;
-  g.out_bf16 = out_bf16; g.vec_store = 1; g.stream_form = 1;
+  g.out_bf16 = (uint8_t)out_bf16; g.vec_store = 1; g.stream_form = 1; g.splits = 1; g.partial = nullptr;
   *taken = true;
   return dispatch_gemm<false>(g, 0, s);
 }
@@ -1393,6 +1540,19 @@ static void fill_gemm_args(const SpmmArgs& a, int form, bool sparse_form, GemmAr
   g->vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
                  (a.bias == nullptr || aligned_to(a.bias, 16));
   g->stream_form = form == FORM_STREAM;
+  {
+    bool sf = false;
+    const size_t operand = operand_bytes(a.O, a.K, a.N, a.M, a.T, &sf);
+    int splits = split_count(a.O, a.K, a.T, sparse_form);
+    // the partial sums need the full workspace; a caller that brings the operand part only gets the uncut product
+    if (splits > 1 && (a.workspace == nullptr || !aligned_to(a.workspace, 256) ||
+                       a.workspace_bytes < ((operand + 255) / 256) * 256 + (size_t)splits * (size_t)a.T * (size_t)a.O * 4))
+      splits = 1;
+    g->splits = (uint8_t)splits;
+    g->partial = splits > 1 ? reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(a.workspace) +
+                                                       ((operand + 255) / 256) * 256)
+                            : nullptr;
+  }
   if (form == FORM_STREAM) {
     const int64_t o_pad = ((a.O + 255) / 256) * 256;
     unsigned char* ws = reinterpret_cast<unsigned char*>(a.workspace);
@@ -1408,7 +1568,7 @@ static void fill_gemm_args(const SpmmArgs& a, int form, bool sparse_form, GemmAr
 // from the packed format instead.
 static bool packed_path(const SpmmArgs& a) {
   if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;
-  const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
+  const size_t need = spmm_operand_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (!need || (a.workspace != nullptr && a.workspace_bytes >= need && aligned_to(a.workspace, 256))) return false;
   return fewtok_takes(a);
 }
@@ -1422,7 +1582,7 @@ hipError_t launch_spmm(const SpmmArgs& a, hipStream_t s, bool* workspace_short, 
   }
   bool sparse_form = false;
   const int form = operand_form(a.O, a.K, a.T, a.N, a.M, &sparse_form);
-  const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
+  const size_t need = spmm_operand_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   if (need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256))) {
     // no workspace: few tokens can still be multiplied straight from the packed format
     if (!packed_path(a)) *workspace_short = true;
@@ -1476,7 +1636,7 @@ static bool stream_entry(const SpmmArgs& a, GemmArgs* g, bool* sparse_form) {
 bool spmm_workspace_short(const SpmmArgs& a) {
   if (packed_path(a)) return false;
   if (!tiles_ok(a.K, a.X, a.ldx, a.values, a.indices, a.O, a.T)) return false;  // the gather kernel needs none
-  const size_t need = spmm_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
+  const size_t need = spmm_operand_workspace_bytes(a.O, a.K, a.N, a.M, a.T);
   return need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256));
 }
 
@@ -1499,6 +1659,8 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
     grp.count = 0; grp.n_tiles = 0;
     return r;
   };
+  SplitGroup split_grp;
+  split_grp.count = 0;
   GemmGroup tile_grp[4];  // 2:4 form with 128 x 128 and 64 x 64 tiles, dense form likewise
   for (GemmGroup& t : tile_grp) t.count = 0;
   auto tile_append = [&](int which, const GemmArgs& g) {
@@ -1560,12 +1722,24 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
     } else if (int pick = 0; tiled_entry(layers[i], &g, &sparse_form, &pick)) {
       // small layers: the tiled kernel, all layers of one operand form and tile size in one launch
       const int which = (sparse_form ? 0 : 2) + ((pick == 2 || promote) ? 0 : 1);
-      if (!tile_append(which, g)) {
+      // a call that fills the chip with whole tiles has no use for cut reductions (their partial sums would only
+      // add traffic and a launch): such a call's sums differ from the single calls' in rounding order only
+      if (promote) { g.splits = 1; g.partial = nullptr; }
+      bool listed = tile_append(which, g);
+      if (!listed) {
         if ((e = tile_flush(which)) != hipSuccess) return e;
-        if (!tile_append(which, g)) {  // more blocks than a grid holds: alone
+        listed = tile_append(which, g);
+        if (!listed) {  // more blocks than a grid holds: alone
           bool short_ws = false;
           if ((e = launch_spmm(layers[i], s, &short_ws, SPMM_PRODUCT)) != hipSuccess) return e;
         }
+      }
+      // a layer whose reduction is cut into ranges: its partial sums are added up after the tile launches
+      if (listed && g.splits > 1 && !split_group_append(split_grp, g)) {
+        for (int w = 0; w < 4; ++w)
+          if ((e = tile_flush(w)) != hipSuccess) return e;
+        if ((e = launch_split_reduce(split_grp, s)) != hipSuccess) return e;
+        split_group_append(split_grp, g);  // its tiles have just run; the table is empty again
       }
     } else {
       bool short_ws = false;
@@ -1576,7 +1750,7 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
   if ((e = flush(dense_grp, false)) != hipSuccess) return e;
   for (int which = 0; which < 4; ++which)
     if ((e = tile_flush(which)) != hipSuccess) return e;
-  return hipSuccess;
+  return launch_split_reduce(split_grp, s);
 }
 
 }  // namespace nm

@@ -359,6 +359,13 @@ def test_batched_call_groups_small_products_into_shared_launches():
     nm.nm_linear_forward_prepared_batched(entries)
     torch.cuda.synchronize()
     for n, (e, ref) in enumerate(zip(entries, singles)):
+        if n < len(specs) and specs[n][1] >= 1024 and specs[n][0] <= 208:
+            # few tiles and a long K: alone the reduction is cut into ranges, inside this call (which fills the
+            # chip) it is not; same sums in another order
+            tol = 2.0 ** -7 if e[-1].dtype == torch.bfloat16 else 2.0 ** -18
+            scale = ref.float().abs().max().item()
+            assert (e[-1].float() - ref.float()).abs().max().item() <= tol * scale, (n, specs[n])
+            continue
         assert torch.equal(e[-1], ref), (n, specs[n] if n < len(specs) else "view")
     assert int(wide[:, 0].count_nonzero()) == 0 and int(wide[:, O + 1:].count_nonzero()) == 0
     # a call with few small layers keeps their own (smaller) tiles: same bytes again
