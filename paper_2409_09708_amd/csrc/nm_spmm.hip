@@ -167,6 +167,7 @@ struct GemmArgs {
   uint8_t vec_store;    // Y rows split into whole aligned 16-byte pieces (ldy, O multiples of 8 (bf16) / 4 (fp32))
   uint8_t stream_form;  // A (and sel) lie in stream order (the pre-pass's output), else row-major as packed
   uint8_t splits;       // ranges the reduction is cut into (tiled kernel only; 1 = the whole K in one block)
+  uint8_t rot;          // tiled kernel: XCD x takes the layer's share number (x + rot) mod 8
 };
 
 template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES_>
@@ -233,7 +234,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, unsigned block, uns
   const int n_splits = a.splits > 1 ? a.splits : 1;
   const int n_units = a.n_o_tiles * a.n_t_tiles * n_splits;
   const int per_xcd = (n_units + 7) >> 3;
-  const int unit = (int)(block & 7) * per_xcd + (int)(block >> 3);
+  // (the shares at the end of the list may be short or empty; `rot` says which XCDs get those, so that the layers
+  // of a launch can leave them to different ones)
+  const int unit = (int)((block + a.rot) & 7) * per_xcd + (int)(block >> 3);
   if (unit >= n_units) return;
   const int tile = unit / n_splits, split = unit - tile * n_splits;
   const int o_tile = tile % a.n_o_tiles;
@@ -507,30 +510,59 @@ nm_gemm_kernel(const GemmArgs a) {
   else gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, false>(a, blockIdx.x, smem);
 }
 
-// The tiles of many small layers of one operand form in one launch: products of a few tokens are a handful of
-// tiles each, far fewer than the chip has compute units, and independent ones fill it together.  A block finds
-// its layer in the running block counts (whole multiples of 8 per layer) by bisection.
-constexpr int kTileLayersMax = 36;
-struct GemmGroup {
-  int32_t count;
-  uint32_t block_end[kTileLayersMax];  // exclusive prefix ends, in blocks
-  GemmArgs layer[kTileLayersMax];
+// The tiles of many small layers in one launch, whatever their operand form and weight order: products of a few
+// tokens are a handful of tiles each, far fewer than the chip has compute units, and independent ones fill it
+// together (two launches, one per form, would each end in a partly filled chip and run one after the other).
+// A block finds its layer in the running block counts (whole multiples of 8 per layer) by bisection and takes the
+// branch of that layer's form; the table entry is the layer's arguments packed to 80 bytes, so that the 48 linears
+// of a 12-block model fit one kernel argument segment.
+constexpr int kTileLayersMax = 50;
+struct TileLayer {
+  const bf16_t* A;
+  const uint32_t* sel;
+  const bf16_t* X;
+  const float* bias;
+  void* Y;
+  float* partial;
+  int64_t ldy;
+  uint32_t O, T;           // O <= 2^24, T < 2^31
+  uint32_t K : 23, rot : 3;  // K <= 2^22
+  uint32_t ldx : 23, out_bf16 : 1, vec_store : 1, stream_form : 1, sparse_form : 1, splits : 4;
+  uint32_t block_end;      // exclusive prefix end, in blocks
 };
-static_assert(sizeof(GemmGroup) <= 4096, "the table must fit the kernel argument segment");
+struct TileGroup {
+  int32_t count;
+  TileLayer layer[kTileLayersMax];
+};
+static_assert(sizeof(TileLayer) == 80 && sizeof(TileGroup) <= 4096, "the table must fit the kernel argument segment");
 
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
+// SS, SD: LDS stages of the 2:4-form and of the dense-form tiles (the launch's LDS is the larger of the two).
+template <int WO, int WT, int OT, int TT, int SS, int SD>
 __global__ void __launch_bounds__(WO * WT * 64)
-nm_gemm_group_kernel(const GemmGroup g) {
+nm_gemm_group_kernel(const TileGroup g) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   int lo = 0, hi = g.count - 1;  // the first layer whose end lies beyond this block
   while (lo < hi) {
     const int mid = (lo + hi) >> 1;
-    if (blockIdx.x >= g.block_end[mid]) lo = mid + 1;
+    if (blockIdx.x >= g.layer[mid].block_end) lo = mid + 1;
     else hi = mid;
   }
-  const unsigned first = lo ? g.block_end[lo - 1] : 0u;
-  if (g.layer[lo].stream_form) gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, true>(g.layer[lo], blockIdx.x - first, smem);
-  else gemm_tile<SPARSE, WO, WT, OT, TT, STAGES, false>(g.layer[lo], blockIdx.x - first, smem);
+  const TileLayer& L = g.layer[lo];
+  const unsigned block = blockIdx.x - (lo ? g.layer[lo - 1].block_end : 0u);
+  GemmArgs a;
+  a.A = L.A; a.sel = L.sel; a.X = L.X; a.bias = L.bias; a.Y = L.Y; a.partial = L.partial;
+  a.O = L.O; a.K = L.K; a.T = L.T; a.ldx = L.ldx; a.ldy = L.ldy;
+  a.n_o_tiles = (int)((L.O + WO * OT * 16 - 1) / (WO * OT * 16));
+  a.n_t_tiles = (int)((L.T + WT * TT * 16 - 1) / (WT * TT * 16));
+  a.out_bf16 = L.out_bf16; a.vec_store = L.vec_store; a.stream_form = L.stream_form; a.splits = L.splits;
+  a.rot = L.rot;
+  if (L.sparse_form) {
+    if (L.stream_form) gemm_tile<true, WO, WT, OT, TT, SS, true>(a, block, smem);
+    else gemm_tile<true, WO, WT, OT, TT, SS, false>(a, block, smem);
+  } else {
+    if (L.stream_form) gemm_tile<false, WO, WT, OT, TT, SD, true>(a, block, smem);
+    else gemm_tile<false, WO, WT, OT, TT, SD, false>(a, block, smem);
+  }
 }
 
 // The partial sums of layers whose reduction was cut into ranges, added up in range order (so the result does not
@@ -1346,40 +1378,83 @@ static hipError_t launch_gemm(GemmArgs g, hipStream_t s) {
 
 // Tiled kernel, many layers in one launch.  tile_group_append fills the table (false: full, launch it and retry;
 // a layer with more blocks than a grid holds never fits and is launched alone).
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
-static bool tile_group_append(GemmGroup& grp, GemmArgs g) {
-  using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
-  g.n_o_tiles = (int)((g.O + C::BO - 1) / C::BO);
-  g.n_t_tiles = (int)((g.T + C::BT - 1) / C::BT);
-  const int64_t blocks = (((int64_t)g.n_o_tiles * g.n_t_tiles * (g.splits > 1 ? g.splits : 1) + 7) / 8) * 8;
-  const int64_t first = grp.count ? grp.block_end[grp.count - 1] : 0;
-  if (grp.count >= kTileLayersMax || first + blocks > 0x7FFFFFF0) return false;
-  grp.block_end[grp.count] = (uint32_t)(first + blocks);
-  grp.layer[grp.count++] = g;
+template <int BO, int BT>
+static int64_t tile_layer_blocks(const TileLayer& L) {
+  const int64_t tiles = (int64_t)((L.O + BO - 1) / BO) * ((L.T + BT - 1) / BT);
+  return ((tiles * (L.splits > 1 ? L.splits : 1) + 7) / 8) * 8;
+}
+// estimated duration of one of the layer's blocks (the model of pick_tile): the order of the launch
+static double tile_layer_cost(const TileLayer& L) {
+  const int n = L.splits > 1 ? L.splits : 1;
+  return (double)((L.K / 64 + n - 1) / n) * (L.sparse_form ? 0.34 : 0.5);
+}
+
+template <int WO, int WT, int OT, int TT>
+static bool tile_group_append(TileGroup& grp, const GemmArgs& g, bool sparse_form) {
+  if (grp.count >= kTileLayersMax) return false;
+  TileLayer& L = grp.layer[grp.count];
+  L.A = g.A; L.sel = g.sel; L.X = g.X; L.bias = g.bias; L.Y = g.Y; L.partial = g.partial;
+  L.ldy = g.ldy;
+  L.O = (uint32_t)g.O; L.K = (uint32_t)g.K; L.T = (uint32_t)g.T;   // tiles_ok has bounded them
+  L.ldx = (uint32_t)g.ldx; L.out_bf16 = g.out_bf16; L.vec_store = g.vec_store; L.stream_form = g.stream_form;
+  L.sparse_form = sparse_form; L.splits = g.splits > 1 ? g.splits : 1;
+  L.block_end = 0; L.rot = 0;
+  int64_t total = tile_layer_blocks<WO * OT * 16, WT * TT * 16>(L);
+  for (int i = 0; i < grp.count; ++i) total += tile_layer_blocks<WO * OT * 16, WT * TT * 16>(grp.layer[i]);
+  if (total > 0x7FFFFFF0) return false;
+  ++grp.count;
   return true;
 }
 
-template <bool SPARSE, int WO, int WT, int OT, int TT, int STAGES>
-static hipError_t launch_gemm_group(GemmGroup& grp, hipStream_t s) {
-  using C = GemmCfg<SPARSE, WO, WT, OT, TT, STAGES>;
+template <int WO, int WT, int OT, int TT, int SS, int SD>
+static hipError_t launch_gemm_group(TileGroup& grp, hipStream_t s) {
+  using CS = GemmCfg<true, WO, WT, OT, TT, SS>;
+  using CD = GemmCfg<false, WO, WT, OT, TT, SD>;
+  constexpr int LDS = CS::LDS_BYTES > CD::LDS_BYTES ? CS::LDS_BYTES : CD::LDS_BYTES;
   if (grp.count == 0) return hipSuccess;
-  auto kern = nm_gemm_group_kernel<SPARSE, WO, WT, OT, TT, STAGES>;
+  auto kern = nm_gemm_group_kernel<WO, WT, OT, TT, SS, SD>;
   static PerDeviceOnce lds_limit;
-  if (hipError_t e = raise_dynamic_lds_limit(kern, C::LDS_BYTES, lds_limit); e != hipSuccess) return e;
-  // deepest layers first, so that the launch ends with the shortest tiles; the block counts move with them
+  if (hipError_t e = raise_dynamic_lds_limit(kern, LDS, lds_limit); e != hipSuccess) return e;
+  // longest blocks first (insertion sort, stable), so that the launch ends with the shortest ones
   for (int i = 1; i < grp.count; ++i) {
-    const GemmArgs L = grp.layer[i];
+    const TileLayer L = grp.layer[i];
+    const double cost = tile_layer_cost(L);
     int j = i;
-    for (; j > 0 && grp.layer[j - 1].K < L.K; --j) grp.layer[j] = grp.layer[j - 1];
+    for (; j > 0 && tile_layer_cost(grp.layer[j - 1]) < cost; --j) grp.layer[j] = grp.layer[j - 1];
     grp.layer[j] = L;
   }
+  // A layer's blocks are a whole multiple of 8, one share per XCD; the last shares are short or empty.  Each layer
+  // turns its shares against the XCDs so that the estimated work per XCD stays as even as the list allows.
   uint32_t end = 0;
+  double load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int i = 0; i < grp.count; ++i) {
-    const GemmArgs& L = grp.layer[i];
-    end += (uint32_t)((((int64_t)L.n_o_tiles * L.n_t_tiles * (L.splits > 1 ? L.splits : 1) + 7) / 8) * 8);
-    grp.block_end[i] = end;
+    TileLayer& L = grp.layer[i];
+    const int64_t blocks = tile_layer_blocks<CS::BO, CS::BT>(L);
+    const int64_t per_xcd = blocks / 8;
+    const int64_t units = (int64_t)((L.O + CS::BO - 1) / CS::BO) * ((L.T + CS::BT - 1) / CS::BT) * L.splits;
+    const double cost = tile_layer_cost(L) + 2.0;  // plus a block's start and write-out
+    double share[8];
+    for (int sl = 0; sl < 8; ++sl) {
+      int64_t u = units - sl * per_xcd;
+      u = u < 0 ? 0 : (u > per_xcd ? per_xcd : u);
+      share[sl] = cost * (double)u;
+    }
+    int best = 0;
+    double best_sq = 0;  // the turn that leaves the sum of squared loads smallest
+    for (int rot = 0; rot < 8; ++rot) {
+      double sq = 0;
+      for (int x = 0; x < 8; ++x) {
+        const double v = load[x] + share[(x + rot) & 7];
+        sq += v * v;
+      }
+      if (rot == 0 || sq < best_sq) { best = rot; best_sq = sq; }
+    }
+    for (int x = 0; x < 8; ++x) load[x] += share[(x + best) & 7];
+    L.rot = (uint32_t)best;
+    end += (uint32_t)blocks;
+    L.block_end = end;
   }
-  hipLaunchKernelGGL(kern, dim3(end), dim3(C::NT), C::LDS_BYTES, s, grp);
+  hipLaunchKernelGGL(kern, dim3(end), dim3(CS::NT), LDS, s, grp);
   grp.count = 0;
   return hipGetLastError();
 }
@@ -1535,6 +1610,7 @@ static void fill_gemm_args(const SpmmArgs& a, int form, bool sparse_form, GemmAr
   g->O = a.O; g->K = a.K; g->T = a.T; g->ldx = a.ldx; g->ldy = a.ldy;
   g->out_bf16 = a.out_bf16;
   g->n_o_tiles = g->n_t_tiles = 0;
+  g->rot = 0;
   // 16-byte pieces of Y rows: every row start and the row end fall on a piece boundary
   const int per_piece = a.out_bf16 ? 8 : 4;
   g->vec_store = (a.ldy % per_piece == 0) && aligned_to(a.Y, 16) && (a.O % per_piece == 0) &&
@@ -1640,6 +1716,7 @@ bool spmm_workspace_short(const SpmmArgs& a) {
   return need && (a.workspace == nullptr || a.workspace_bytes < need || !aligned_to(a.workspace, 256));
 }
 
+constexpr int kGroupDenseStages = 2;
 hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s) {
   StreamGroup sparse_grp, dense_grp;
   sparse_grp.count = dense_grp.count = 0;
@@ -1661,23 +1738,15 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
   };
   SplitGroup split_grp;
   split_grp.count = 0;
-  GemmGroup tile_grp[4];  // 2:4 form with 128 x 128 and 64 x 64 tiles, dense form likewise
-  for (GemmGroup& t : tile_grp) t.count = 0;
-  auto tile_append = [&](int which, const GemmArgs& g) {
-    switch (which) {
-      case 0: return tile_group_append<true, 2, 2, 4, 4, 3>(tile_grp[0], g);
-      case 1: return tile_group_append<true, 2, 2, 2, 2, 3>(tile_grp[1], g);
-      case 2: return tile_group_append<false, 2, 2, 4, 4, 3>(tile_grp[2], g);
-      default: return tile_group_append<false, 2, 2, 2, 2, 3>(tile_grp[3], g);
-    }
+  TileGroup tile_grp[2];  // 128 x 128 and 64 x 64 tiles, both operand forms in each
+  for (TileGroup& t : tile_grp) t.count = 0;
+  auto tile_append = [&](int which, const GemmArgs& g, bool sparse_form) {
+    return which == 0 ? tile_group_append<2, 2, 4, 4>(tile_grp[0], g, sparse_form)
+                      : tile_group_append<2, 2, 2, 2>(tile_grp[1], g, sparse_form);
   };
   auto tile_flush = [&](int which) {
-    switch (which) {
-      case 0: return launch_gemm_group<true, 2, 2, 4, 4, 3>(tile_grp[0], s);
-      case 1: return launch_gemm_group<true, 2, 2, 2, 2, 3>(tile_grp[1], s);
-      case 2: return launch_gemm_group<false, 2, 2, 4, 4, 3>(tile_grp[2], s);
-      default: return launch_gemm_group<false, 2, 2, 2, 2, 3>(tile_grp[3], s);
-    }
+    return which == 0 ? launch_gemm_group<2, 2, 4, 4, 3, kGroupDenseStages>(tile_grp[0], s)
+                      : launch_gemm_group<2, 2, 2, 2, 3, 3>(tile_grp[1], s);
   };
   // A layer alone takes 64 x 64 tiles when 128 x 128 ones would leave most compute units idle; the layers of a
   // call fill the chip together, so they take the larger tiles (half the operand traffic into the compute
@@ -1721,14 +1790,14 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
       }
     } else if (int pick = 0; tiled_entry(layers[i], &g, &sparse_form, &pick)) {
       // small layers: the tiled kernel, all layers of one operand form and tile size in one launch
-      const int which = (sparse_form ? 0 : 2) + ((pick == 2 || promote) ? 0 : 1);
+      const int which = (pick == 2 || promote) ? 0 : 1;
       // a call that fills the chip with whole tiles has no use for cut reductions (their partial sums would only
       // add traffic and a launch): such a call's sums differ from the single calls' in rounding order only
       if (promote) { g.splits = 1; g.partial = nullptr; }
-      bool listed = tile_append(which, g);
+      bool listed = tile_append(which, g, sparse_form);
       if (!listed) {
         if ((e = tile_flush(which)) != hipSuccess) return e;
-        listed = tile_append(which, g);
+        listed = tile_append(which, g, sparse_form);
         if (!listed) {  // more blocks than a grid holds: alone
           bool short_ws = false;
           if ((e = launch_spmm(layers[i], s, &short_ws, SPMM_PRODUCT)) != hipSuccess) return e;
@@ -1736,7 +1805,7 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
       }
       // a layer whose reduction is cut into ranges: its partial sums are added up after the tile launches
       if (listed && g.splits > 1 && !split_group_append(split_grp, g)) {
-        for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < 2; ++w)
           if ((e = tile_flush(w)) != hipSuccess) return e;
         if ((e = launch_split_reduce(split_grp, s)) != hipSuccess) return e;
         split_group_append(split_grp, g);  // its tiles have just run; the table is empty again
@@ -1748,7 +1817,7 @@ hipError_t launch_spmm_batched(const SpmmArgs* layers, int count, hipStream_t s)
   }
   if ((e = flush(sparse_grp, true)) != hipSuccess) return e;
   if ((e = flush(dense_grp, false)) != hipSuccess) return e;
-  for (int which = 0; which < 4; ++which)
+  for (int which = 0; which < 2; ++which)
     if ((e = tile_flush(which)) != hipSuccess) return e;
   return launch_split_reduce(split_grp, s);
 }
