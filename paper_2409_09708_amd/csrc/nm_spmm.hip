@@ -1531,7 +1531,12 @@ template <bool SPARSE>
 static hipError_t dispatch_gemm(const GemmArgs& g, int pick, hipStream_t s) {
   switch (pick) {
     case 0: return launch_stream<SPARSE>(g, s);
-    case 2: return launch_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
+    case 2:
+      // dense form with more tiles than compute units: two LDS stages instead of three, so that two blocks share
+      // a compute unit and one's loads and write-out run under the other's matrix instructions (0.6 - 0.9 of the
+      // three-stage time on such shapes; with a block per unit the deeper pipeline wins)
+      if (!SPARSE && ((g.O + 127) / 128) * ((g.T + 127) / 128) > 256) return launch_gemm<SPARSE, 2, 2, 4, 4, 2>(g, s);
+      return launch_gemm<SPARSE, 2, 2, 4, 4, 3>(g, s);
     default: return launch_gemm<SPARSE, 2, 2, 2, 2, 3>(g, s);
   }
 }
