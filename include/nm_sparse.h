@@ -245,8 +245,10 @@ int32_t nm_linear_forward(const nm_bf16* values, const uint32_t* indices, int64_
  * scratch is a fixed array of nm_static_scratch_bytes() bytes (8 MiB) inside the library's device image; every
  * device the library runs on holds its own copy until the process ends.  The call allocates and frees nothing.
  *   Arguments and results as nm_linear_forward (same kernels, same bytes written to Y).
- *   NM_ERR_WORKSPACE  the layer needs more scratch than the array holds
- *                     (nm_spmm_workspace_bytes(O, K, N, M, T) > nm_static_scratch_bytes()); nothing is launched.
+ *   NM_ERR_WORKSPACE  the layer's operand-order copy needs more scratch than the array holds; nothing is launched.
+ *                     (A layer whose cut reduction, see nm_spmm, does not fit beside that copy, i.e.
+ *                     nm_spmm_workspace_bytes(O, K, N, M, T) > nm_static_scratch_bytes(), is multiplied uncut: the
+ *                     result of nm_linear_forward up to rounding order.)
  * All calls on one device share that device's array: two such calls whose kernels may overlap (different streams,
  * or threads) race on it; calls on one stream are ordered and safe.  The array keeps the last call's contents;
  * every call rewrites the part it reads, so nothing needs clearing.
