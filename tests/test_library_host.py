@@ -66,6 +66,26 @@ def test_workspace_sizes(lib):
     assert lib.nm_spmm_workspace_bytes(768, 768, 8, 8, 50432) == 768 * 768 * 2
 
 
+def test_workspace_of_a_cut_reduction(lib):
+    # few tiles and a long reduction: the fp32 partial sums of 2 .. 8 ranges lie behind the (256-aligned) operand copy
+    T, K, O = 197, 4096, 1024
+    planes = lib.nm_spmm_workspace_bytes(O, K, 2, 4, T)              # 2:4 needs no operand copy
+    assert planes % (T * O * 4) == 0 and 2 <= planes // (T * O * 4) <= 8
+    operand = O * K + O * K // 8
+    with_copy = lib.nm_spmm_workspace_bytes(O, K, 1, 8, T)
+    assert with_copy == (operand + 255) // 256 * 256 + planes       # the same ranges whatever the level of the form
+    # a short reduction, or enough tiles to fill the chip, is never cut
+    assert lib.nm_spmm_workspace_bytes(O, 1024, 2, 4, T) == 0
+    assert lib.nm_spmm_workspace_bytes(O, K, 2, 4, 50432) == O * K + O * K // 8
+    # ranges never come out empty: every count of steps from 64 up gives whole planes
+    for steps in range(64, 100):
+        b = lib.nm_spmm_workspace_bytes(256, steps * 64, 2, 4, 64)
+        n = b // (64 * 256 * 4)
+        assert b == n * 64 * 256 * 4 and 2 <= n <= 8
+        per = -(-steps // n)
+        assert (n - 1) * per < steps
+
+
 def test_status_strings(lib):
     seen = set()
     for s in range(0, 8):
